@@ -1,0 +1,281 @@
+"""Plain fp64 definition of one pre-norm GQA transformer layer run over a batch
+of independent token blocks, as used by parallel context compaction.
+
+TEST INFRASTRUCTURE ONLY: imported by tests, the smoke check and the
+CPU-baseline leg of the benchmark.  It shares no code with the HIP library
+and must never be reachable from the product path.
+
+What it follows.  The method (paper Sec. IV, "Parallel Compaction") cuts the
+conversation snapshot into N contiguous blocks, hands every block to its own
+worker concurrently and concatenates the per-block results in block order.
+In the independent-chunk arrangement discussed in the same section each worker
+sees only its own block, so on the device the N workers are one ragged batch
+in which no token attends outside its block.  The paper treats the model as a
+black box (Sec. IV-A lists Llama-3.x dense and gpt-oss MoE backbones), so the
+layer itself is the textbook one: RMSNorm -> QKV -> rotary embedding -> causal
+softmax attention with grouped KV heads -> output projection + residual ->
+RMSNorm -> SwiGLU feed-forward (dense, or top-k routed experts) + residual.
+
+Everything is written as the definition: the full score matrix per (block,
+head), ordinary matrix products, a full sort for top-k.  No tiling, no online
+softmax, no fusion.  All arithmetic is float64; inputs arrive already rounded
+to the storage type of the case under test and are only widened here.
+
+Parity pins (tests/test_oracle_*.py): softmax rows sum to one; identical keys
+give the running mean of the values; a two-token case worked by hand
+(tests/golden/two_token_attention.txt); batched == one block at a time;
+prefill(L+1) == prefill(L) + one decode step; causality; rotary invariants and
+a complex-number restatement; RMSNorm scale invariance; GQA == MHA with
+duplicated KV weights; SwiGLU special cases; router brute force and the
+identical-experts == dense equivalence; and a whole-layer cross-check against
+library fp64 routines (torch CPU rms_norm / scaled_dot_product_attention /
+silu).  Conventions that no mathematics fixes -- the rotate-half pairing of
+rotary dimensions and the contiguous grouping of query heads onto KV heads --
+are pinned only to the library routines' conventions.
+"""
+import math
+
+import numpy as np
+
+F64 = np.float64
+
+
+def _f64(a):
+    return np.asarray(a, dtype=F64)
+
+
+# ---------------------------------------------------------------------------
+# elementary pieces
+# ---------------------------------------------------------------------------
+def rmsnorm(x, g, eps):
+    """n = x / sqrt(mean_d(x^2) + eps) * g, per token (last axis)."""
+    x = _f64(x)
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return x / np.sqrt(ms + eps) * _f64(g)
+
+
+def rope(x, pos, theta):
+    """Rotary embedding, rotate-half pairing.
+
+    x [T, H, hd]; pos [T] integer positions.  For i < hd/2 the pair
+    (x_i, x_{i+hd/2}) is rotated by the angle pos * theta**(-2i/hd).
+    """
+    x = _f64(x)
+    hd = x.shape[-1]
+    half = hd // 2
+    i = np.arange(half, dtype=F64)
+    freq = np.power(F64(theta), -2.0 * i / hd)
+    phi = _f64(pos)[:, None] * freq[None, :]            # [T, half]
+    c = np.cos(phi)[:, None, :]
+    s = np.sin(phi)[:, None, :]
+    lo, hi = x[..., :half], x[..., half:]
+    return np.concatenate([lo * c - hi * s, hi * c + lo * s], axis=-1)
+
+
+def softmax_rows(s):
+    """Row softmax with the row maximum subtracted; -inf entries get weight 0."""
+    m = np.max(s, axis=-1, keepdims=True)
+    e = np.exp(s - m)
+    return e / np.sum(e, axis=-1, keepdims=True)
+
+
+def attention_probs(q, k, visible):
+    """Softmax weights of R query rows over J keys for one head.
+
+    q [R, hd], k [J, hd]; visible[r] = number of leading keys row r may see
+    (key j is masked out when j >= visible[r]).  Scale 1/sqrt(hd).
+    """
+    q, k = _f64(q), _f64(k)
+    hd = q.shape[-1]
+    s = (q @ k.T) / math.sqrt(hd)                       # full [R, J] scores
+    j = np.arange(k.shape[0])[None, :]
+    s = np.where(j < np.asarray(visible)[:, None], s, -np.inf)
+    return softmax_rows(s)
+
+
+def attention_head(q, k, v, visible):
+    """o_r = sum_j a_rj v_j for one head."""
+    return attention_probs(q, k, visible) @ _f64(v)
+
+
+def gqa_attention(q, k, v, visible):
+    """q [R, Hq, hd], k/v [J, Hkv, hd] -> o [R, Hq, hd].
+
+    Query head h reads KV head h // (Hq // Hkv) (contiguous groups).
+    """
+    R, Hq, hd = q.shape
+    Hkv = k.shape[1]
+    group = Hq // Hkv
+    o = np.empty((R, Hq, hd), dtype=F64)
+    for h in range(Hq):
+        o[:, h, :] = attention_head(q[:, h, :], k[:, h // group, :],
+                                    v[:, h // group, :], visible)
+    return o
+
+
+def silu(z):
+    return z / (1.0 + np.exp(-z))
+
+
+def swiglu_ffn(m, w_gate, w_up, w_down):
+    """(silu(m Wg^T) * (m Wu^T)) Wd^T; weights are [out, in]."""
+    m = _f64(m)
+    return (silu(m @ _f64(w_gate).T) * (m @ _f64(w_up).T)) @ _f64(w_down).T
+
+
+def router_logits(m, w_router):
+    return _f64(m) @ _f64(w_router).T
+
+
+def topk_route(logits, k):
+    """Indices of the k largest logits per row (descending; equal logits ->
+    lower expert index first) and the softmax over just those k logits."""
+    logits = _f64(logits)
+    order = np.argsort(-logits, axis=-1, kind="stable")  # full sort
+    idx = order[:, :k]
+    sel = np.take_along_axis(logits, idx, axis=-1)
+    return idx.astype(np.int32), softmax_rows(sel)
+
+
+def moe_ffn(m, idx, gate, w_exp_gate_up, w_exp_down):
+    """sum_{e in idx[r]} gate[r,e] * FFN_e(m_r).  No capacity limit, no drops.
+
+    w_exp_gate_up [E, 2F, d] (rows 0..F-1 gate, F..2F-1 up), w_exp_down [E, d, F].
+    """
+    m = _f64(m)
+    F = w_exp_gate_up.shape[1] // 2
+    out = np.zeros((m.shape[0], w_exp_down.shape[1]), dtype=F64)
+    for e in np.unique(idx):
+        rows, slot = np.nonzero(idx == e)
+        y = swiglu_ffn(m[rows], w_exp_gate_up[e, :F], w_exp_gate_up[e, F:],
+                       w_exp_down[e])
+        out[rows] += gate[rows, slot][:, None] * y
+    return out
+
+
+# ---------------------------------------------------------------------------
+# the layer
+# ---------------------------------------------------------------------------
+class Layer:
+    """Weights in the layout of the library boundary, all [out, in] row-major.
+
+    cfg keys: d_model, n_q_heads, n_kv_heads, head_dim, ffn_dim, n_experts
+    (0 = dense), top_k, rms_eps, rope_theta.
+    w keys: g_attn [d], w_qkv [Dq+2Dkv, d], w_o [d, Dq], g_ffn [d], and either
+    w_gate_up [2F, d], w_down [d, F] (dense) or w_router [E, d],
+    w_exp_gate_up [E, 2F, d], w_exp_down [E, d, F] (MoE).
+    """
+
+    def __init__(self, cfg, w):
+        self.cfg = dict(cfg)
+        self.w = w
+        c = self.cfg
+        self.d = c["d_model"]
+        self.Hq, self.Hkv, self.hd = c["n_q_heads"], c["n_kv_heads"], c["head_dim"]
+        self.Dq, self.Dkv = self.Hq * self.hd, self.Hkv * self.hd
+        self.F = c["ffn_dim"]
+        self.E = c.get("n_experts", 0)
+        self.k = c.get("top_k", 0)
+        self.eps = c["rms_eps"]
+        self.theta = c["rope_theta"]
+
+    # -- attention half -----------------------------------------------------
+    def qkv(self, x, pos):
+        """RMSNorm, QKV projection and rotary embedding for the rows of x."""
+        n = rmsnorm(x, self.w["g_attn"], self.eps)
+        p = n @ _f64(self.w["w_qkv"]).T
+        T = p.shape[0]
+        q = p[:, :self.Dq].reshape(T, self.Hq, self.hd)
+        k = p[:, self.Dq:self.Dq + self.Dkv].reshape(T, self.Hkv, self.hd)
+        v = p[:, self.Dq + self.Dkv:].reshape(T, self.Hkv, self.hd)
+        return rope(q, pos, self.theta), rope(k, pos, self.theta), v
+
+    # -- feed-forward half --------------------------------------------------
+    def ffn(self, h):
+        """Second RMSNorm, feed-forward, residual.  Returns (y, idx, gate)."""
+        m = rmsnorm(h, self.w["g_ffn"], self.eps)
+        if self.E == 0:
+            F = self.F
+            wgu = self.w["w_gate_up"]
+            return h + swiglu_ffn(m, wgu[:F], wgu[F:], self.w["w_down"]), None, None
+        idx, gate = topk_route(router_logits(m, self.w["w_router"]), self.k)
+        y = h + moe_ffn(m, idx, gate, self.w["w_exp_gate_up"], self.w["w_exp_down"])
+        return y, idx, gate
+
+    # -- one block ----------------------------------------------------------
+    def prefill_block(self, x, pos0=0, rows=None):
+        """Causal forward over one block's own L tokens.
+
+        x [L, d].  Positions are pos0 .. pos0+L-1.  K and V are produced for
+        every token; attention and everything after it are evaluated for the
+        query rows in `rows` (default: all).  Returns dict with y [R, d],
+        K, V [L, Hkv, hd] (K after rotation), rows, idx, gate.
+        """
+        x = _f64(x)
+        L = x.shape[0]
+        pos = pos0 + np.arange(L)
+        q, k, v = self.qkv(x, pos)
+        rows = np.arange(L) if rows is None else np.asarray(rows, dtype=np.int64)
+        o = gqa_attention(q[rows], k, v, visible=rows + 1)     # row i sees j <= i
+        h = x[rows] + o.reshape(len(rows), self.Dq) @ _f64(self.w["w_o"]).T
+        y, idx, gate = self.ffn(h)
+        return dict(y=y, K=k, V=v, rows=rows, idx=idx, gate=gate)
+
+    def decode_block(self, x, K, V, pos0=0):
+        """One new token for one block whose cache holds len = K.shape[0] rows.
+
+        The token sits at position pos0 + len, its K/V row is appended, and it
+        attends rows 0..len inclusive.  Returns dict with y [d], K, V grown by
+        one row, idx, gate.
+        """
+        x = _f64(x).reshape(1, self.d)
+        n_cached = K.shape[0]
+        q, k, v = self.qkv(x, np.array([pos0 + n_cached]))
+        K = np.concatenate([K, k], axis=0)
+        V = np.concatenate([V, v], axis=0)
+        o = gqa_attention(q, K, V, visible=np.array([n_cached + 1]))
+        h = x + o.reshape(1, self.Dq) @ _f64(self.w["w_o"]).T
+        y, idx, gate = self.ffn(h)
+        return dict(y=y[0], K=K, V=V,
+                    idx=None if idx is None else idx[0],
+                    gate=None if gate is None else gate[0])
+
+    # -- the batch of blocks ------------------------------------------------
+    def prefill(self, x, cu_seqlens, pos_offset=None, rows=None):
+        """Block b = rows cu[b]..cu[b+1]-1 of the packed x [T, d]; blocks are
+        independent.  rows: optional list (per block) of block-local query rows.
+        Returns one prefill_block dict per block, in block order."""
+        out = []
+        for b in range(len(cu_seqlens) - 1):
+            xb = x[cu_seqlens[b]:cu_seqlens[b + 1]]
+            out.append(self.prefill_block(
+                xb, 0 if pos_offset is None else int(pos_offset[b]),
+                None if rows is None else rows[b]))
+        return out
+
+    def decode_step(self, x, Ks, Vs, pos_offset=None):
+        """x [N, d]: one token per block, each against its own cache."""
+        out = []
+        for b in range(len(Ks)):
+            out.append(self.decode_block(
+                x[b], Ks[b], Vs[b], 0 if pos_offset is None else int(pos_offset[b])))
+        return out
+
+    def forward(self, x_prefill, cu_seqlens, x_decode, pos_offset=None, rows=None):
+        """Prefill of every block, then S batched decode steps with the given
+        step inputs x_decode [S, N, d].  Returns (prefill dicts, y_decode
+        [S, N, d], final K list, final V list, decode routing list)."""
+        pre = self.prefill(x_prefill, cu_seqlens, pos_offset, rows)
+        Ks = [p["K"] for p in pre]
+        Vs = [p["V"] for p in pre]
+        S = 0 if x_decode is None else x_decode.shape[0]
+        N = len(Ks)
+        y_dec = np.zeros((S, N, self.d), dtype=F64)
+        routes = []
+        for s in range(S):
+            st = self.decode_step(x_decode[s], Ks, Vs, pos_offset)
+            for b in range(N):
+                y_dec[s, b] = st[b]["y"]
+                Ks[b], Vs[b] = st[b]["K"], st[b]["V"]
+            routes.append([(st[b]["idx"], st[b]["gate"]) for b in range(N)])
+        return pre, y_dec, Ks, Vs, routes

@@ -1,0 +1,372 @@
+"""Pins for the fp64 checker: invariants, closed forms, a hand-worked case and
+library special cases.  Each is chosen so that a plausible mistake in
+oracle/layer.py (dropped term, wrong sign or index, transposed operand, wrong
+mask edge) fails at least one of them.  CPU only."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import layer as O
+from tests.util import read_golden
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def small_cfg(**kw):
+    cfg = dict(d_model=32, n_q_heads=4, n_kv_heads=2, head_dim=8, ffn_dim=48,
+               n_experts=0, top_k=0, rms_eps=1e-5, rope_theta=10000.0)
+    cfg.update(kw)
+    return cfg
+
+
+def small_weights(cfg, rng, std=0.2):
+    d, F = cfg["d_model"], cfg["ffn_dim"]
+    Dq = cfg["n_q_heads"] * cfg["head_dim"]
+    Dkv = cfg["n_kv_heads"] * cfg["head_dim"]
+    w = dict(g_attn=1 + 0.1 * rng.standard_normal(d), g_ffn=1 + 0.1 * rng.standard_normal(d),
+             w_qkv=std * rng.standard_normal((Dq + 2 * Dkv, d)),
+             w_o=std * rng.standard_normal((d, Dq)))
+    if cfg["n_experts"] == 0:
+        w["w_gate_up"] = std * rng.standard_normal((2 * F, d))
+        w["w_down"] = std * rng.standard_normal((d, F))
+    else:
+        E = cfg["n_experts"]
+        w["w_router"] = std * rng.standard_normal((E, d))
+        w["w_exp_gate_up"] = std * rng.standard_normal((E, 2 * F, d))
+        w["w_exp_down"] = std * rng.standard_normal((E, d, F))
+    return w
+
+
+# ---------------------------------------------------------------- softmax / attention core
+def test_softmax_rows_sum_to_one_and_nonnegative(rng):
+    q = rng.standard_normal((9, 16)) * 3
+    k = rng.standard_normal((9, 16)) * 3
+    p = O.attention_probs(q, k, visible=np.arange(9) + 1)
+    assert np.all(p >= 0)
+    np.testing.assert_allclose(p.sum(-1), 1.0, atol=1e-14)
+    # masked entries are exactly zero: strictly upper triangle
+    assert np.all(np.triu(p, 1) == 0)
+    # the diagonal is visible (inclusive causal mask)
+    assert np.all(np.diag(p) > 0)
+
+
+def test_identical_keys_give_running_mean_of_values(rng):
+    L, hd = 7, 8
+    q = rng.standard_normal((L, hd))
+    k = np.tile(rng.standard_normal((1, hd)), (L, 1))
+    v = rng.standard_normal((L, hd))
+    o = O.attention_head(q, k, v, visible=np.arange(L) + 1)
+    want = np.cumsum(v, axis=0) / (np.arange(L) + 1)[:, None]
+    np.testing.assert_allclose(o, want, atol=1e-14)
+
+
+def test_zero_query_gives_running_mean_through_whole_layer_attention(rng):
+    # q = 0 so the rotary embedding cannot break the tie between keys
+    L, hd = 5, 8
+    q = np.zeros((L, 2, hd))
+    k = rng.standard_normal((L, 1, hd))
+    v = rng.standard_normal((L, 1, hd))
+    o = O.gqa_attention(q, k, v, visible=np.arange(L) + 1)
+    want = np.cumsum(v[:, 0], axis=0) / (np.arange(L) + 1)[:, None]
+    np.testing.assert_allclose(o[:, 0], want, atol=1e-14)
+    np.testing.assert_allclose(o[:, 1], want, atol=1e-14)
+
+
+def test_two_token_case_worked_by_hand():
+    g = read_golden(os.path.join(HERE, "golden", "two_token_attention.txt"))
+    q = np.stack([g["q0"], g["q1"]])
+    k = np.stack([g["k0"], g["k1"]])
+    v = np.stack([g["v0"], g["v1"]])
+    p = O.attention_probs(q, k, visible=[1, 2])
+    np.testing.assert_allclose(p[0], [1.0, 0.0], atol=1e-15)
+    np.testing.assert_allclose(p[1], g["p1"], atol=1e-15)
+    o = O.attention_head(q, k, v, visible=[1, 2])
+    np.testing.assert_allclose(o[0], g["o0"], atol=1e-14)
+    np.testing.assert_allclose(o[1], g["o1"], atol=1e-14)
+    # and with the rotary embedding applied at positions 0, 1 first
+    qr = O.rope(q[:, None, :], np.array([0, 1]), 10000.0)[:, 0]
+    kr = O.rope(k[:, None, :], np.array([0, 1]), 10000.0)[:, 0]
+    o = O.attention_head(qr, kr, v, visible=[1, 2])
+    np.testing.assert_allclose(o[1], g["o1"], atol=1e-14)
+
+
+def test_scale_is_one_over_sqrt_head_dim():
+    # a single query against two keys; closed form of the weight ratio
+    hd = 16
+    q = np.ones((1, hd))
+    k = np.stack([np.zeros(hd), np.full(hd, 0.5)])
+    p = O.attention_probs(q, k, visible=[2])
+    # score difference = hd*0.5/sqrt(hd) = 0.5*sqrt(hd) = 2
+    np.testing.assert_allclose(p[0, 1] / p[0, 0], math.exp(2.0), rtol=1e-13)
+
+
+def test_attention_core_equals_library_sdpa(rng):
+    L, Hq, Hkv, hd = 11, 4, 2, 8
+    q = rng.standard_normal((L, Hq, hd))
+    k = rng.standard_normal((L, Hkv, hd))
+    v = rng.standard_normal((L, Hkv, hd))
+    o = O.gqa_attention(q, k, v, visible=np.arange(L) + 1)
+    tq, tk, tv = (torch.from_numpy(a).permute(1, 0, 2)[None] for a in (q, k, v))
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        tq, tk, tv, is_causal=True, enable_gqa=True)[0].permute(1, 0, 2).numpy()
+    np.testing.assert_allclose(o, ref, atol=1e-12)
+
+
+# ---------------------------------------------------------------- rotary embedding
+def test_rope_identity_at_position_zero_and_norm_preserving(rng):
+    x = rng.standard_normal((6, 3, 16))
+    np.testing.assert_array_equal(O.rope(x, np.zeros(6, dtype=int), 5e5), x)
+    r = O.rope(x, np.arange(6) * 37, 5e5)
+    np.testing.assert_allclose(np.linalg.norm(r, axis=-1), np.linalg.norm(x, axis=-1), rtol=1e-13)
+
+
+def test_rope_inner_product_depends_only_on_relative_position(rng):
+    q = rng.standard_normal((1, 1, 16))
+    k = rng.standard_normal((1, 1, 16))
+
+    def dot(m, n):
+        return float(np.sum(O.rope(q, np.array([m]), 1e4) * O.rope(k, np.array([n]), 1e4)))
+
+    assert abs(dot(5, 2) - dot(103, 100)) < 1e-12
+    assert abs(dot(5, 2) - dot(2, 5)) > 1e-3        # sign of the rotation matters
+
+
+def test_rope_equals_complex_multiplication(rng):
+    # pair (x_i, x_{i+hd/2}) read as the complex number x_i + 1j x_{i+hd/2},
+    # multiplied by exp(1j * pos * theta^(-2i/hd))
+    T, H, hd, theta = 5, 2, 8, 500000.0
+    x = rng.standard_normal((T, H, hd))
+    pos = np.array([0, 1, 7, 100, 4095])
+    z = x[..., :hd // 2] + 1j * x[..., hd // 2:]
+    ang = pos[:, None] * theta ** (-np.arange(hd // 2) / (hd // 2))
+    z = z * np.exp(1j * ang)[:, None, :]
+    want = np.concatenate([z.real, z.imag], axis=-1)
+    np.testing.assert_allclose(O.rope(x, pos, theta), want, atol=1e-12)
+
+
+def test_rope_first_pair_rotates_by_position_radians():
+    # frequency of pair 0 is theta^0 = 1: position 1 rotates (1, 0) to (cos 1, sin 1)
+    x = np.zeros((1, 1, 4))
+    x[0, 0, 0] = 1.0
+    r = O.rope(x, np.array([1]), 10000.0)
+    np.testing.assert_allclose(r[0, 0], [math.cos(1.0), 0.0, math.sin(1.0), 0.0], atol=1e-15)
+    # pair 1 of hd=4 has frequency theta^(-1/2)
+    x = np.zeros((1, 1, 4))
+    x[0, 0, 1] = 1.0
+    r = O.rope(x, np.array([3]), 10000.0)
+    np.testing.assert_allclose(r[0, 0], [0.0, math.cos(0.03), 0.0, math.sin(0.03)], atol=1e-15)
+
+
+# ---------------------------------------------------------------- RMSNorm
+def test_rmsnorm_unit_rms_scale_invariance_and_library(rng):
+    x = rng.standard_normal((4, 64)) * 5
+    n = O.rmsnorm(x, np.ones(64), 0.0)
+    np.testing.assert_allclose(np.sqrt(np.mean(n * n, -1)), 1.0, rtol=1e-13)
+    np.testing.assert_allclose(O.rmsnorm(3.7 * x, np.ones(64), 0.0), n, rtol=1e-13)
+    g = 1 + 0.1 * rng.standard_normal(64)
+    ref = torch.nn.functional.rms_norm(torch.from_numpy(x), (64,), torch.from_numpy(g), 1e-5).numpy()
+    np.testing.assert_allclose(O.rmsnorm(x, g, 1e-5), ref, rtol=1e-13)
+    # eps sits inside the square root, added to the mean square
+    one = O.rmsnorm(np.array([[2.0, 2.0]]), np.ones(2), 5.0)
+    np.testing.assert_allclose(one, [[2 / 3.0, 2 / 3.0]], rtol=1e-15)
+
+
+# ---------------------------------------------------------------- SwiGLU
+def test_silu_and_swiglu_special_cases(rng):
+    assert O.silu(np.array(0.0)) == 0.0
+    np.testing.assert_allclose(O.silu(np.array(40.0)), 40.0, rtol=1e-15)
+    np.testing.assert_allclose(O.silu(np.array(1.0)), 1 / (1 + math.exp(-1.0)), rtol=1e-15)
+    m = rng.standard_normal((3, 8))
+    wu = rng.standard_normal((12, 8))
+    wd = rng.standard_normal((8, 12))
+    assert np.all(O.swiglu_ffn(m, np.zeros((12, 8)), wu, wd) == 0)
+    wg = rng.standard_normal((12, 8))
+    ref = torch.nn.functional.linear(
+        torch.nn.functional.silu(torch.from_numpy(m @ wg.T)) * torch.from_numpy(m @ wu.T),
+        torch.from_numpy(wd)).numpy()
+    np.testing.assert_allclose(O.swiglu_ffn(m, wg, wu, wd), ref, rtol=1e-12, atol=1e-12)
+    # gate and up are not interchangeable: silu is applied to the gate only
+    assert np.max(np.abs(O.swiglu_ffn(m, wu, wg, wd) - ref)) > 1e-3
+
+
+# ---------------------------------------------------------------- router / MoE
+def test_topk_route_is_brute_force_argsort_with_ties_to_lower_index(rng):
+    logits = rng.standard_normal((50, 16))
+    logits[3, 5] = logits[3, 9] = 10.0         # exact tie at the top
+    logits[4, :] = 0.0                         # all equal
+    idx, gate = O.topk_route(logits, 4)
+    for r in range(50):
+        brute = sorted(range(16), key=lambda e: (-logits[r, e], e))[:4]
+        assert list(idx[r]) == brute
+    assert list(idx[3][:2]) == [5, 9]
+    assert list(idx[4]) == [0, 1, 2, 3]
+    np.testing.assert_allclose(gate.sum(-1), 1.0, atol=1e-14)
+    # gate = softmax over the selected logits only
+    r = 7
+    e = np.exp(logits[r, idx[r]])
+    np.testing.assert_allclose(gate[r], e / e.sum(), rtol=1e-13)
+    # equivalently: softmax over all experts, renormalised over the top-k
+    full = np.exp(logits[r]) / np.exp(logits[r]).sum()
+    np.testing.assert_allclose(gate[r], full[idx[r]] / full[idx[r]].sum(), rtol=1e-12)
+
+
+def test_moe_with_identical_experts_equals_dense(rng):
+    cfg = small_cfg(n_experts=6, top_k=3)
+    w = small_weights(cfg, rng)
+    w["w_exp_gate_up"][:] = w["w_exp_gate_up"][0]
+    w["w_exp_down"][:] = w["w_exp_down"][0]
+    dense_cfg = small_cfg()
+    wd = {k: v for k, v in w.items() if not k.startswith("w_exp") and k != "w_router"}
+    wd["w_gate_up"] = w["w_exp_gate_up"][0]
+    wd["w_down"] = w["w_exp_down"][0]
+    x = rng.standard_normal((9, cfg["d_model"]))
+    y_moe = O.Layer(cfg, w).prefill_block(x)["y"]
+    y_dense = O.Layer(dense_cfg, wd).prefill_block(x)["y"]
+    np.testing.assert_allclose(y_moe, y_dense, atol=1e-12)
+
+
+def test_moe_one_hot_router_and_expert_permutation(rng):
+    cfg = small_cfg(n_experts=5, top_k=2)
+    w = small_weights(cfg, rng)
+    m = rng.standard_normal((4, cfg["d_model"]))
+    idx, gate = O.topk_route(O.router_logits(m, w["w_router"]), 2)
+    out = O.moe_ffn(m, idx, gate, w["w_exp_gate_up"], w["w_exp_down"])
+    F = cfg["ffn_dim"]
+    # definition, token by token
+    for r in range(4):
+        want = sum(gate[r, s] * O.swiglu_ffn(m[r:r + 1], w["w_exp_gate_up"][e, :F],
+                                             w["w_exp_gate_up"][e, F:], w["w_exp_down"][e])[0]
+                   for s, e in enumerate(idx[r]))
+        np.testing.assert_allclose(out[r], want, atol=1e-12)
+    # rows over experts account for k rows per token
+    assert sum(int(np.sum(idx == e)) for e in range(5)) == 2 * 4
+    # permuting the experts permutes the indices only
+    perm = np.array([3, 0, 4, 1, 2])          # new expert j is old expert perm[j]
+    idx2, gate2 = O.topk_route(O.router_logits(m, w["w_router"][perm]), 2)
+    np.testing.assert_array_equal(perm[idx2], idx)
+    out2 = O.moe_ffn(m, idx2, gate2, w["w_exp_gate_up"][perm], w["w_exp_down"][perm])
+    np.testing.assert_allclose(out2, out, atol=1e-12)
+    # a router row that dominates picks its expert first
+    wr = np.zeros_like(w["w_router"])
+    wr[2] = 50 * m[0] / np.dot(m[0], m[0])
+    idx3, gate3 = O.topk_route(O.router_logits(m[:1], wr), 2)
+    assert idx3[0, 0] == 2 and gate3[0, 0] > 0.999
+
+
+# ---------------------------------------------------------------- whole layer
+@pytest.mark.parametrize("moe", [False, True])
+def test_batched_equals_one_block_at_a_time(rng, moe):
+    """The method's central equivalence (Sec. IV: per-block results are produced
+    independently and concatenated in block order)."""
+    cfg = small_cfg(n_experts=4, top_k=2) if moe else small_cfg()
+    lay = O.Layer(cfg, small_weights(cfg, rng))
+    lens = [5, 1, 9, 3]
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    x = rng.standard_normal((cu[-1], cfg["d_model"]))
+    xd = rng.standard_normal((3, len(lens), cfg["d_model"]))
+    pre, yd, Ks, Vs, _ = lay.forward(x, cu, xd)
+    for b, L in enumerate(lens):
+        pre1, yd1, K1, V1, _ = lay.forward(x[cu[b]:cu[b + 1]], [0, L], xd[:, b:b + 1])
+        assert np.array_equal(pre[b]["y"], pre1[0]["y"])
+        assert np.array_equal(yd[:, b], yd1[:, 0])
+        assert np.array_equal(Ks[b], K1[0]) and np.array_equal(Vs[b], V1[0])
+        assert Ks[b].shape[0] == L + 3
+    # and a block's result changes if its own tokens change (the test is not vacuous)
+    x2 = x.copy()
+    x2[cu[2]] += 1.0
+    pre2 = lay.prefill(x2, cu)
+    assert not np.array_equal(pre2[2]["y"], pre[2]["y"])
+    for b in (0, 1, 3):
+        assert np.array_equal(pre2[b]["y"], pre[b]["y"])
+
+
+def test_prefill_then_decode_equals_longer_prefill(rng):
+    cfg = small_cfg()
+    lay = O.Layer(cfg, small_weights(cfg, rng))
+    L = 6
+    x = rng.standard_normal((L + 2, cfg["d_model"]))
+    full = lay.prefill_block(x, pos0=3)
+    part = lay.prefill_block(x[:L], pos0=3)
+    s1 = lay.decode_block(x[L], part["K"], part["V"], pos0=3)
+    s2 = lay.decode_block(x[L + 1], s1["K"], s1["V"], pos0=3)
+    np.testing.assert_allclose(s1["y"], full["y"][L], atol=1e-12)
+    np.testing.assert_allclose(s2["y"], full["y"][L + 1], atol=1e-12)
+    np.testing.assert_allclose(s2["K"], full["K"], atol=1e-13)
+    np.testing.assert_allclose(s2["V"], full["V"], atol=1e-13)
+
+
+def test_causality(rng):
+    cfg = small_cfg()
+    lay = O.Layer(cfg, small_weights(cfg, rng))
+    x = rng.standard_normal((8, cfg["d_model"]))
+    y = lay.prefill_block(x)["y"]
+    x2 = x.copy()
+    x2[5] += 1.0
+    y2 = lay.prefill_block(x2)["y"]
+    assert np.array_equal(y2[:5], y[:5])
+    assert np.all(np.max(np.abs(y2[5:] - y[5:]), axis=-1) > 1e-6)
+
+
+def test_row_subset_equals_full(rng):
+    cfg = small_cfg()
+    lay = O.Layer(cfg, small_weights(cfg, rng))
+    x = rng.standard_normal((10, cfg["d_model"]))
+    full = lay.prefill_block(x)
+    sub = lay.prefill_block(x, rows=[0, 4, 9])
+    np.testing.assert_allclose(sub["y"], full["y"][[0, 4, 9]], atol=1e-13)
+    assert np.array_equal(sub["K"], full["K"])
+
+
+def test_gqa_equals_mha_with_duplicated_kv_weights(rng):
+    cfg = small_cfg()                                   # 4 q heads on 2 kv heads
+    w = small_weights(cfg, rng)
+    hd, Dq, Dkv = cfg["head_dim"], 32, 16
+    mha = small_cfg(n_kv_heads=4)
+    w2 = dict(w)
+    wq, wk, wv = w["w_qkv"][:Dq], w["w_qkv"][Dq:Dq + Dkv], w["w_qkv"][Dq + Dkv:]
+    dup = lambda m: np.repeat(m.reshape(2, hd, -1), 2, axis=0).reshape(4 * hd, -1)
+    w2["w_qkv"] = np.concatenate([wq, dup(wk), dup(wv)])
+    x = rng.standard_normal((7, cfg["d_model"]))
+    np.testing.assert_allclose(O.Layer(cfg, w).prefill_block(x)["y"],
+                               O.Layer(mha, w2).prefill_block(x)["y"], atol=1e-12)
+
+
+@pytest.mark.parametrize("theta", [10000.0, 500000.0])
+def test_whole_layer_against_library_routines(rng, theta):
+    """Independent composition of the same layer from torch fp64 CPU routines
+    (rms_norm, linear, scaled_dot_product_attention with grouped KV, silu); the
+    rotary step is restated with complex numbers.  Pins the residual structure,
+    the order of the two norms, the QKV row split and the head grouping."""
+    cfg = small_cfg(rope_theta=theta)
+    w = small_weights(cfg, rng)
+    L, d, Hq, Hkv, hd, F = 9, 32, 4, 2, 8, 48
+    x = rng.standard_normal((L, d))
+    got = O.Layer(cfg, w).prefill_block(x, pos0=2)["y"]
+
+    tw = {k: torch.from_numpy(np.asarray(v)) for k, v in w.items()}
+    tx = torch.from_numpy(x)
+    TF = torch.nn.functional
+    n = TF.rms_norm(tx, (d,), tw["g_attn"], 1e-5)
+    qkv = TF.linear(n, tw["w_qkv"])
+    q, k, v = qkv.split([Hq * hd, Hkv * hd, Hkv * hd], dim=-1)
+
+    def rot(t, H):
+        t = t.reshape(L, H, hd)
+        z = torch.complex(t[..., :hd // 2], t[..., hd // 2:])
+        ang = (torch.arange(L, dtype=torch.float64) + 2)[:, None] * \
+            theta ** (-torch.arange(hd // 2, dtype=torch.float64) / (hd // 2))
+        z = z * torch.polar(torch.ones_like(ang), ang)[:, None, :]
+        return torch.cat([z.real, z.imag], -1)
+
+    q, k, v = rot(q, Hq), rot(k, Hkv), v.reshape(L, Hkv, hd)
+    o = TF.scaled_dot_product_attention(q.permute(1, 0, 2)[None], k.permute(1, 0, 2)[None],
+                                        v.permute(1, 0, 2)[None], is_causal=True, enable_gqa=True)
+    o = o[0].permute(1, 0, 2).reshape(L, Hq * hd)
+    h = tx + TF.linear(o, tw["w_o"])
+    m = TF.rms_norm(h, (d,), tw["g_ffn"], 1e-5)
+    gu = TF.linear(m, tw["w_gate_up"])
+    y = h + TF.linear(TF.silu(gu[:, :F]) * gu[:, F:], tw["w_down"])
+    np.testing.assert_allclose(got, y.numpy(), atol=1e-11)
