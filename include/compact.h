@@ -1,0 +1,217 @@
+/*
+ * compact.h -- C ABI of libcompact: one transformer layer's forward over a
+ * batch of independent token blocks, for parallel context compaction.
+ *
+ * The method (paper Sec. IV, "Parallel Compaction"): when a conversation
+ * exceeds the compaction threshold it is snapshotted, cut into
+ * N = ceil(|X| / B) contiguous blocks, every block is summarised by its own
+ * worker concurrently, and the N per-block results are concatenated in block
+ * order.  On the device the N concurrent workers are one ragged batch: a
+ * varlen causal prefill in which no token attends outside its own block,
+ * followed by batched single-token decode steps, each block against its own
+ * KV cache.  The calls below take "N blocks with token spans" in and give
+ * "per-block hidden states and KV caches" out, in block order.
+ *
+ * Conventions
+ *  - All d_* pointers are DEVICE pointers, all h_* pointers are HOST pointers.
+ *    Every buffer is owned by the caller and only borrowed for the call; the
+ *    library owns nothing but the context and a small device metadata buffer.
+ *  - Host arrays are read (and h_len written) before the call returns.
+ *  - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL =
+ *    the default stream) and the call returns without synchronising.
+ *  - Activations and weights are row-major, dtype per cfg.dtype (fp32 or
+ *    bf16).  Weights are [out, in], so both GEMM operands are contiguous
+ *    along the contraction.
+ *  - Return value 0 = COMPACT_OK, otherwise one of the COMPACT_E* codes;
+ *    compact_last_error() gives a readable detail.  All argument validation
+ *    happens before the first HIP call.
+ *  - Results are deterministic run to run, and a block's results do not
+ *    depend on which other blocks share the call (no work split is chosen
+ *    from the batch).
+ */
+#ifndef COMPACT_H
+#define COMPACT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    COMPACT_OK = 0,
+    COMPACT_EINVAL = 1,       /* null pointer, non-positive size, empty block, cu_seqlens not increasing */
+    COMPACT_ESHAPE = 2,       /* layer shape violates a kernel constraint */
+    COMPACT_ECAPACITY = 3,    /* a block (or len+1) exceeds its KV slab capacity */
+    COMPACT_EWORKSPACE = 4,   /* workspace missing or too small */
+    COMPACT_EUNSUPPORTED = 5, /* dtype / feature not built */
+    COMPACT_EHIP = 6          /* HIP runtime failure (allocation, launch) */
+};
+
+enum { COMPACT_FP32 = 0, COMPACT_BF16 = 1 };
+
+/* Layer shape.  Pre-norm, two residual branches, no biases:
+ *   n = RMSNorm(x; g_attn); [q,k,v] = n W_qkv^T; rotary(q,k); o = causal GQA attention;
+ *   h = x + o W_o^T; m = RMSNorm(h; g_ffn);
+ *   dense: y = h + (silu(m W_g^T) * (m W_u^T)) W_d^T
+ *   MoE:   l = m W_r^T (fp32); I = top_k(l) (descending, ties to the lower index);
+ *          w = softmax(l_I); y = h + sum_{e in I} w_e FFN_e(m)   (no capacity limit)
+ * Rotary pairing is rotate-half: (x_i, x_{i+hd/2}) turned by pos * theta^(-2i/hd).
+ * Query head h reads KV head h / (n_q_heads / n_kv_heads).
+ * Constraints: head_dim in {64, 128}; n_q_heads % n_kv_heads == 0 with a
+ * group of at most 16; d_model, ffn_dim multiples of 64; top_k <= 8;
+ * n_experts <= 256.                                                        */
+typedef struct compact_layer_cfg {
+    int32_t d_model;
+    int32_t n_q_heads;
+    int32_t n_kv_heads;
+    int32_t head_dim;
+    int32_t ffn_dim;      /* F: width of the SwiGLU hidden layer (per expert for MoE) */
+    int32_t n_experts;    /* 0 = dense */
+    int32_t top_k;        /* experts per token (MoE only) */
+    float   rms_eps;
+    float   rope_theta;
+    int32_t dtype;        /* COMPACT_FP32 or COMPACT_BF16: storage type of activations, weights, KV */
+} compact_layer_cfg;
+
+/* Device pointers to the layer's weights, dtype per cfg. Unused ones may be NULL. */
+typedef struct compact_weights {
+    const void* g_attn;         /* [d]                                   */
+    const void* w_qkv;          /* [Dq + 2 Dkv, d]: q rows, then k, then v */
+    const void* w_o;            /* [d, Dq]                               */
+    const void* g_ffn;          /* [d]                                   */
+    const void* w_gate_up;      /* dense: [2F, d], rows 0..F-1 gate, F..2F-1 up */
+    const void* w_down;         /* dense: [d, F]                         */
+    const void* w_router;       /* MoE: [E, d]                           */
+    const void* w_exp_gate_up;  /* MoE: [E, 2F, d]                       */
+    const void* w_exp_down;     /* MoE: [E, d, F]                        */
+} compact_weights;
+
+/* Per-block KV caches.  Block b owns one K slab and one V slab, both starting
+ * h_slab_offset[b] ELEMENTS into d_k / d_v and holding Hkv*capacity*hd elements:
+ *   K slab: [Hkv][capacity_b][hd]   (row = cached token, after rotary embedding)
+ *   V slab: [Hkv][hd][capacity_b]   (transposed: cached tokens contiguous)
+ * h_capacity[b] and h_slab_offset[b] must be multiples of 8.  h_len[b] is the
+ * number of cached tokens: written by compact_prefill, read and incremented by
+ * compact_decode_step.  h_pos_offset[b] (NULL => 0) is added to the block-local
+ * index to get the rotary position.                                         */
+typedef struct compact_kv {
+    void*          d_k;
+    void*          d_v;
+    const int64_t* h_slab_offset;   /* [N] */
+    const int32_t* h_capacity;      /* [N] */
+    int32_t*       h_len;           /* [N] in/out */
+    const int32_t* h_pos_offset;    /* [N] or NULL */
+} compact_kv;
+
+/* Optional MoE routing outputs (all nullable): the k expert ids per token in
+ * selection order and their gate weights.                                   */
+typedef struct compact_route_out {
+    int32_t* d_expert_idx;   /* [rows, top_k] */
+    float*   d_gate;         /* [rows, top_k] */
+} compact_route_out;
+
+typedef struct compact_ctx compact_ctx;
+
+/* Validates cfg and creates a context.  No HIP call is made here. */
+int compact_create(const compact_layer_cfg* cfg, compact_ctx** out);
+/* Frees the context and the library's metadata buffer; never caller buffers. */
+void compact_destroy(compact_ctx* ctx);
+/* Detail of the last non-zero return on this context ("" if none). ctx may be
+ * NULL, which gives the detail of the last failed compact_create.            */
+const char* compact_last_error(const compact_ctx* ctx);
+
+/* Bytes of device workspace needed by any call with at most max_tokens packed
+ * prefill tokens, max_blocks blocks and max_kv_len cached tokens per block.
+ * The caller allocates it once and passes it to every call.                 */
+int compact_workspace_bytes(const compact_ctx* ctx, int64_t max_tokens, int32_t max_blocks,
+                            int32_t max_kv_len, size_t* bytes);
+
+/* Prefill: the layer's forward over N ragged blocks (paper Sec. IV phases 1-2:
+ * the N blocks of the partitioned snapshot, dispatched together).  Block b is
+ * rows h_cu_seqlens[b] .. h_cu_seqlens[b+1]-1 of d_x [T, d]; attention is
+ * causal within a block and never crosses blocks.  Writes d_y [T, d], rows
+ * 0..L_b-1 of block b's K and V slabs, and h_len[b] = L_b.  L_b >= 1.
+ * route (nullable) receives [T, top_k] routing tables for MoE layers.       */
+int compact_prefill(compact_ctx* ctx, const compact_weights* w, int32_t n_blocks,
+                    const int32_t* h_cu_seqlens, const void* d_x, compact_kv* kv, void* d_y,
+                    const compact_route_out* route, void* d_workspace, size_t ws_bytes,
+                    void* hip_stream);
+
+/* One batched decode step (the concurrent workers each emitting one summary
+ * token): d_x [N, d] holds one new token per block, at rotary position
+ * pos_offset[b] + len[b].  Its K/V row is appended at row len[b], it attends
+ * rows 0..len[b] inclusive, and h_len[b] is incremented.  Writes d_y [N, d]. */
+int compact_decode_step(compact_ctx* ctx, const compact_weights* w, int32_t n_blocks,
+                        const void* d_x, compact_kv* kv, void* d_y,
+                        const compact_route_out* route, void* d_workspace, size_t ws_bytes,
+                        void* hip_stream);
+
+/* The whole compaction pass for one layer (paper Sec. IV phases 2-3): prefill
+ * of all blocks, then n_steps batched decode steps with caller-supplied step
+ * inputs d_x_decode [S, N, d] (no LM head or sampling at layer level).
+ * d_y_prefill [T, d] and d_y_last [N, d] (last prefill row of each block) are
+ * nullable; d_y_decode [S, N, d] holds the per-block outputs of every step in
+ * block order (the merge is the identity on this layout).  h_len ends at
+ * L_b + n_steps.                                                            */
+int compact_layer_forward(compact_ctx* ctx, const compact_weights* w, int32_t n_blocks,
+                          const int32_t* h_cu_seqlens, const void* d_x_prefill, int32_t n_steps,
+                          const void* d_x_decode, compact_kv* kv, void* d_y_prefill,
+                          void* d_y_last, void* d_y_decode, void* d_workspace, size_t ws_bytes,
+                          void* hip_stream);
+
+/* ---- per-kernel timing ----------------------------------------------------
+ * When enabled, every launch of the selected kernel class is bracketed by HIP
+ * events on the launch stream.  compact_profile_read synchronises those
+ * events and returns the number of launches and their summed duration since
+ * the last reset.  Classes: see COMPACT_K_*.                                */
+enum {
+    COMPACT_K_NONE = 0,
+    COMPACT_K_GEMM = 1,          /* bf16 MFMA GEMM (prefill projections, expert GEMMs) */
+    COMPACT_K_ATTN_PREFILL = 2,  /* varlen causal flash prefill attention */
+    COMPACT_K_ATTN_DECODE = 3,   /* split-KV decode attention (streaming part) */
+    COMPACT_K_GEMM_SKINNY = 4,   /* weight-streaming decode projections */
+    COMPACT_K_COUNT = 5
+};
+int compact_profile_select(compact_ctx* ctx, int32_t kernel_class);
+int compact_profile_read(compact_ctx* ctx, int64_t* n_launches, double* total_ms);
+
+/* ---- per-kernel entry points (used by the parity tests; same kernels as the
+ * layer calls launch).  All pointers are device pointers unless named h_*. -- */
+
+/* y[r] = x[r] / sqrt(mean(x[r]^2) + eps) * g, rows x d. */
+int compact_rmsnorm(compact_ctx* ctx, const void* d_x, const void* d_g, void* d_y, int64_t rows,
+                    void* hip_stream);
+/* Rotary embedding of q and k in a packed qkv [T, Dq+2Dkv] buffer (q rotated
+ * in place) and scatter of k (rotated) and v into the block slabs.          */
+int compact_rope_kvwrite(compact_ctx* ctx, int32_t n_blocks, const int32_t* h_cu_seqlens,
+                         void* d_qkv, compact_kv* kv, void* hip_stream);
+/* C[M, N] = A[M, K] B[N, K]^T (+ R[M, N] if d_r != NULL); epilogue 1 treats B
+ * as [2N, K] stacked gate/up and stores silu(A Bg^T) * (A Bu^T).            */
+int compact_gemm(compact_ctx* ctx, const void* d_a, const void* d_b, const void* d_r, void* d_c,
+                 int64_t M, int32_t N, int32_t K, int32_t epilogue, void* d_workspace,
+                 size_t ws_bytes, void* hip_stream);
+/* Causal attention of every block over its own tokens.  q is read from the
+ * packed qkv buffer (row stride Dq+2Dkv), K/V from the slabs (lens in h_len),
+ * o [T, Dq].                                                                 */
+int compact_attn_prefill(compact_ctx* ctx, int32_t n_blocks, const int32_t* h_cu_seqlens,
+                         const void* d_qkv, const compact_kv* kv, void* d_o, void* hip_stream);
+/* One query token per block against rows 0..h_len[b]-1 of its slabs.
+ * q [N, Dq] -> o [N, Dq].                                                    */
+int compact_attn_decode(compact_ctx* ctx, int32_t n_blocks, const void* d_q, const compact_kv* kv,
+                        void* d_o, void* d_workspace, size_t ws_bytes, void* hip_stream);
+/* Router: logits in fp32, top-k ids (descending, ties to the lower id) and
+ * softmax gate over the selected logits, for rows of m [rows, d].           */
+int compact_moe_route(compact_ctx* ctx, const void* d_m, const void* d_w_router, int64_t rows,
+                      int32_t* d_expert_idx, float* d_gate, float* d_logits, void* d_workspace,
+                      size_t ws_bytes, void* hip_stream);
+/* y = h + sum_k gate_k FFN_{idx_k}(m) for rows of m/h [rows, d], routing given. */
+int compact_moe_ffn(compact_ctx* ctx, const compact_weights* w, const void* d_m, const void* d_h,
+                    const int32_t* d_expert_idx, const float* d_gate, int64_t rows, void* d_y,
+                    void* d_workspace, size_t ws_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COMPACT_H */

@@ -1,0 +1,715 @@
+// C ABI of libcompact: argument validation, host-side planning (ragged tile
+// lists, workspace carving, metadata upload) and the launch sequences of the
+// prefill pass and the decode step.  All arithmetic is in the kernels.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <mutex>
+
+#include "common.h"
+
+static std::string g_create_err;
+
+int set_err(compact_ctx* ctx, int code, const std::string& msg) {
+    if (ctx)
+        ctx->err = msg;
+    else
+        g_create_err = msg;
+    return code;
+}
+
+// ---------------------------------------------------------------------------
+// profiling
+// ---------------------------------------------------------------------------
+ProfileScope::ProfileScope(compact_ctx* c, int klass, hipStream_t s) : ctx(c), stream(s), on(false) {
+    if (c->profile_class != klass || klass == COMPACT_K_NONE) return;
+    if (c->prof_used == c->prof_events.size()) {
+        ProfileSlot ns;
+        if (hipEventCreate(&ns.start) != hipSuccess || hipEventCreate(&ns.stop) != hipSuccess) return;
+        c->prof_events.push_back(ns);
+    }
+    slot = c->prof_events[c->prof_used++];
+    on = hipEventRecord(slot.start, stream) == hipSuccess;
+}
+ProfileScope::~ProfileScope() {
+    if (on) (void)hipEventRecord(slot.stop, stream);
+}
+
+extern "C" int compact_profile_select(compact_ctx* ctx, int32_t klass) {
+    if (!ctx) return COMPACT_EINVAL;
+    if (klass < 0 || klass >= COMPACT_K_COUNT) return set_err(ctx, COMPACT_EINVAL, "unknown kernel class");
+    ctx->profile_class = klass;
+    ctx->prof_used = 0;
+    ctx->prof_launches = 0;
+    ctx->prof_ms = 0.0;
+    return COMPACT_OK;
+}
+
+extern "C" int compact_profile_read(compact_ctx* ctx, int64_t* n_launches, double* total_ms) {
+    if (!ctx || !n_launches || !total_ms) return COMPACT_EINVAL;
+    for (size_t i = 0; i < ctx->prof_used; ++i) {
+        HIP_TRY(ctx, hipEventSynchronize(ctx->prof_events[i].stop));
+        float ms = 0.f;
+        HIP_TRY(ctx, hipEventElapsedTime(&ms, ctx->prof_events[i].start, ctx->prof_events[i].stop));
+        ctx->prof_ms += ms;
+        ctx->prof_launches += 1;
+    }
+    ctx->prof_used = 0;
+    *n_launches = ctx->prof_launches;
+    *total_ms = ctx->prof_ms;
+    return COMPACT_OK;
+}
+
+// ---------------------------------------------------------------------------
+// context
+// ---------------------------------------------------------------------------
+static int validate_cfg(const compact_layer_cfg* c, std::string& why) {
+    if (c->d_model <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->head_dim <= 0 || c->ffn_dim <= 0) {
+        why = "non-positive layer dimension";
+        return COMPACT_EINVAL;
+    }
+    if (c->dtype != COMPACT_FP32 && c->dtype != COMPACT_BF16) {
+        why = "dtype must be COMPACT_FP32 or COMPACT_BF16";
+        return COMPACT_EUNSUPPORTED;
+    }
+    if (c->head_dim != 64 && c->head_dim != 128) {
+        why = "head_dim must be 64 or 128";
+        return COMPACT_ESHAPE;
+    }
+    if (c->n_q_heads % c->n_kv_heads != 0 || c->n_q_heads / c->n_kv_heads > 16) {
+        why = "n_q_heads must be a multiple of n_kv_heads with a group of at most 16";
+        return COMPACT_ESHAPE;
+    }
+    if (c->d_model % 64 != 0 || c->ffn_dim % 64 != 0) {
+        why = "d_model and ffn_dim must be multiples of 64";
+        return COMPACT_ESHAPE;
+    }
+    if (c->n_experts < 0 || c->n_experts > 256) {
+        why = "n_experts must be in 0..256";
+        return COMPACT_ESHAPE;
+    }
+    if (c->n_experts > 0 && (c->top_k < 1 || c->top_k > 8 || c->top_k > c->n_experts)) {
+        why = "top_k must be in 1..min(8, n_experts)";
+        return COMPACT_ESHAPE;
+    }
+    if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) {
+        why = "rms_eps must be >= 0 and rope_theta > 0";
+        return COMPACT_EINVAL;
+    }
+    return COMPACT_OK;
+}
+
+extern "C" int compact_create(const compact_layer_cfg* cfg, compact_ctx** out) {
+    if (!cfg || !out) return set_err(nullptr, COMPACT_EINVAL, "null cfg or out");
+    std::string why;
+    const int rc = validate_cfg(cfg, why);
+    if (rc != COMPACT_OK) return set_err(nullptr, rc, why);
+    compact_ctx* ctx = new compact_ctx();
+    ctx->cfg = *cfg;
+    *out = ctx;
+    return COMPACT_OK;
+}
+
+extern "C" void compact_destroy(compact_ctx* ctx) {
+    if (!ctx) return;
+    if (ctx->d_meta) (void)hipFree(ctx->d_meta);
+    if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
+    if (ctx->stage_event) (void)hipEventDestroy(ctx->stage_event);
+    for (auto& e : ctx->prof_events) {
+        (void)hipEventDestroy(e.start);
+        (void)hipEventDestroy(e.stop);
+    }
+    delete ctx;
+}
+
+extern "C" const char* compact_last_error(const compact_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_err.c_str(); }
+
+// ---------------------------------------------------------------------------
+// workspace carving: the same routine sizes the workspace (base == nullptr)
+// and hands out its pieces
+// ---------------------------------------------------------------------------
+struct Carver {
+    char* base;
+    size_t off = 0;
+    explicit Carver(void* b) : base((char*)b) {}
+    void* take(size_t bytes) {
+        off = align_up(off, 256);
+        void* p = base ? base + off : nullptr;
+        off += bytes;
+        return p;
+    }
+};
+
+struct PrefillBufs {
+    void *n, *qkv, *o, *h, *act;
+    // MoE
+    float* logits;
+    int32_t* idx;
+    float* gate;
+    MoePlan plan;
+    void* expert_out;
+};
+
+struct DecodeBufs {
+    void *n, *q, *o, *m, *act;
+    float *h, *partials, *attn_partials;
+    float* logits;
+    int32_t* idx;
+    float* gate;
+    MoePlan plan;
+    void* expert_out;
+};
+
+static size_t max_partial_cols(const compact_layer_cfg& c) {
+    size_t cols = (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
+    cols = std::max(cols, (size_t)c.d_model);
+    cols = std::max(cols, (size_t)2 * c.ffn_dim);
+    return cols;
+}
+
+static void carve_moe_plan(Carver& cv, const compact_layer_cfg& c, int64_t rows, MoePlan& plan) {
+    const int64_t rk = rows * c.top_k;
+    const int mt = gemm_bf16_mtile();
+    plan.max_mtiles = (int32_t)(rk / mt + c.n_experts + 1);
+    plan.counts = (int32_t*)cv.take(sizeof(int32_t) * c.n_experts);
+    plan.offsets = (int32_t*)cv.take(sizeof(int32_t) * (c.n_experts + 1));
+    plan.sorted_token = (int32_t*)cv.take(sizeof(int32_t) * rk);
+    plan.sorted_gate = (float*)cv.take(sizeof(float) * rk);
+    plan.slot_of = (int32_t*)cv.take(sizeof(int32_t) * rk);
+    plan.tile_expert = (int32_t*)cv.take(sizeof(int32_t) * plan.max_mtiles);
+    plan.tile_row0 = (int32_t*)cv.take(sizeof(int32_t) * plan.max_mtiles);
+    plan.tile_rows = (int32_t*)cv.take(sizeof(int32_t) * plan.max_mtiles);
+}
+
+static void carve_prefill(Carver& cv, const compact_layer_cfg& c, int64_t T, PrefillBufs& b) {
+    const size_t es = dtype_size(c.dtype);
+    const size_t ld = (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
+    b.n = cv.take((size_t)T * c.d_model * es);  // reused for m
+    b.qkv = cv.take((size_t)T * ld * es);
+    b.o = cv.take((size_t)T * c.n_q_heads * c.head_dim * es);
+    b.h = cv.take((size_t)T * c.d_model * es);
+    if (c.n_experts == 0) {
+        b.act = cv.take((size_t)T * c.ffn_dim * es);
+    } else {
+        b.act = cv.take((size_t)T * c.top_k * c.ffn_dim * es);
+        b.logits = (float*)cv.take((size_t)T * c.n_experts * 4);
+        b.idx = (int32_t*)cv.take((size_t)T * c.top_k * 4);
+        b.gate = (float*)cv.take((size_t)T * c.top_k * 4);
+        carve_moe_plan(cv, c, T, b.plan);
+        b.expert_out = cv.take((size_t)T * c.top_k * c.d_model * es);
+    }
+}
+
+static int decode_max_ksplit(const compact_layer_cfg& c, int N);
+
+static void carve_decode(Carver& cv, const compact_layer_cfg& c, int N, int max_chunks, DecodeBufs& b) {
+    const size_t es = dtype_size(c.dtype);
+    b.n = cv.take((size_t)N * c.d_model * es);
+    b.q = cv.take((size_t)N * c.n_q_heads * c.head_dim * es);
+    b.o = cv.take((size_t)N * c.n_q_heads * c.head_dim * es);
+    b.m = cv.take((size_t)N * c.d_model * es);
+    b.h = (float*)cv.take((size_t)N * c.d_model * 4);
+    const int rows = c.n_experts == 0 ? N : N * c.top_k;
+    b.act = cv.take((size_t)rows * c.ffn_dim * es);
+    b.partials = (float*)cv.take((size_t)decode_max_ksplit(c, N) * rows * max_partial_cols(c) * 4);
+    b.attn_partials = (float*)cv.take(attn_decode_partial_floats(c, N, max_chunks) * 4);
+    if (c.n_experts > 0) {
+        b.logits = (float*)cv.take((size_t)N * c.n_experts * 4);
+        b.idx = (int32_t*)cv.take((size_t)N * c.top_k * 4);
+        b.gate = (float*)cv.take((size_t)N * c.top_k * 4);
+        carve_moe_plan(cv, c, N, b.plan);
+        b.expert_out = cv.take((size_t)N * c.top_k * c.d_model * es);
+    }
+}
+
+static int decode_max_ksplit(const compact_layer_cfg& c, int N) {
+    if (c.dtype != COMPACT_BF16) return 1;
+    const int Dtot = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
+    int ks = skinny_ksplit(N, Dtot, c.d_model);
+    ks = std::max(ks, skinny_ksplit(N, c.d_model, c.n_q_heads * c.head_dim));
+    ks = std::max(ks, skinny_ksplit(N, 2 * c.ffn_dim, c.d_model));
+    ks = std::max(ks, skinny_ksplit(N, c.d_model, c.ffn_dim));
+    return ks;
+}
+
+static int chunks_for(int len) { return (len + DECODE_CHUNK - 1) / DECODE_CHUNK; }
+
+extern "C" int compact_workspace_bytes(const compact_ctx* ctx, int64_t max_tokens, int32_t max_blocks,
+                                       int32_t max_kv_len, size_t* bytes) {
+    if (!ctx || !bytes) return COMPACT_EINVAL;
+    compact_ctx* c = const_cast<compact_ctx*>(ctx);
+    if (max_tokens < 0 || max_blocks < 1 || max_kv_len < 1)
+        return set_err(c, COMPACT_EINVAL, "max_tokens >= 0, max_blocks >= 1, max_kv_len >= 1 required");
+    Carver cp(nullptr), cd(nullptr);
+    PrefillBufs pb;
+    DecodeBufs db;
+    carve_prefill(cp, ctx->cfg, max_tokens, pb);
+    carve_decode(cd, ctx->cfg, max_blocks, chunks_for(max_kv_len), db);
+    // the decode region follows the prefill region, so a forward pass can keep
+    // the prefill outputs alive while it decodes
+    *bytes = align_up(cp.off, 256) + align_up(cd.off, 256) + 256;
+    return COMPACT_OK;
+}
+
+// ---------------------------------------------------------------------------
+// metadata upload
+// ---------------------------------------------------------------------------
+struct Plan {
+    std::vector<BlockMeta> meta;
+    std::vector<TileItem> rope_tiles, q_tiles;
+    int max_len = 0;
+    // device views
+    const BlockMeta* d_meta = nullptr;
+    const TileItem* d_rope_tiles = nullptr;
+    const TileItem* d_q_tiles = nullptr;
+};
+
+static int upload_plan(compact_ctx* ctx, Plan& p, hipStream_t s) {
+    const size_t b0 = align_up(p.meta.size() * sizeof(BlockMeta), 256);
+    const size_t b1 = align_up(p.rope_tiles.size() * sizeof(TileItem), 256);
+    const size_t b2 = align_up(p.q_tiles.size() * sizeof(TileItem), 256);
+    const size_t total = b0 + b1 + b2;
+    if (total > ctx->meta_bytes) {
+        // growing the metadata buffer: wait for work that may still read the old one
+        HIP_TRY(ctx, hipDeviceSynchronize());
+        if (ctx->d_meta) HIP_TRY(ctx, hipFree(ctx->d_meta));
+        if (ctx->h_stage) HIP_TRY(ctx, hipHostFree(ctx->h_stage));
+        ctx->d_meta = nullptr;
+        ctx->h_stage = nullptr;
+        ctx->meta_bytes = 0;
+        const size_t cap = std::max(total * 2, (size_t)1 << 16);
+        HIP_TRY(ctx, hipMalloc(&ctx->d_meta, cap));
+        HIP_TRY(ctx, hipHostMalloc(&ctx->h_stage, cap, hipHostMallocDefault));
+        ctx->meta_bytes = cap;
+    }
+    if (!ctx->stage_event) HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->stage_event, hipEventDisableTiming));
+    if (ctx->stage_pending) {  // the previous upload must have left the staging buffer
+        HIP_TRY(ctx, hipEventSynchronize(ctx->stage_event));
+        ctx->stage_pending = false;
+    }
+    char* hs = (char*)ctx->h_stage;
+    memcpy(hs, p.meta.data(), p.meta.size() * sizeof(BlockMeta));
+    if (!p.rope_tiles.empty()) memcpy(hs + b0, p.rope_tiles.data(), p.rope_tiles.size() * sizeof(TileItem));
+    if (!p.q_tiles.empty()) memcpy(hs + b0 + b1, p.q_tiles.data(), p.q_tiles.size() * sizeof(TileItem));
+    HIP_TRY(ctx, hipMemcpyAsync(ctx->d_meta, hs, total, hipMemcpyHostToDevice, s));
+    HIP_TRY(ctx, hipEventRecord(ctx->stage_event, s));
+    ctx->stage_pending = true;
+    char* dm = (char*)ctx->d_meta;
+    p.d_meta = (const BlockMeta*)dm;
+    p.d_rope_tiles = (const TileItem*)(dm + b0);
+    p.d_q_tiles = (const TileItem*)(dm + b0 + b1);
+    return COMPACT_OK;
+}
+
+// ---------------------------------------------------------------------------
+// validation shared by the entry points
+// ---------------------------------------------------------------------------
+static int check_kv(compact_ctx* ctx, const compact_kv* kv, int n_blocks) {
+    if (!kv || !kv->d_k || !kv->d_v || !kv->h_slab_offset || !kv->h_capacity || !kv->h_len)
+        return set_err(ctx, COMPACT_EINVAL, "kv and its d_k, d_v, h_slab_offset, h_capacity, h_len must be non-null");
+    for (int b = 0; b < n_blocks; ++b) {
+        if (kv->h_capacity[b] < 8 || kv->h_capacity[b] % 8 != 0)
+            return set_err(ctx, COMPACT_EINVAL, "h_capacity[b] must be a positive multiple of 8");
+        if (kv->h_slab_offset[b] < 0 || kv->h_slab_offset[b] % 8 != 0)
+            return set_err(ctx, COMPACT_EINVAL, "h_slab_offset[b] must be a non-negative multiple of 8");
+    }
+    return COMPACT_OK;
+}
+
+static int check_weights(compact_ctx* ctx, const compact_weights* w) {
+    if (!w) return set_err(ctx, COMPACT_EINVAL, "null weights");
+    if (!w->g_attn || !w->w_qkv || !w->w_o || !w->g_ffn) return set_err(ctx, COMPACT_EINVAL, "null attention weights");
+    if (ctx->cfg.n_experts == 0) {
+        if (!w->w_gate_up || !w->w_down) return set_err(ctx, COMPACT_EINVAL, "null dense FFN weights");
+    } else {
+        if (!w->w_router || !w->w_exp_gate_up || !w->w_exp_down) return set_err(ctx, COMPACT_EINVAL, "null MoE weights");
+    }
+    return COMPACT_OK;
+}
+
+static int check_blocks(compact_ctx* ctx, int n_blocks, const int32_t* cu) {
+    if (n_blocks < 1) return set_err(ctx, COMPACT_EINVAL, "n_blocks must be >= 1");
+    if (!cu) return set_err(ctx, COMPACT_EINVAL, "null h_cu_seqlens");
+    if (cu[0] != 0) return set_err(ctx, COMPACT_EINVAL, "h_cu_seqlens[0] must be 0");
+    for (int b = 0; b < n_blocks; ++b)
+        if (cu[b + 1] <= cu[b]) return set_err(ctx, COMPACT_EINVAL, "h_cu_seqlens must be strictly increasing (empty blocks are not allowed)");
+    return COMPACT_OK;
+}
+
+static void build_prefill_plan(const compact_kv* kv, int n_blocks, const int32_t* cu, Plan& p) {
+    p.meta.resize(n_blocks);
+    for (int b = 0; b < n_blocks; ++b) {
+        BlockMeta& m = p.meta[b];
+        m.row0 = cu[b];
+        m.len = cu[b + 1] - cu[b];
+        m.capacity = kv->h_capacity[b];
+        m.pos_offset = kv->h_pos_offset ? kv->h_pos_offset[b] : 0;
+        m.slab = kv->h_slab_offset[b];
+        p.max_len = std::max(p.max_len, m.len);
+        for (int r = 0; r < m.len; r += ROPE_TILE) p.rope_tiles.push_back({b, r});
+        for (int r = 0; r < m.len; r += PREFILL_QTILE) p.q_tiles.push_back({b, r});
+    }
+    // causal work of a query tile grows with its row offset: heaviest first
+    std::stable_sort(p.q_tiles.begin(), p.q_tiles.end(),
+                     [](const TileItem& a, const TileItem& b) { return a.row0 > b.row0; });
+}
+
+static void build_decode_plan(const compact_kv* kv, int n_blocks, Plan& p) {
+    p.meta.resize(n_blocks);
+    for (int b = 0; b < n_blocks; ++b) {
+        BlockMeta& m = p.meta[b];
+        m.row0 = b;
+        m.len = kv->h_len[b];
+        m.capacity = kv->h_capacity[b];
+        m.pos_offset = kv->h_pos_offset ? kv->h_pos_offset[b] : 0;
+        m.slab = kv->h_slab_offset[b];
+        p.max_len = std::max(p.max_len, m.len);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// GEMM dispatch by storage type
+// ---------------------------------------------------------------------------
+// prefill-size: C = A B^T (+R) or SwiGLU epilogue
+static int gemm_full(compact_ctx* ctx, const void* A, const void* B, const void* R, void* C, int64_t M, int N, int K,
+                     int epi, hipStream_t s) {
+    if (ctx->cfg.dtype == COMPACT_BF16) {
+        ProfileScope ps(ctx, COMPACT_K_GEMM, s);
+        return launch_gemm_bf16(ctx, (const bf16*)A, (const bf16*)B, (const bf16*)R, (bf16*)C, M, N, K, epi, nullptr, s);
+    }
+    return launch_gemm_f32(ctx, (const float*)A, (const float*)B, (const float*)R, (float*)C, M, N, K, epi, s);
+}
+
+// decode-size: fp32 split-K partials [ks][M][N]
+static int gemm_partials(compact_ctx* ctx, const void* A, const void* B, float* partials, int M, int N, int K, int* ks,
+                         hipStream_t s) {
+    if (ctx->cfg.dtype == COMPACT_BF16) {
+        *ks = skinny_ksplit(M, N, K);
+        ProfileScope ps(ctx, COMPACT_K_GEMM_SKINNY, s);
+        return launch_gemm_skinny(ctx, (const bf16*)A, (const bf16*)B, partials, M, N, K, *ks, s);
+    }
+    *ks = 1;
+    return launch_gemm_f32(ctx, (const float*)A, (const float*)B, nullptr, partials, M, N, K, 0, s);
+}
+
+#define TRY(expr)                      \
+    do {                               \
+        const int _rc = (expr);        \
+        if (_rc != COMPACT_OK) return _rc; \
+    } while (0)
+
+// ---------------------------------------------------------------------------
+// prefill
+// ---------------------------------------------------------------------------
+static int run_attn_prefill(compact_ctx* ctx, const Plan& p, int n_blocks, const void* qkv, const compact_kv* kv, void* o,
+                            hipStream_t s) {
+    ProfileScope ps(ctx, COMPACT_K_ATTN_PREFILL, s);
+    if (ctx->cfg.dtype == COMPACT_BF16)
+        return launch_attn_prefill_bf16(ctx, p.d_meta, p.d_q_tiles, (int)p.q_tiles.size(), (const bf16*)qkv,
+                                        (const bf16*)kv->d_k, (const bf16*)kv->d_v, (bf16*)o, s);
+    return launch_attn_prefill_f32(ctx, p.d_meta, n_blocks, p.max_len, (const float*)qkv, (const float*)kv->d_k,
+                                   (const float*)kv->d_v, (float*)o, s);
+}
+
+static int moe_ffn_rows(compact_ctx* ctx, const compact_weights* w, const void* m, const void* h, const int32_t* idx,
+                        const float* gate, int64_t rows, void* act, const MoePlan& plan, void* expert_out, void* y,
+                        hipStream_t s);
+
+static int prefill_impl(compact_ctx* ctx, const compact_weights* w, int n_blocks, const int32_t* cu, const void* x,
+                        compact_kv* kv, void* y, void* y_last, const compact_route_out* route, void* ws, size_t ws_bytes,
+                        Plan& plan, hipStream_t s) {
+    const compact_layer_cfg& c = ctx->cfg;
+    const int64_t T = cu[n_blocks];
+    Carver cv(ws);
+    PrefillBufs b;
+    carve_prefill(cv, c, T, b);
+    if (cv.off > ws_bytes) return set_err(ctx, COMPACT_EWORKSPACE, "workspace too small for this prefill");
+    const int Dq = c.n_q_heads * c.head_dim, Dtot = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
+
+    TRY(upload_plan(ctx, plan, s));
+    TRY(launch_rmsnorm(ctx, x, w->g_attn, b.n, T, s));
+    TRY(gemm_full(ctx, b.n, w->w_qkv, nullptr, b.qkv, T, Dtot, c.d_model, 0, s));
+    TRY(launch_rope_kvwrite(ctx, plan.d_meta, plan.d_rope_tiles, (int)plan.rope_tiles.size(), b.qkv, kv->d_k, kv->d_v, s));
+    TRY(run_attn_prefill(ctx, plan, n_blocks, b.qkv, kv, b.o, s));
+    TRY(gemm_full(ctx, b.o, w->w_o, x, b.h, T, c.d_model, Dq, 0, s));
+    TRY(launch_rmsnorm(ctx, b.h, w->g_ffn, b.n, T, s));
+    if (c.n_experts == 0) {
+        TRY(gemm_full(ctx, b.n, w->w_gate_up, nullptr, b.act, T, c.ffn_dim, c.d_model, 1, s));
+        TRY(gemm_full(ctx, b.act, w->w_down, b.h, y, T, c.d_model, c.ffn_dim, 0, s));
+    } else {
+        int32_t* idx = route && route->d_expert_idx ? route->d_expert_idx : b.idx;
+        float* gate = route && route->d_gate ? route->d_gate : b.gate;
+        TRY(launch_moe_route(ctx, b.n, w->w_router, T, idx, gate, b.logits, s));
+        TRY(moe_ffn_rows(ctx, w, b.n, b.h, idx, gate, T, b.act, b.plan, b.expert_out, y, s));
+    }
+    if (y_last) TRY(launch_gather_last_rows(ctx, plan.d_meta, n_blocks, y, y_last, s));
+    return COMPACT_OK;
+}
+
+static int validate_prefill(compact_ctx* ctx, const compact_weights* w, int n_blocks, const int32_t* cu, const void* x,
+                            compact_kv* kv, void* ws, int extra_rows) {
+    TRY(check_blocks(ctx, n_blocks, cu));
+    TRY(check_weights(ctx, w));
+    if (!x) return set_err(ctx, COMPACT_EINVAL, "null input");
+    if (!ws) return set_err(ctx, COMPACT_EWORKSPACE, "null workspace");
+    TRY(check_kv(ctx, kv, n_blocks));
+    for (int b = 0; b < n_blocks; ++b)
+        if ((int64_t)(cu[b + 1] - cu[b]) + extra_rows > kv->h_capacity[b])
+            return set_err(ctx, COMPACT_ECAPACITY, "block " + std::to_string(b) + " does not fit its KV slab");
+    return COMPACT_OK;
+}
+
+extern "C" int compact_prefill(compact_ctx* ctx, const compact_weights* w, int32_t n_blocks, const int32_t* h_cu_seqlens,
+                               const void* d_x, compact_kv* kv, void* d_y, const compact_route_out* route,
+                               void* d_workspace, size_t ws_bytes, void* hip_stream) {
+    if (!ctx) return COMPACT_EINVAL;
+    TRY(validate_prefill(ctx, w, n_blocks, h_cu_seqlens, d_x, kv, d_workspace, 0));
+    if (!d_y) return set_err(ctx, COMPACT_EINVAL, "null output");
+    Plan plan;
+    build_prefill_plan(kv, n_blocks, h_cu_seqlens, plan);
+    TRY(prefill_impl(ctx, w, n_blocks, h_cu_seqlens, d_x, kv, d_y, nullptr, route, d_workspace, ws_bytes, plan,
+                     (hipStream_t)hip_stream));
+    for (int b = 0; b < n_blocks; ++b) kv->h_len[b] = h_cu_seqlens[b + 1] - h_cu_seqlens[b];
+    return COMPACT_OK;
+}
+
+// ---------------------------------------------------------------------------
+// decode
+// ---------------------------------------------------------------------------
+static int run_attn_decode(compact_ctx* ctx, const Plan& p, int n_blocks, int step, const void* q, const compact_kv* kv,
+                           float* attn_partials, void* o, hipStream_t s) {
+    if (ctx->cfg.dtype == COMPACT_BF16) {
+        const int max_chunks = chunks_for(p.max_len + step + 1);
+        return launch_attn_decode_bf16(ctx, p.d_meta, n_blocks, step, max_chunks, (const bf16*)q, (const bf16*)kv->d_k,
+                                       (const bf16*)kv->d_v, attn_partials, (bf16*)o, s);
+    }
+    return launch_attn_decode_f32(ctx, p.d_meta, n_blocks, step, (const float*)q, (const float*)kv->d_k,
+                                  (const float*)kv->d_v, (float*)o, s);
+}
+
+// one decode step for all blocks; plan.meta.len = cached tokens before step 0
+static int decode_impl(compact_ctx* ctx, const compact_weights* w, int n_blocks, int step, const void* x,
+                       compact_kv* kv, void* y, const compact_route_out* route, const DecodeBufs& b, const Plan& plan,
+                       hipStream_t s) {
+    const compact_layer_cfg& c = ctx->cfg;
+    const int N = n_blocks;
+    const int Dq = c.n_q_heads * c.head_dim, Dtot = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
+    int ks = 1;
+    TRY(launch_rmsnorm(ctx, x, w->g_attn, b.n, N, s));
+    TRY(gemm_partials(ctx, b.n, w->w_qkv, b.partials, N, Dtot, c.d_model, &ks, s));
+    TRY(launch_decode_qkv_epilogue(ctx, plan.d_meta, N, step, b.partials, ks, b.q, kv->d_k, kv->d_v, s));
+    TRY(run_attn_decode(ctx, plan, N, step, b.q, kv, b.attn_partials, b.o, s));
+    TRY(gemm_partials(ctx, b.o, w->w_o, b.partials, N, c.d_model, Dq, &ks, s));
+    TRY(launch_residual_norm(ctx, b.partials, ks, x, w->g_ffn, b.h, b.m, N, s));
+    if (c.n_experts == 0) {
+        TRY(gemm_partials(ctx, b.m, w->w_gate_up, b.partials, N, 2 * c.ffn_dim, c.d_model, &ks, s));
+        TRY(launch_swiglu_reduce(ctx, b.partials, ks, b.act, N, c.ffn_dim, s));
+        TRY(gemm_partials(ctx, b.act, w->w_down, b.partials, N, c.d_model, c.ffn_dim, &ks, s));
+        TRY(launch_residual_reduce(ctx, b.partials, ks, b.h, y, N, c.d_model, s));
+    } else {
+        return set_err(ctx, COMPACT_EUNSUPPORTED, "MoE decode not built yet");
+    }
+    return COMPACT_OK;
+}
+
+static int validate_decode(compact_ctx* ctx, const compact_weights* w, int n_blocks, const void* x, compact_kv* kv,
+                           void* y, void* ws, int n_steps) {
+    if (n_blocks < 1) return set_err(ctx, COMPACT_EINVAL, "n_blocks must be >= 1");
+    TRY(check_weights(ctx, w));
+    if (!x || !y) return set_err(ctx, COMPACT_EINVAL, "null input or output");
+    if (!ws) return set_err(ctx, COMPACT_EWORKSPACE, "null workspace");
+    TRY(check_kv(ctx, kv, n_blocks));
+    for (int b = 0; b < n_blocks; ++b) {
+        if (kv->h_len[b] < 0) return set_err(ctx, COMPACT_EINVAL, "negative h_len");
+        if ((int64_t)kv->h_len[b] + n_steps > kv->h_capacity[b])
+            return set_err(ctx, COMPACT_ECAPACITY, "block " + std::to_string(b) + ": len + steps exceeds its KV slab");
+    }
+    return COMPACT_OK;
+}
+
+extern "C" int compact_decode_step(compact_ctx* ctx, const compact_weights* w, int32_t n_blocks, const void* d_x,
+                                   compact_kv* kv, void* d_y, const compact_route_out* route, void* d_workspace,
+                                   size_t ws_bytes, void* hip_stream) {
+    if (!ctx) return COMPACT_EINVAL;
+    TRY(validate_decode(ctx, w, n_blocks, d_x, kv, d_y, d_workspace, 1));
+    hipStream_t s = (hipStream_t)hip_stream;
+    Plan plan;
+    build_decode_plan(kv, n_blocks, plan);
+    Carver cv(d_workspace);
+    DecodeBufs b;
+    carve_decode(cv, ctx->cfg, n_blocks, chunks_for(plan.max_len + 1), b);
+    if (cv.off > ws_bytes) return set_err(ctx, COMPACT_EWORKSPACE, "workspace too small for this decode step");
+    TRY(upload_plan(ctx, plan, s));
+    TRY(decode_impl(ctx, w, n_blocks, 0, d_x, kv, d_y, route, b, plan, s));
+    for (int b2 = 0; b2 < n_blocks; ++b2) kv->h_len[b2] += 1;
+    return COMPACT_OK;
+}
+
+extern "C" int compact_layer_forward(compact_ctx* ctx, const compact_weights* w, int32_t n_blocks,
+                                     const int32_t* h_cu_seqlens, const void* d_x_prefill, int32_t n_steps,
+                                     const void* d_x_decode, compact_kv* kv, void* d_y_prefill, void* d_y_last,
+                                     void* d_y_decode, void* d_workspace, size_t ws_bytes, void* hip_stream) {
+    if (!ctx) return COMPACT_EINVAL;
+    if (n_steps < 0) return set_err(ctx, COMPACT_EINVAL, "n_steps must be >= 0");
+    TRY(validate_prefill(ctx, w, n_blocks, h_cu_seqlens, d_x_prefill, kv, d_workspace, n_steps));
+    if (n_steps > 0 && (!d_x_decode || !d_y_decode)) return set_err(ctx, COMPACT_EINVAL, "null decode input or output");
+    const compact_layer_cfg& c = ctx->cfg;
+    hipStream_t s = (hipStream_t)hip_stream;
+    Plan plan;
+    build_prefill_plan(kv, n_blocks, h_cu_seqlens, plan);
+    const int64_t T = h_cu_seqlens[n_blocks];
+
+    // workspace: [prefill region][prefill y if the caller wants none][decode region]
+    Carver cp(d_workspace);
+    PrefillBufs pb;
+    carve_prefill(cp, c, T, pb);
+    size_t off = align_up(cp.off, 256);
+    void* y_pre = d_y_prefill;
+    if (!y_pre) {
+        // the FFN output may overwrite the attention scratch that is dead by then
+        y_pre = pb.qkv;
+    }
+    Carver cd(d_workspace ? (char*)d_workspace + off : nullptr);
+    DecodeBufs db;
+    carve_decode(cd, c, n_blocks, chunks_for(plan.max_len + n_steps), db);
+    if (off + cd.off > ws_bytes) return set_err(ctx, COMPACT_EWORKSPACE, "workspace too small for this forward pass");
+
+    TRY(prefill_impl(ctx, w, n_blocks, h_cu_seqlens, d_x_prefill, kv, y_pre, d_y_last, nullptr, d_workspace, off, plan, s));
+    const size_t row_bytes = (size_t)n_blocks * c.d_model * dtype_size(c.dtype);
+    for (int st = 0; st < n_steps; ++st) {
+        TRY(decode_impl(ctx, w, n_blocks, st, (const char*)d_x_decode + st * row_bytes, kv,
+                        (char*)d_y_decode + st * row_bytes, nullptr, db, plan, s));
+    }
+    for (int b = 0; b < n_blocks; ++b) kv->h_len[b] = h_cu_seqlens[b + 1] - h_cu_seqlens[b] + n_steps;
+    return COMPACT_OK;
+}
+
+// ---------------------------------------------------------------------------
+// MoE feed-forward over rows with given routing (shared by prefill and hooks)
+// ---------------------------------------------------------------------------
+static int moe_ffn_rows(compact_ctx* ctx, const compact_weights* w, const void* m, const void* h, const int32_t* idx,
+                        const float* gate, int64_t rows, void* act, const MoePlan& plan, void* expert_out, void* y,
+                        hipStream_t s) {
+    return set_err(ctx, COMPACT_EUNSUPPORTED, "MoE feed-forward not built yet");
+}
+
+// ---------------------------------------------------------------------------
+// per-kernel entry points
+// ---------------------------------------------------------------------------
+extern "C" int compact_rmsnorm(compact_ctx* ctx, const void* d_x, const void* d_g, void* d_y, int64_t rows,
+                               void* hip_stream) {
+    if (!ctx) return COMPACT_EINVAL;
+    if (!d_x || !d_g || !d_y || rows < 0) return set_err(ctx, COMPACT_EINVAL, "null pointer or negative rows");
+    return launch_rmsnorm(ctx, d_x, d_g, d_y, rows, (hipStream_t)hip_stream);
+}
+
+extern "C" int compact_rope_kvwrite(compact_ctx* ctx, int32_t n_blocks, const int32_t* h_cu_seqlens, void* d_qkv,
+                                    compact_kv* kv, void* hip_stream) {
+    if (!ctx) return COMPACT_EINVAL;
+    TRY(check_blocks(ctx, n_blocks, h_cu_seqlens));
+    if (!d_qkv) return set_err(ctx, COMPACT_EINVAL, "null qkv");
+    TRY(check_kv(ctx, kv, n_blocks));
+    for (int b = 0; b < n_blocks; ++b)
+        if (h_cu_seqlens[b + 1] - h_cu_seqlens[b] > kv->h_capacity[b])
+            return set_err(ctx, COMPACT_ECAPACITY, "block does not fit its KV slab");
+    hipStream_t s = (hipStream_t)hip_stream;
+    Plan plan;
+    build_prefill_plan(kv, n_blocks, h_cu_seqlens, plan);
+    TRY(upload_plan(ctx, plan, s));
+    TRY(launch_rope_kvwrite(ctx, plan.d_meta, plan.d_rope_tiles, (int)plan.rope_tiles.size(), d_qkv, kv->d_k, kv->d_v, s));
+    for (int b = 0; b < n_blocks; ++b) kv->h_len[b] = h_cu_seqlens[b + 1] - h_cu_seqlens[b];
+    return COMPACT_OK;
+}
+
+extern "C" int compact_gemm(compact_ctx* ctx, const void* d_a, const void* d_b, const void* d_r, void* d_c, int64_t M,
+                            int32_t N, int32_t K, int32_t epilogue, void* d_workspace, size_t ws_bytes,
+                            void* hip_stream) {
+    if (!ctx) return COMPACT_EINVAL;
+    if (!d_a || !d_b || !d_c) return set_err(ctx, COMPACT_EINVAL, "null operand");
+    if (M < 0 || N < 1 || K < 1) return set_err(ctx, COMPACT_EINVAL, "bad GEMM shape");
+    if (epilogue != 0 && epilogue != 1) return set_err(ctx, COMPACT_EINVAL, "epilogue must be 0 or 1");
+    if (ctx->cfg.dtype == COMPACT_BF16 && (K % 64 != 0 || N % 8 != 0))
+        return set_err(ctx, COMPACT_ESHAPE, "bf16 GEMM needs K % 64 == 0 and N % 8 == 0");
+    hipStream_t s = (hipStream_t)hip_stream;
+    // rows at or below the decode batch limit take the weight-streaming kernel
+    if (ctx->cfg.dtype == COMPACT_BF16 && M <= 64 && M > 0 && epilogue == 0 && d_workspace) {
+        const int ks = skinny_ksplit((int)M, N, K);
+        if ((size_t)ks * M * N * 4 > ws_bytes) return set_err(ctx, COMPACT_EWORKSPACE, "workspace too small for split-K partials");
+        {
+            ProfileScope ps(ctx, COMPACT_K_GEMM_SKINNY, s);
+            TRY(launch_gemm_skinny(ctx, (const bf16*)d_a, (const bf16*)d_b, (float*)d_workspace, (int)M, N, K, ks, s));
+        }
+        return launch_skinny_finish(ctx, (const float*)d_workspace, ks, (const bf16*)d_r, (bf16*)d_c, (int)M, N, s);
+    }
+    return gemm_full(ctx, d_a, d_b, d_r, d_c, M, N, K, epilogue, s);
+}
+
+extern "C" int compact_attn_prefill(compact_ctx* ctx, int32_t n_blocks, const int32_t* h_cu_seqlens, const void* d_qkv,
+                                    const compact_kv* kv, void* d_o, void* hip_stream) {
+    if (!ctx) return COMPACT_EINVAL;
+    TRY(check_blocks(ctx, n_blocks, h_cu_seqlens));
+    if (!d_qkv || !d_o) return set_err(ctx, COMPACT_EINVAL, "null qkv or o");
+    TRY(check_kv(ctx, kv, n_blocks));
+    for (int b = 0; b < n_blocks; ++b)
+        if (h_cu_seqlens[b + 1] - h_cu_seqlens[b] > kv->h_capacity[b])
+            return set_err(ctx, COMPACT_ECAPACITY, "block does not fit its KV slab");
+    hipStream_t s = (hipStream_t)hip_stream;
+    Plan plan;
+    build_prefill_plan(kv, n_blocks, h_cu_seqlens, plan);
+    TRY(upload_plan(ctx, plan, s));
+    return run_attn_prefill(ctx, plan, n_blocks, d_qkv, kv, d_o, s);
+}
+
+extern "C" int compact_attn_decode(compact_ctx* ctx, int32_t n_blocks, const void* d_q, const compact_kv* kv, void* d_o,
+                                   void* d_workspace, size_t ws_bytes, void* hip_stream) {
+    if (!ctx) return COMPACT_EINVAL;
+    if (n_blocks < 1) return set_err(ctx, COMPACT_EINVAL, "n_blocks must be >= 1");
+    if (!d_q || !d_o) return set_err(ctx, COMPACT_EINVAL, "null q or o");
+    TRY(check_kv(ctx, kv, n_blocks));
+    for (int b = 0; b < n_blocks; ++b)
+        if (kv->h_len[b] < 1 || kv->h_len[b] > kv->h_capacity[b])
+            return set_err(ctx, COMPACT_ECAPACITY, "h_len must be in 1..capacity");
+    hipStream_t s = (hipStream_t)hip_stream;
+    Plan plan;
+    build_decode_plan(kv, n_blocks, plan);
+    for (auto& m : plan.meta) m.len -= 1;  // the kernels attend rows 0..len inclusive
+    plan.max_len -= 1;
+    const size_t need = attn_decode_partial_floats(ctx->cfg, n_blocks, chunks_for(plan.max_len + 1)) * 4;
+    if (ctx->cfg.dtype == COMPACT_BF16 && (!d_workspace || ws_bytes < need))
+        return set_err(ctx, COMPACT_EWORKSPACE, "workspace too small for the split-KV partials");
+    TRY(upload_plan(ctx, plan, s));
+    return run_attn_decode(ctx, plan, n_blocks, 0, d_q, kv, (float*)d_workspace, d_o, s);
+}
+
+extern "C" int compact_moe_route(compact_ctx* ctx, const void* d_m, const void* d_w_router, int64_t rows,
+                                 int32_t* d_expert_idx, float* d_gate, float* d_logits, void* d_workspace,
+                                 size_t ws_bytes, void* hip_stream) {
+    if (!ctx) return COMPACT_EINVAL;
+    if (ctx->cfg.n_experts == 0) return set_err(ctx, COMPACT_EINVAL, "layer has no experts");
+    if (!d_m || !d_w_router || !d_expert_idx || !d_gate || rows < 0) return set_err(ctx, COMPACT_EINVAL, "null pointer or negative rows");
+    float* logits = d_logits;
+    if (!logits) {
+        if (!d_workspace || ws_bytes < (size_t)rows * ctx->cfg.n_experts * 4)
+            return set_err(ctx, COMPACT_EWORKSPACE, "workspace too small for the router logits");
+        logits = (float*)d_workspace;
+    }
+    return launch_moe_route(ctx, d_m, d_w_router, rows, d_expert_idx, d_gate, logits, (hipStream_t)hip_stream);
+}
+
+extern "C" int compact_moe_ffn(compact_ctx* ctx, const compact_weights* w, const void* d_m, const void* d_h,
+                               const int32_t* d_expert_idx, const float* d_gate, int64_t rows, void* d_y,
+                               void* d_workspace, size_t ws_bytes, void* hip_stream) {
+    if (!ctx) return COMPACT_EINVAL;
+    if (ctx->cfg.n_experts == 0) return set_err(ctx, COMPACT_EINVAL, "layer has no experts");
+    TRY(check_weights(ctx, w));
+    if (!d_m || !d_h || !d_expert_idx || !d_gate || !d_y || rows < 0) return set_err(ctx, COMPACT_EINVAL, "null pointer or negative rows");
+    const compact_layer_cfg& c = ctx->cfg;
+    const size_t es = dtype_size(c.dtype);
+    Carver cv(d_workspace);
+    void* act = cv.take((size_t)rows * c.top_k * c.ffn_dim * es);
+    MoePlan plan;
+    carve_moe_plan(cv, c, rows, plan);
+    void* expert_out = cv.take((size_t)rows * c.top_k * c.d_model * es);
+    if (!d_workspace || cv.off > ws_bytes) return set_err(ctx, COMPACT_EWORKSPACE, "workspace too small for the expert feed-forward");
+    return moe_ffn_rows(ctx, w, d_m, d_h, d_expert_idx, d_gate, rows, act, plan, expert_out, d_y, (hipStream_t)hip_stream);
+}

@@ -1,0 +1,168 @@
+// Internal declarations shared by the translation units of libcompact.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include <string>
+#include <vector>
+
+#include "../../include/compact.h"
+
+typedef __bf16 bf16;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+#define WAVE 64
+
+// Chunk of cached tokens handled by one decode-attention workgroup.  Fixed, so
+// that the split of a block's cache depends on that block's length only.
+#define DECODE_CHUNK 256
+// Query rows per prefill-attention tile and token rows per rotary/KV-write tile.
+#define PREFILL_QTILE 128
+#define ROPE_TILE 64
+
+// Per-block metadata as the kernels see it (device copy lives in the context).
+struct BlockMeta {
+    int32_t row0;        // first packed row of the block (prefill) / unused in decode
+    int32_t len;         // prefill: L_b; decode: cached tokens before this call
+    int32_t capacity;    // slab rows
+    int32_t pos_offset;  // added to the block-local index to get the rotary position
+    int64_t slab;        // element offset of the block's slabs in d_k / d_v
+};
+
+struct TileItem {  // (block, first block-local row) of a row tile
+    int32_t block;
+    int32_t row0;
+};
+
+struct ProfileSlot {
+    hipEvent_t start, stop;
+};
+
+struct compact_ctx {
+    compact_layer_cfg cfg;
+    std::string err;
+    // device metadata (allocated on first use)
+    void* d_meta = nullptr;
+    void* h_stage = nullptr;      // pinned staging copy of the metadata
+    hipEvent_t stage_event = nullptr;
+    bool stage_pending = false;
+    size_t meta_bytes = 0;
+    // profiling
+    int profile_class = COMPACT_K_NONE;
+    std::vector<ProfileSlot> prof_events;
+    size_t prof_used = 0;
+    int64_t prof_launches = 0;
+    double prof_ms = 0.0;
+};
+
+// RAII-free helper used by launchers: brackets a launch with events when its
+// class is the one being profiled.
+struct ProfileScope {
+    compact_ctx* ctx;
+    hipStream_t stream;
+    bool on;
+    ProfileSlot slot;
+    ProfileScope(compact_ctx* c, int klass, hipStream_t s);
+    ~ProfileScope();
+};
+
+int set_err(compact_ctx* ctx, int code, const std::string& msg);
+#define HIP_TRY(ctx, expr)                                                             \
+    do {                                                                               \
+        hipError_t _e = (expr);                                                        \
+        if (_e != hipSuccess)                                                          \
+            return set_err(ctx, COMPACT_EHIP, std::string(#expr) + ": " + hipGetErrorString(_e)); \
+    } while (0)
+#define LAUNCH_CHECK(ctx) HIP_TRY(ctx, hipGetLastError())
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static inline size_t dtype_size(int dtype) { return dtype == COMPACT_BF16 ? 2 : 4; }
+
+// ---------------------------------------------------------------------------
+// kernel launchers (one translation unit each)
+// ---------------------------------------------------------------------------
+
+// norm_rope.hip
+int launch_rmsnorm(compact_ctx* ctx, const void* x, const void* g, void* y, int64_t rows, hipStream_t s);
+int launch_rope_kvwrite(compact_ctx* ctx, const BlockMeta* d_meta, const TileItem* d_tiles, int n_tiles,
+                        void* qkv, void* d_k, void* d_v, hipStream_t s);
+// decode: reduce ks split partials of the QKV projection, rotate, append K/V, emit q
+int launch_decode_qkv_epilogue(compact_ctx* ctx, const BlockMeta* d_meta, int n_blocks, int step,
+                               const float* partials, int ks, void* q_out, void* d_k, void* d_v,
+                               hipStream_t s);
+// decode: h = resid + sum partials; writes h and m = RMSNorm(h; g)
+int launch_residual_norm(compact_ctx* ctx, const float* partials, int ks, const void* resid,
+                         const void* g, void* h_out, void* m_out, int rows, hipStream_t s);
+// decode: act = silu(gate) * up from ks partials of the stacked gate/up projection
+int launch_swiglu_reduce(compact_ctx* ctx, const float* partials, int ks, void* act, int rows, int F,
+                         hipStream_t s);
+// decode: y = resid + sum partials
+int launch_residual_reduce(compact_ctx* ctx, const float* partials, int ks, const void* resid, void* y,
+                           int rows, int cols, hipStream_t s);
+// copies the last row of every block of y [T, d] to y_last [N, d]
+int launch_gather_last_rows(compact_ctx* ctx, const BlockMeta* d_meta, int n_blocks, const void* y,
+                            void* y_last, hipStream_t s);
+
+// gemm_f32.hip : C = A B^T (+R) ; epilogue 1 = SwiGLU on stacked gate/up
+int launch_gemm_f32(compact_ctx* ctx, const float* A, const float* B, const float* R, float* C,
+                    int64_t M, int N, int K, int epilogue, hipStream_t s);
+
+// gemm_bf16.hip
+struct GroupedArgs {          // all device pointers; null tile_expert => plain GEMM
+    const int32_t* tile_expert;   // [n_mtiles] expert of every row tile (-1 = no work)
+    const int32_t* tile_row0;     // [n_mtiles] first row (in expert-sorted order)
+    const int32_t* tile_rows;     // [n_mtiles] valid rows in the tile
+    const int32_t* a_gather;      // [rows] source row of A for every sorted row (null = identity)
+    const float* row_scale;       // [rows] multiplies the output row (null = 1)
+    int64_t b_expert_stride;      // elements between consecutive experts' B
+    int32_t n_mtiles;
+};
+int launch_gemm_bf16(compact_ctx* ctx, const bf16* A, const bf16* B, const bf16* R, bf16* C, int64_t M,
+                     int N, int K, int epilogue, const GroupedArgs* grouped, hipStream_t s);
+int gemm_bf16_mtile();
+
+// gemm_skinny.hip : partials[ks][M][N] (fp32) = A[M,K] B[N,K]^T split over K
+int skinny_ksplit(int M, int N, int K);
+int launch_gemm_skinny(compact_ctx* ctx, const bf16* A, const bf16* B, float* partials, int M, int N, int K,
+                       int ks, hipStream_t s);
+// C = sum of partials (+R), rounded to bf16
+int launch_skinny_finish(compact_ctx* ctx, const float* partials, int ks, const bf16* R, bf16* C, int M, int N,
+                         hipStream_t s);
+
+// attn_f32.hip
+int launch_attn_prefill_f32(compact_ctx* ctx, const BlockMeta* d_meta, int n_blocks, int max_len,
+                            const float* qkv, const float* d_k, const float* d_v, float* o, hipStream_t s);
+int launch_attn_decode_f32(compact_ctx* ctx, const BlockMeta* d_meta, int n_blocks, int step, const float* q,
+                           const float* d_k, const float* d_v, float* o, hipStream_t s);
+
+// attn_prefill.hip (bf16 MFMA)
+int launch_attn_prefill_bf16(compact_ctx* ctx, const BlockMeta* d_meta, const TileItem* d_qtiles, int n_qtiles,
+                             const bf16* qkv, const bf16* d_k, const bf16* d_v, bf16* o, hipStream_t s);
+
+// attn_decode.hip (bf16 MFMA, split-KV)
+size_t attn_decode_partial_floats(const compact_layer_cfg& cfg, int n_blocks, int max_chunks);
+int launch_attn_decode_bf16(compact_ctx* ctx, const BlockMeta* d_meta, int n_blocks, int step, int max_chunks,
+                            const bf16* q, const bf16* d_k, const bf16* d_v, float* partials, bf16* o,
+                            hipStream_t s);
+
+// moe.hip
+struct MoePlan {              // device buffers carved from the workspace
+    int32_t* counts;          // [E]
+    int32_t* offsets;         // [E+1]
+    int32_t* sorted_token;    // [rows*k] source token of every sorted row
+    float* sorted_gate;       // [rows*k]
+    int32_t* slot_of;         // [rows*k] sorted position of (token, j)
+    int32_t* tile_expert;     // [max_mtiles]
+    int32_t* tile_row0;
+    int32_t* tile_rows;
+    int32_t max_mtiles;
+};
+int launch_moe_route(compact_ctx* ctx, const void* m, const void* w_router, int64_t rows, int32_t* idx,
+                     float* gate, float* logits, hipStream_t s);
+int launch_moe_plan(compact_ctx* ctx, const int32_t* idx, const float* gate, int64_t rows, int mtile,
+                    const MoePlan& plan, hipStream_t s);
+int launch_moe_combine(compact_ctx* ctx, const void* expert_out, const void* h, const int32_t* slot_of,
+                       int64_t rows, void* y, hipStream_t s);

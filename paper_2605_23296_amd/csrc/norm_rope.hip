@@ -1,0 +1,357 @@
+// RMSNorm, rotary embedding + KV-cache write, and the row epilogues of the
+// decode step.  All of these are bandwidth-bound row kernels: 16-byte loads,
+// fp32 arithmetic, one workgroup per row (or per 64-token tile).
+#include "common.h"
+#include "vecio.h"
+
+#define NT 256
+
+// sum over the workgroup; every thread gets the result
+__device__ __forceinline__ float block_sum(float v, float* red) {
+    v = wave_sum(v);
+    const int w = threadIdx.x / WAVE;
+    __syncthreads();
+    if ((threadIdx.x & (WAVE - 1)) == 0) red[w] = v;
+    __syncthreads();
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < NT / WAVE; ++i) t += red[i];
+    return t;
+}
+
+// ---------------------------------------------------------------------------
+// y = x / sqrt(mean(x^2) + eps) * g
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(NT) void rmsnorm_kernel(const T* __restrict__ x, const T* __restrict__ g,
+                                                     T* __restrict__ y, int d, float eps) {
+    __shared__ float red[NT / WAVE];
+    const T* xr = x + (size_t)blockIdx.x * d;
+    T* yr = y + (size_t)blockIdx.x * d;
+    float ss = 0.f;
+    for (int c = threadIdx.x * 8; c < d; c += NT * 8) {
+        float v[8];
+        load8(xr + c, v);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) ss += v[j] * v[j];
+    }
+    ss = block_sum(ss, red);
+    const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+    for (int c = threadIdx.x * 8; c < d; c += NT * 8) {
+        float v[8], gv[8];
+        load8(xr + c, v);
+        load8(g + c, gv);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = v[j] * inv * gv[j];
+        store8(yr + c, v);
+    }
+}
+
+int launch_rmsnorm(compact_ctx* ctx, const void* x, const void* g, void* y, int64_t rows, hipStream_t s) {
+    if (rows == 0) return COMPACT_OK;
+    const int d = ctx->cfg.d_model;
+    if (ctx->cfg.dtype == COMPACT_BF16)
+        rmsnorm_kernel<bf16><<<dim3((unsigned)rows), NT, 0, s>>>((const bf16*)x, (const bf16*)g, (bf16*)y, d, ctx->cfg.rms_eps);
+    else
+        rmsnorm_kernel<float><<<dim3((unsigned)rows), NT, 0, s>>>((const float*)x, (const float*)g, (float*)y, d, ctx->cfg.rms_eps);
+    LAUNCH_CHECK(ctx);
+    return COMPACT_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Rotary embedding of q and k for a 64-token tile of one block, K rows to the
+// K slab, V rows transposed to the V slab.  The rotation angle is formed in
+// fp64 (position * theta^(-2i/hd)) so that positions in the thousands do not
+// cost fp32 angle precision; cos/sin are then used as fp32.
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(NT) void rope_kvwrite_kernel(const BlockMeta* __restrict__ meta,
+                                                          const TileItem* __restrict__ tiles, T* __restrict__ qkv,
+                                                          T* __restrict__ kbase, T* __restrict__ vbase, int Hq, int Hkv,
+                                                          int hd, double log2_theta) {
+    extern __shared__ char smem[];
+    const int half = hd / 2;
+    float2* cs = reinterpret_cast<float2*>(smem);                       // [ROPE_TILE][half]
+    T* vt = reinterpret_cast<T*>(smem + (size_t)ROPE_TILE * half * 8);  // [ROPE_TILE][hd + 8]
+    const int vld = hd + 8;
+
+    const TileItem it = tiles[blockIdx.x];
+    const BlockMeta bm = meta[it.block];
+    const int p0 = it.row0;
+    const int ntok = min(ROPE_TILE, bm.len - p0);
+    const int ld = (Hq + 2 * Hkv) * hd;
+    T* rows = qkv + (size_t)(bm.row0 + p0) * ld;
+
+    for (int idx = threadIdx.x; idx < ntok * half; idx += NT) {
+        const int tok = idx / half, i = idx - tok * half;
+        const double inv_freq = exp2(-2.0 * (double)i / (double)hd * log2_theta);
+        const double ang = (double)(bm.pos_offset + p0 + tok) * inv_freq;
+        double sn, cn;
+        sincos(ang, &sn, &cn);
+        cs[idx] = make_float2((float)cn, (float)sn);
+    }
+    __syncthreads();
+
+    // q heads (in place) and k heads (to the slab)
+    const int chunks = half / 8;
+    const int per_tok = (Hq + Hkv) * chunks;
+    T* kslab = kbase + bm.slab;
+    for (int idx = threadIdx.x; idx < ntok * per_tok; idx += NT) {
+        const int tok = idx / per_tok;
+        const int r = idx - tok * per_tok;
+        const int head = r / chunks, c = r - head * chunks;
+        T* src = rows + (size_t)tok * ld + head * hd + c * 8;
+        float lo[8], hi[8], olo[8], ohi[8];
+        load8(src, lo);
+        load8(src + half, hi);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float2 t = cs[tok * half + c * 8 + j];
+            olo[j] = lo[j] * t.x - hi[j] * t.y;
+            ohi[j] = hi[j] * t.x + lo[j] * t.y;
+        }
+        T* dst = src;
+        if (head >= Hq) dst = kslab + ((size_t)(head - Hq) * bm.capacity + p0 + tok) * hd + c * 8;
+        store8(dst, olo);
+        store8(dst + half, ohi);
+    }
+
+    // v heads: stage [tok][hd] in LDS, write [hd][tok]
+    T* vslab = vbase + bm.slab;
+    for (int kvh = 0; kvh < Hkv; ++kvh) {
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < ntok * (hd / 8); idx += NT) {
+            const int tok = idx / (hd / 8), c = idx - tok * (hd / 8);
+            const T* src = rows + (size_t)tok * ld + (Hq + Hkv + kvh) * hd + c * 8;
+            float v[8];
+            load8(src, v);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) vt[tok * vld + c * 8 + j] = from_f32<T>(v[j]);
+        }
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < hd * (ROPE_TILE / 8); idx += NT) {
+            const int dd = idx / (ROPE_TILE / 8), c = idx - dd * (ROPE_TILE / 8);
+            const int t0 = c * 8;
+            if (t0 >= ntok) continue;
+            T* dst = vslab + ((size_t)kvh * hd + dd) * bm.capacity + p0 + t0;
+            if (t0 + 8 <= ntok) {
+                float v[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) v[j] = to_f32(vt[(t0 + j) * vld + dd]);
+                store8(dst, v);
+            } else {
+                for (int j = 0; t0 + j < ntok; ++j) dst[j] = vt[(t0 + j) * vld + dd];
+            }
+        }
+    }
+}
+
+int launch_rope_kvwrite(compact_ctx* ctx, const BlockMeta* d_meta, const TileItem* d_tiles, int n_tiles, void* qkv,
+                        void* d_k, void* d_v, hipStream_t s) {
+    if (n_tiles == 0) return COMPACT_OK;
+    const compact_layer_cfg& c = ctx->cfg;
+    const double l2t = log2((double)c.rope_theta);
+    const size_t es = dtype_size(c.dtype);
+    const size_t smem = (size_t)ROPE_TILE * (c.head_dim / 2) * 8 + (size_t)ROPE_TILE * (c.head_dim + 8) * es;
+    if (c.dtype == COMPACT_BF16)
+        rope_kvwrite_kernel<bf16><<<n_tiles, NT, smem, s>>>(d_meta, d_tiles, (bf16*)qkv, (bf16*)d_k, (bf16*)d_v,
+                                                           c.n_q_heads, c.n_kv_heads, c.head_dim, l2t);
+    else
+        rope_kvwrite_kernel<float><<<n_tiles, NT, smem, s>>>(d_meta, d_tiles, (float*)qkv, (float*)d_k, (float*)d_v,
+                                                            c.n_q_heads, c.n_kv_heads, c.head_dim, l2t);
+    LAUNCH_CHECK(ctx);
+    return COMPACT_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Decode: sum the split-K partials of the QKV projection for one block's
+// token, rotate q and k at position pos_offset + len + step, write q, append
+// the K row and the V column at cache row len + step.
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(NT) void decode_qkv_epilogue_kernel(const BlockMeta* __restrict__ meta, int n_rows, int step,
+                                                                 const float* __restrict__ partials, int ks,
+                                                                 T* __restrict__ q_out, T* __restrict__ kbase,
+                                                                 T* __restrict__ vbase, int Hq, int Hkv, int hd,
+                                                                 double log2_theta) {
+    __shared__ float2 cs[64];  // half <= 64
+    const int b = blockIdx.x;
+    const BlockMeta bm = meta[b];
+    const int half = hd / 2;
+    const int p = bm.len + step;
+    const int ld = (Hq + 2 * Hkv) * hd;
+    const size_t ps = (size_t)n_rows * ld;  // stride between split partials
+    const float* row = partials + (size_t)b * ld;
+
+    if (threadIdx.x < half) {
+        const int i = threadIdx.x;
+        const double inv_freq = exp2(-2.0 * (double)i / (double)hd * log2_theta);
+        double sn, cn;
+        sincos((double)(bm.pos_offset + p) * inv_freq, &sn, &cn);
+        cs[i] = make_float2((float)cn, (float)sn);
+    }
+    __syncthreads();
+    T* kslab = kbase + bm.slab;
+    T* vslab = vbase + bm.slab;
+    for (int idx = threadIdx.x; idx < (Hq + Hkv) * half; idx += NT) {
+        const int head = idx / half, i = idx - head * half;
+        float lo = 0.f, hi = 0.f;
+        for (int s = 0; s < ks; ++s) {
+            lo += row[s * ps + head * hd + i];
+            hi += row[s * ps + head * hd + half + i];
+        }
+        const float2 t = cs[i];
+        const float olo = lo * t.x - hi * t.y;
+        const float ohi = hi * t.x + lo * t.y;
+        if (head < Hq) {
+            T* dst = q_out + (size_t)b * Hq * hd + head * hd + i;
+            dst[0] = from_f32<T>(olo);
+            dst[half] = from_f32<T>(ohi);
+        } else {
+            T* dst = kslab + ((size_t)(head - Hq) * bm.capacity + p) * hd + i;
+            dst[0] = from_f32<T>(olo);
+            dst[half] = from_f32<T>(ohi);
+        }
+    }
+    for (int idx = threadIdx.x; idx < Hkv * hd; idx += NT) {
+        float v = 0.f;
+        for (int s = 0; s < ks; ++s) v += row[s * ps + (Hq + Hkv) * hd + idx];
+        vslab[(size_t)idx * bm.capacity + p] = from_f32<T>(v);  // idx = kvh*hd + dd
+    }
+}
+
+int launch_decode_qkv_epilogue(compact_ctx* ctx, const BlockMeta* d_meta, int n_blocks, int step, const float* partials,
+                               int ks, void* q_out, void* d_k, void* d_v, hipStream_t s) {
+    const compact_layer_cfg& c = ctx->cfg;
+    const double l2t = log2((double)c.rope_theta);
+    if (c.dtype == COMPACT_BF16)
+        decode_qkv_epilogue_kernel<bf16><<<n_blocks, NT, 0, s>>>(d_meta, n_blocks, step, partials, ks, (bf16*)q_out,
+                                                                (bf16*)d_k, (bf16*)d_v, c.n_q_heads, c.n_kv_heads,
+                                                                c.head_dim, l2t);
+    else
+        decode_qkv_epilogue_kernel<float><<<n_blocks, NT, 0, s>>>(d_meta, n_blocks, step, partials, ks, (float*)q_out,
+                                                                 (float*)d_k, (float*)d_v, c.n_q_heads, c.n_kv_heads,
+                                                                 c.head_dim, l2t);
+    LAUNCH_CHECK(ctx);
+    return COMPACT_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Decode: h = resid + sum_s partial_s (kept in fp32), m = RMSNorm(h; g)
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(NT) void residual_norm_kernel(const float* __restrict__ partials, int ks, int rows,
+                                                           const T* __restrict__ resid, const T* __restrict__ g,
+                                                           float* __restrict__ h_out, T* __restrict__ m_out, int d,
+                                                           float eps) {
+    extern __shared__ char smem[];
+    float* hrow = reinterpret_cast<float*>(smem);  // [d]
+    __shared__ float red[NT / WAVE];
+    const int r = blockIdx.x;
+    const size_t ps = (size_t)rows * d;
+    float ss = 0.f;
+    for (int c = threadIdx.x; c < d; c += NT) {
+        float v = to_f32(resid[(size_t)r * d + c]);
+        for (int s = 0; s < ks; ++s) v += partials[s * ps + (size_t)r * d + c];
+        hrow[c] = v;
+        h_out[(size_t)r * d + c] = v;
+        ss += v * v;
+    }
+    ss = block_sum(ss, red);
+    const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+    for (int c = threadIdx.x; c < d; c += NT)
+        m_out[(size_t)r * d + c] = from_f32<T>(hrow[c] * inv * to_f32(g[c]));
+}
+
+int launch_residual_norm(compact_ctx* ctx, const float* partials, int ks, const void* resid, const void* g,
+                         void* h_out, void* m_out, int rows, hipStream_t s) {
+    const compact_layer_cfg& c = ctx->cfg;
+    const size_t smem = (size_t)c.d_model * 4;
+    if (c.dtype == COMPACT_BF16)
+        residual_norm_kernel<bf16><<<rows, NT, smem, s>>>(partials, ks, rows, (const bf16*)resid, (const bf16*)g,
+                                                         (float*)h_out, (bf16*)m_out, c.d_model, c.rms_eps);
+    else
+        residual_norm_kernel<float><<<rows, NT, smem, s>>>(partials, ks, rows, (const float*)resid, (const float*)g,
+                                                          (float*)h_out, (float*)m_out, c.d_model, c.rms_eps);
+    LAUNCH_CHECK(ctx);
+    return COMPACT_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Decode: act = silu(gate) * up, gate/up = sum of partials of the stacked
+// projection [rows, 2F]
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(NT) void swiglu_reduce_kernel(const float* __restrict__ partials, int ks, int rows,
+                                                           T* __restrict__ act, int F) {
+    const int r = blockIdx.y;
+    const int c = blockIdx.x * NT + threadIdx.x;
+    if (c >= F) return;
+    const size_t ps = (size_t)rows * 2 * F;
+    float gt = 0.f, up = 0.f;
+    for (int s = 0; s < ks; ++s) {
+        gt += partials[s * ps + (size_t)r * 2 * F + c];
+        up += partials[s * ps + (size_t)r * 2 * F + F + c];
+    }
+    const float sg = gt / (1.0f + expf(-gt));
+    act[(size_t)r * F + c] = from_f32<T>(sg * up);
+}
+
+int launch_swiglu_reduce(compact_ctx* ctx, const float* partials, int ks, void* act, int rows, int F, hipStream_t s) {
+    dim3 grid((F + NT - 1) / NT, rows);
+    if (ctx->cfg.dtype == COMPACT_BF16)
+        swiglu_reduce_kernel<bf16><<<grid, NT, 0, s>>>(partials, ks, rows, (bf16*)act, F);
+    else
+        swiglu_reduce_kernel<float><<<grid, NT, 0, s>>>(partials, ks, rows, (float*)act, F);
+    LAUNCH_CHECK(ctx);
+    return COMPACT_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Decode: y = resid (fp32) + sum_s partial_s
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(NT) void residual_reduce_kernel(const float* __restrict__ partials, int ks, int rows,
+                                                             const float* __restrict__ resid, T* __restrict__ y,
+                                                             int cols) {
+    const int r = blockIdx.y;
+    const int c = blockIdx.x * NT + threadIdx.x;
+    if (c >= cols) return;
+    const size_t ps = (size_t)rows * cols;
+    float v = resid[(size_t)r * cols + c];
+    for (int s = 0; s < ks; ++s) v += partials[s * ps + (size_t)r * cols + c];
+    y[(size_t)r * cols + c] = from_f32<T>(v);
+}
+
+int launch_residual_reduce(compact_ctx* ctx, const float* partials, int ks, const void* resid, void* y, int rows,
+                           int cols, hipStream_t s) {
+    dim3 grid((cols + NT - 1) / NT, rows);
+    if (ctx->cfg.dtype == COMPACT_BF16)
+        residual_reduce_kernel<bf16><<<grid, NT, 0, s>>>(partials, ks, rows, (const float*)resid, (bf16*)y, cols);
+    else
+        residual_reduce_kernel<float><<<grid, NT, 0, s>>>(partials, ks, rows, (const float*)resid, (float*)y, cols);
+    LAUNCH_CHECK(ctx);
+    return COMPACT_OK;
+}
+
+// ---------------------------------------------------------------------------
+// y_last[b] = y[last row of block b]
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(NT) void gather_last_rows_kernel(const BlockMeta* __restrict__ meta,
+                                                              const T* __restrict__ y, T* __restrict__ y_last, int d) {
+    const BlockMeta bm = meta[blockIdx.x];
+    const T* src = y + (size_t)(bm.row0 + bm.len - 1) * d;
+    T* dst = y_last + (size_t)blockIdx.x * d;
+    for (int c = threadIdx.x; c < d; c += NT) dst[c] = src[c];
+}
+
+int launch_gather_last_rows(compact_ctx* ctx, const BlockMeta* d_meta, int n_blocks, const void* y, void* y_last,
+                            hipStream_t s) {
+    if (ctx->cfg.dtype == COMPACT_BF16)
+        gather_last_rows_kernel<bf16><<<n_blocks, NT, 0, s>>>(d_meta, (const bf16*)y, (bf16*)y_last, ctx->cfg.d_model);
+    else
+        gather_last_rows_kernel<float><<<n_blocks, NT, 0, s>>>(d_meta, (const float*)y, (float*)y_last, ctx->cfg.d_model);
+    LAUNCH_CHECK(ctx);
+    return COMPACT_OK;
+}

@@ -1,0 +1,140 @@
+"""Host-side checks of the C ABI: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2605_23296_amd import binding as B
+from paper_2605_23296_amd.workloads import WORKLOADS, LayerConfig
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "compact.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(compact_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = B.lib()
+    syms = header_symbols()
+    assert len(syms) >= 16
+    for s in syms:
+        assert hasattr(L, s), s
+    assert sorted(B.EXPORTS) == syms
+
+
+def test_create_validates_cfg():
+    L = B.lib()
+    good = WORKLOADS["tiny_fp32"].layer
+    ctx = C.c_void_p()
+    assert L.compact_create(C.byref(B.make_cfg(good)), C.byref(ctx)) == 0
+    L.compact_destroy(ctx)
+    bad = [
+        (dict(head_dim=48), 2), (dict(n_kv_heads=3), 2), (dict(d_model=100), 2),
+        (dict(n_experts=4, top_k=0), 2), (dict(n_experts=4, top_k=5), 2), (dict(d_model=0), 1),
+        (dict(dtype="fp32", rope_theta=-1.0), 1),
+    ]
+    for kw, code in bad:
+        d = good.as_dict()
+        d.update(kw)
+        cfg = B.make_cfg(LayerConfig(**d))
+        assert L.compact_create(C.byref(cfg), C.byref(ctx)) == code, kw
+        assert L.compact_last_error(None) != b""
+    cfg = B.make_cfg(good)
+    cfg.dtype = 7
+    assert L.compact_create(C.byref(cfg), C.byref(ctx)) == 5
+    assert L.compact_create(None, C.byref(ctx)) == 1
+
+
+def test_workspace_bytes_grows_with_the_problem():
+    lay = B.Layer(WORKLOADS["dense_8x4096"].layer, None)
+    a = lay.workspace_bytes(1024, 4, 2048)
+    b = lay.workspace_bytes(32768, 8, 4352)
+    assert 0 < a < b
+    # n, qkv, o, h, act for 32768 tokens in bf16
+    assert b > 32768 * 2 * (4096 * 3 + 6144 + 14336)
+    with pytest.raises(B.CompactError) as e:
+        lay.workspace_bytes(-1, 4, 16)
+    assert e.value.code == 1
+
+
+def _fake_layer(name="tiny_fp32"):
+    layer = WORKLOADS[name].layer
+
+    class T:  # stand-in for a device tensor: validation never dereferences it
+        def __init__(self, addr):
+            self.addr = addr
+
+        def data_ptr(self):
+            return self.addr
+
+    names = ["g_attn", "w_qkv", "w_o", "g_ffn", "w_gate_up", "w_down"]
+    return B.Layer(layer, {n: T(0x1000 * (i + 1)) for i, n in enumerate(names)})
+
+
+def _kv(caps, lens, offs=None):
+    n = len(caps)
+    offs = offs or [i * 1 << 20 for i in range(n)]
+    keep = dict(off=(C.c_int64 * n)(*offs), cap=(C.c_int32 * n)(*caps), len=(C.c_int32 * n)(*lens))
+    kv = B.KV(0x10000, 0x20000, keep["off"], keep["cap"], keep["len"], C.cast(None, C.POINTER(C.c_int32)))
+    return kv, keep
+
+
+def test_layer_calls_reject_bad_arguments_without_a_device():
+    lay = _fake_layer()
+    L, ctx, w = lay.L, lay.ctx, C.byref(lay.w)
+    x = C.c_void_p(0x30000)
+    ws = C.c_void_p(0x40000)
+    kv, keep = _kv([128, 128], [0, 0])
+    cu = (C.c_int32 * 3)(0, 100, 200)
+
+    def prefill(cu=cu, x=x, kv=kv, y=x, ws=ws, n=2, w=w):
+        return L.compact_prefill(ctx, w, n, cu, x, C.byref(kv) if kv is not None else None, y, None, ws, 1 << 30, None)
+
+    assert prefill(n=0) == 1
+    assert prefill(cu=None) == 1
+    assert prefill(cu=(C.c_int32 * 3)(0, 100, 100)) == 1          # empty block
+    assert b"empty" in L.compact_last_error(ctx)
+    assert prefill(cu=(C.c_int32 * 3)(0, 100, 50)) == 1           # not increasing
+    assert prefill(cu=(C.c_int32 * 3)(1, 100, 200)) == 1          # does not start at 0
+    assert prefill(x=None) == 1
+    assert prefill(y=None) == 1
+    assert prefill(kv=None) == 1
+    assert prefill(ws=None) == 4
+    assert prefill(w=None) == 1
+    assert prefill(cu=(C.c_int32 * 3)(0, 129, 200)) == 3          # block longer than its slab
+    kv2, k2 = _kv([128, 100], [0, 0])
+    assert prefill(kv=kv2) == 1                                   # capacity not a multiple of 8
+    kv3, k3 = _kv([128, 128], [0, 0], offs=[0, 12])
+    assert prefill(kv=kv3) == 1                                   # slab offset not a multiple of 8
+
+    # decode: len + 1 must fit the slab
+    kv4, k4 = _kv([128, 128], [128, 5])
+    assert L.compact_decode_step(ctx, w, 2, x, C.byref(kv4), x, None, ws, 1 << 30, None) == 3
+    assert k4["len"][0] == 128 and k4["len"][1] == 5              # untouched on failure
+    kv5, k5 = _kv([128, 128], [5, 5])
+    assert L.compact_decode_step(ctx, w, 2, None, C.byref(kv5), x, None, ws, 1 << 30, None) == 1
+    assert L.compact_decode_step(ctx, w, 2, x, C.byref(kv5), x, None, None, 0, None) == 4
+
+    # forward: prefill rows + decode steps must fit
+    assert L.compact_layer_forward(ctx, w, 2, cu, x, 29, x, C.byref(kv), x, None, x, ws, 1 << 30, None) == 3
+    assert L.compact_layer_forward(ctx, w, 2, cu, x, -1, x, C.byref(kv), x, None, x, ws, 1 << 30, None) == 1
+    assert L.compact_layer_forward(ctx, w, 2, cu, x, 4, None, C.byref(kv), x, None, x, ws, 1 << 30, None) == 1
+
+
+def test_kernel_hooks_reject_bad_arguments_without_a_device():
+    lay = _fake_layer()
+    L, ctx = lay.L, lay.ctx
+    p = C.c_void_p(0x1000)
+    assert L.compact_rmsnorm(ctx, None, p, p, 4, None) == 1
+    assert L.compact_gemm(ctx, p, p, None, None, 4, 8, 8, 0, None, 0, None) == 1
+    assert L.compact_gemm(ctx, p, p, None, p, 4, 8, 8, 3, None, 0, None) == 1
+    assert L.compact_moe_route(ctx, p, p, 4, p, p, p, None, 0, None) == 1     # dense layer: no experts
+    kv, keep = _kv([128], [0])
+    assert L.compact_attn_decode(ctx, 1, p, C.byref(kv), p, None, 0, None) == 3   # empty cache
+    blay = _fake_layer("dense_8x4096")
+    assert blay.L.compact_gemm(blay.ctx, p, p, None, p, 128, 64, 100, 0, None, 0, None) == 2

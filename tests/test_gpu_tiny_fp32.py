@@ -1,0 +1,88 @@
+"""fp32 storage mode against the fp64 checker: the tiny layer in full, at 1e-5."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_23296_amd import binding as B
+from paper_2605_23296_amd.workloads import WORKLOADS, make_inputs, to_numpy_f64
+from tests import harness as H
+from tests.util import rel_err
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-5     # fp32 mode: max |g - r| / max(|r|, rms(r)) per output tensor
+
+
+def check_forward(inp, pos_offset=None, tol=TOL):
+    g = H.gpu_forward(inp, pos_offset=pos_offset)
+    r = H.oracle_forward(inp, pos_offset=pos_offset)
+    y_pre = np.concatenate([p["y"] for p in r["pre"]])
+    errs = dict(y_prefill=rel_err(g["y_prefill"], y_pre), y_decode=rel_err(g["y_decode"], r["y_decode"]))
+    last = np.stack([p["y"][-1] for p in r["pre"]])
+    errs["y_last"] = rel_err(g["y_last"], last)
+    for b in range(len(inp.block_lens)):
+        assert g["lens"][b] == inp.block_lens[b] + inp.x_decode.shape[0]
+        errs["K%d" % b] = rel_err(g["K"][b], r["K"][b])
+        errs["V%d" % b] = rel_err(g["V"][b], r["V"][b])
+    print({k: "%.2e" % v for k, v in errs.items()})
+    assert max(errs.values()) < tol, errs
+    return g, r
+
+
+def test_tiny_fp32_layer_in_full():
+    check_forward(make_inputs(WORKLOADS["tiny_fp32"]))
+
+
+def test_ragged_blocks_with_gain_and_position_offsets():
+    # lengths straddling every tile edge of the row kernels: 1, 63..65, 127..129, a long ragged tail
+    lens = [1, 63, 64, 65, 127, 128, 129, 257, 2]
+    inp = make_inputs(WORKLOADS["tiny_fp32"], block_lens=lens, decode_steps=3, gain_jitter=True)
+    check_forward(inp, pos_offset=[0, 5, 1000, 0, 7, 0, 4000, 1, 0])
+
+
+def test_head_dim_128_fp32():
+    wl = WORKLOADS["tiny_fp32"]
+    import copy
+    wl = copy.deepcopy(wl)
+    wl.layer.head_dim, wl.layer.n_q_heads, wl.layer.n_kv_heads, wl.layer.rope_theta = 128, 4, 1, 500000.0
+    check_forward(make_inputs(wl, block_lens=[70, 33], decode_steps=2))
+
+
+def test_step_by_step_api_matches_forward_call():
+    inp = make_inputs(WORKLOADS["tiny_fp32"], block_lens=[40, 9, 77], decode_steps=4)
+    ref = H.gpu_forward(inp)
+    lay = H.gpu_layer(inp)
+    layer = inp.layer
+    N, S, T = 3, 4, inp.cu_seqlens[-1]
+    kv = B.KVCache(layer, [L + S for L in inp.block_lens], "cuda", torch.float32)
+    lay.ensure_workspace(T, N, max(inp.block_lens) + S, "cuda")
+    x = inp.x_prefill.cuda()
+    y = torch.empty_like(x)
+    lay.compact_prefill(inp.cu_seqlens, x, kv, y)
+    assert kv.lens() == inp.block_lens
+    ys = []
+    for s in range(S):
+        ys.append(torch.empty(N, layer.d_model, device="cuda"))
+        lay.compact_decode_step(inp.x_decode[s].cuda().contiguous(), kv, ys[-1])
+    torch.cuda.synchronize()
+    assert kv.lens() == [L + S for L in inp.block_lens]
+    assert np.array_equal(to_numpy_f64(y), ref["y_prefill"])
+    assert np.array_equal(to_numpy_f64(torch.stack(ys)), ref["y_decode"])
+    for b in range(N):
+        assert np.array_equal(to_numpy_f64(kv.block_k(b)), ref["K"][b])
+        assert np.array_equal(to_numpy_f64(kv.block_v(b)), ref["V"][b])
+
+
+def test_batched_equals_one_block_at_a_time_bitwise():
+    """Sec. IV: per-block results are independent of the rest of the batch."""
+    import copy
+    inp = make_inputs(WORKLOADS["tiny_fp32"], block_lens=[40, 9, 77, 128], decode_steps=3)
+    full = H.gpu_forward(inp)
+    for b, L in enumerate(inp.block_lens):
+        one = copy.copy(inp)
+        one.block_lens, one.cu_seqlens = [L], [0, L]
+        one.x_prefill = inp.x_prefill[inp.cu_seqlens[b]:inp.cu_seqlens[b + 1]].contiguous()
+        one.x_decode = inp.x_decode[:, b:b + 1].contiguous()
+        g = H.gpu_forward(one)
+        assert np.array_equal(g["y_prefill"], full["y_prefill"][inp.cu_seqlens[b]:inp.cu_seqlens[b + 1]])
+        assert np.array_equal(g["y_decode"][:, 0], full["y_decode"][:, b])
+        assert np.array_equal(g["K"][0], full["K"][b]) and np.array_equal(g["V"][0], full["V"][b])
