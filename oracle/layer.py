@@ -113,6 +113,11 @@ def gqa_attention(q, k, v, visible):
     return o
 
 
+def linear(x, w):
+    """x W^T with W stored [out, in]."""
+    return _f64(x) @ _f64(w).T
+
+
 def silu(z):
     return z / (1.0 + np.exp(-z))
 
@@ -192,15 +197,16 @@ class Layer:
 
     # -- feed-forward half --------------------------------------------------
     def ffn(self, h):
-        """Second RMSNorm, feed-forward, residual.  Returns (y, idx, gate)."""
+        """Second RMSNorm, feed-forward, residual.  Returns (y, idx, gate, router logits)."""
         m = rmsnorm(h, self.w["g_ffn"], self.eps)
         if self.E == 0:
             F = self.F
             wgu = self.w["w_gate_up"]
-            return h + swiglu_ffn(m, wgu[:F], wgu[F:], self.w["w_down"]), None, None
-        idx, gate = topk_route(router_logits(m, self.w["w_router"]), self.k)
+            return h + swiglu_ffn(m, wgu[:F], wgu[F:], self.w["w_down"]), None, None, None
+        logits = router_logits(m, self.w["w_router"])
+        idx, gate = topk_route(logits, self.k)
         y = h + moe_ffn(m, idx, gate, self.w["w_exp_gate_up"], self.w["w_exp_down"])
-        return y, idx, gate
+        return y, idx, gate, logits
 
     # -- one block ----------------------------------------------------------
     def prefill_block(self, x, pos0=0, rows=None):
@@ -218,8 +224,8 @@ class Layer:
         rows = np.arange(L) if rows is None else np.asarray(rows, dtype=np.int64)
         o = gqa_attention(q[rows], k, v, visible=rows + 1)     # row i sees j <= i
         h = x[rows] + o.reshape(len(rows), self.Dq) @ _f64(self.w["w_o"]).T
-        y, idx, gate = self.ffn(h)
-        return dict(y=y, K=k, V=v, rows=rows, idx=idx, gate=gate)
+        y, idx, gate, logits = self.ffn(h)
+        return dict(y=y, K=k, V=v, rows=rows, idx=idx, gate=gate, logits=logits)
 
     def decode_block(self, x, K, V, pos0=0):
         """One new token for one block whose cache holds len = K.shape[0] rows.
@@ -235,10 +241,11 @@ class Layer:
         V = np.concatenate([V, v], axis=0)
         o = gqa_attention(q, K, V, visible=np.array([n_cached + 1]))
         h = x + o.reshape(1, self.Dq) @ _f64(self.w["w_o"]).T
-        y, idx, gate = self.ffn(h)
+        y, idx, gate, logits = self.ffn(h)
         return dict(y=y[0], K=K, V=V,
                     idx=None if idx is None else idx[0],
-                    gate=None if gate is None else gate[0])
+                    gate=None if gate is None else gate[0],
+                    logits=None if logits is None else logits[0])
 
     # -- the batch of blocks ------------------------------------------------
     def prefill(self, x, cu_seqlens, pos_offset=None, rows=None):
@@ -277,5 +284,35 @@ class Layer:
             for b in range(N):
                 y_dec[s, b] = st[b]["y"]
                 Ks[b], Vs[b] = st[b]["K"], st[b]["V"]
-            routes.append([(st[b]["idx"], st[b]["gate"]) for b in range(N)])
+            routes.append([(st[b]["idx"], st[b]["gate"], st[b]["logits"]) for b in range(N)])
+        return pre, y_dec, Ks, Vs, routes
+
+    def forward_sampled(self, x_prefill, cu_seqlens, x_decode, rows, steps, pos_offset=None):
+        """The same pass, evaluated only at sampled places (for workloads too
+        large to check everywhere).  Because the decode-step inputs are given
+        rather than generated, the K/V rows of every decode token follow from
+        x_decode alone; they are appended to each block's cache up front, and
+        attention + feed-forward are then evaluated for the prefill query rows
+        `rows[b]` and for the decode steps in `steps` (step s of block b sees
+        cache rows 0 .. L_b + s).  Returns (prefill dicts, {s: y [N, d]},
+        K list, V list, {s: (idx, gate, logits)})."""
+        pre = self.prefill(x_prefill, cu_seqlens, pos_offset, rows)
+        S, N = x_decode.shape[0], len(pre)
+        Ks, Vs, qs = [], [], []
+        for b in range(N):
+            L = pre[b]["K"].shape[0]
+            p0 = 0 if pos_offset is None else int(pos_offset[b])
+            q, k, v = self.qkv(_f64(x_decode[:, b]), p0 + L + np.arange(S))
+            Ks.append(np.concatenate([pre[b]["K"], k], axis=0))
+            Vs.append(np.concatenate([pre[b]["V"], v], axis=0))
+            qs.append(q)
+        y_dec, routes = {}, {}
+        for s in steps:
+            o = np.stack([gqa_attention(qs[b][s:s + 1], Ks[b], Vs[b],
+                                        visible=np.array([pre[b]["K"].shape[0] + s + 1]))[0]
+                          for b in range(N)])
+            h = _f64(x_decode[s]) + o.reshape(N, self.Dq) @ _f64(self.w["w_o"]).T
+            y, idx, gate, logits = self.ffn(h)
+            y_dec[s] = y
+            routes[s] = (idx, gate, logits)
         return pre, y_dec, Ks, Vs, routes

@@ -167,9 +167,11 @@ static size_t max_partial_cols(const compact_layer_cfg& c) {
     return cols;
 }
 
+static int moe_mtile(const compact_layer_cfg& c) { return c.dtype == COMPACT_BF16 ? gemm_bf16_mtile() : gemm_f32_mtile(); }
+
 static void carve_moe_plan(Carver& cv, const compact_layer_cfg& c, int64_t rows, MoePlan& plan) {
     const int64_t rk = rows * c.top_k;
-    const int mt = gemm_bf16_mtile();
+    const int mt = moe_mtile(c);
     plan.max_mtiles = (int32_t)(rk / mt + c.n_experts + 1);
     plan.counts = (int32_t*)cv.take(sizeof(int32_t) * c.n_experts);
     plan.offsets = (int32_t*)cv.take(sizeof(int32_t) * (c.n_experts + 1));
@@ -187,7 +189,7 @@ static void carve_prefill(Carver& cv, const compact_layer_cfg& c, int64_t T, Pre
     b.n = cv.take((size_t)T * c.d_model * es);  // reused for m
     b.qkv = cv.take((size_t)T * ld * es);
     b.o = cv.take((size_t)T * c.n_q_heads * c.head_dim * es);
-    b.h = cv.take((size_t)T * c.d_model * es);
+    b.h = cv.take((size_t)T * c.d_model * 4);  // the residual stream between the two halves stays fp32
     if (c.n_experts == 0) {
         b.act = cv.take((size_t)T * c.ffn_dim * es);
     } else {
@@ -370,14 +372,16 @@ static void build_decode_plan(const compact_kv* kv, int n_blocks, Plan& p) {
 // ---------------------------------------------------------------------------
 // GEMM dispatch by storage type
 // ---------------------------------------------------------------------------
-// prefill-size: C = A B^T (+R) or SwiGLU epilogue
-static int gemm_full(compact_ctx* ctx, const void* A, const void* B, const void* R, void* C, int64_t M, int N, int K,
-                     int epi, hipStream_t s) {
+// prefill-size: C = A B^T (+R) or SwiGLU epilogue.  epi 2 = fp32 output; r_f32 = fp32 residual
+// (both only matter for bf16 storage: in fp32 storage everything is fp32 anyway).
+static int gemm_full(compact_ctx* ctx, const void* A, const void* B, const void* R, bool r_f32, void* C, int64_t M,
+                     int N, int K, int epi, hipStream_t s) {
     if (ctx->cfg.dtype == COMPACT_BF16) {
         ProfileScope ps(ctx, COMPACT_K_GEMM, s);
-        return launch_gemm_bf16(ctx, (const bf16*)A, (const bf16*)B, (const bf16*)R, (bf16*)C, M, N, K, epi, nullptr, s);
+        return launch_gemm_bf16(ctx, (const bf16*)A, (const bf16*)B, R, r_f32, (bf16*)C, M, N, K, epi, nullptr, s);
     }
-    return launch_gemm_f32(ctx, (const float*)A, (const float*)B, (const float*)R, (float*)C, M, N, K, epi, s);
+    return launch_gemm_f32(ctx, (const float*)A, (const float*)B, (const float*)R, (float*)C, M, N, K, epi == 2 ? 0 : epi,
+                           nullptr, s);
 }
 
 // decode-size: fp32 split-K partials [ks][M][N]
@@ -389,7 +393,7 @@ static int gemm_partials(compact_ctx* ctx, const void* A, const void* B, float* 
         return launch_gemm_skinny(ctx, (const bf16*)A, (const bf16*)B, partials, M, N, K, *ks, s);
     }
     *ks = 1;
-    return launch_gemm_f32(ctx, (const float*)A, (const float*)B, nullptr, partials, M, N, K, 0, s);
+    return launch_gemm_f32(ctx, (const float*)A, (const float*)B, nullptr, partials, M, N, K, 0, nullptr, s);
 }
 
 #define TRY(expr)                      \
@@ -411,9 +415,9 @@ static int run_attn_prefill(compact_ctx* ctx, const Plan& p, int n_blocks, const
                                    (const float*)kv->d_v, (float*)o, s);
 }
 
-static int moe_ffn_rows(compact_ctx* ctx, const compact_weights* w, const void* m, const void* h, const int32_t* idx,
-                        const float* gate, int64_t rows, void* act, const MoePlan& plan, void* expert_out, void* y,
-                        hipStream_t s);
+static int moe_ffn_rows(compact_ctx* ctx, const compact_weights* w, const void* m, const void* h, bool h_is_f32,
+                        const int32_t* idx, const float* gate, int64_t rows, void* act, const MoePlan& plan,
+                        void* expert_out, void* y, hipStream_t s);
 
 static int prefill_impl(compact_ctx* ctx, const compact_weights* w, int n_blocks, const int32_t* cu, const void* x,
                         compact_kv* kv, void* y, void* y_last, const compact_route_out* route, void* ws, size_t ws_bytes,
@@ -427,20 +431,20 @@ static int prefill_impl(compact_ctx* ctx, const compact_weights* w, int n_blocks
     const int Dq = c.n_q_heads * c.head_dim, Dtot = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
 
     TRY(upload_plan(ctx, plan, s));
-    TRY(launch_rmsnorm(ctx, x, w->g_attn, b.n, T, s));
-    TRY(gemm_full(ctx, b.n, w->w_qkv, nullptr, b.qkv, T, Dtot, c.d_model, 0, s));
+    TRY(launch_rmsnorm(ctx, x, false, w->g_attn, b.n, T, s));
+    TRY(gemm_full(ctx, b.n, w->w_qkv, nullptr, false, b.qkv, T, Dtot, c.d_model, 0, s));
     TRY(launch_rope_kvwrite(ctx, plan.d_meta, plan.d_rope_tiles, (int)plan.rope_tiles.size(), b.qkv, kv->d_k, kv->d_v, s));
     TRY(run_attn_prefill(ctx, plan, n_blocks, b.qkv, kv, b.o, s));
-    TRY(gemm_full(ctx, b.o, w->w_o, x, b.h, T, c.d_model, Dq, 0, s));
-    TRY(launch_rmsnorm(ctx, b.h, w->g_ffn, b.n, T, s));
+    TRY(gemm_full(ctx, b.o, w->w_o, x, false, b.h, T, c.d_model, Dq, 2, s));   // h = x + o Wo^T, kept in fp32
+    TRY(launch_rmsnorm(ctx, b.h, true, w->g_ffn, b.n, T, s));
     if (c.n_experts == 0) {
-        TRY(gemm_full(ctx, b.n, w->w_gate_up, nullptr, b.act, T, c.ffn_dim, c.d_model, 1, s));
-        TRY(gemm_full(ctx, b.act, w->w_down, b.h, y, T, c.d_model, c.ffn_dim, 0, s));
+        TRY(gemm_full(ctx, b.n, w->w_gate_up, nullptr, false, b.act, T, c.ffn_dim, c.d_model, 1, s));
+        TRY(gemm_full(ctx, b.act, w->w_down, b.h, true, y, T, c.d_model, c.ffn_dim, 0, s));
     } else {
         int32_t* idx = route && route->d_expert_idx ? route->d_expert_idx : b.idx;
         float* gate = route && route->d_gate ? route->d_gate : b.gate;
         TRY(launch_moe_route(ctx, b.n, w->w_router, T, idx, gate, b.logits, s));
-        TRY(moe_ffn_rows(ctx, w, b.n, b.h, idx, gate, T, b.act, b.plan, b.expert_out, y, s));
+        TRY(moe_ffn_rows(ctx, w, b.n, b.h, true, idx, gate, T, b.act, b.plan, b.expert_out, y, s));
     }
     if (y_last) TRY(launch_gather_last_rows(ctx, plan.d_meta, n_blocks, y, y_last, s));
     return COMPACT_OK;
@@ -495,7 +499,7 @@ static int decode_impl(compact_ctx* ctx, const compact_weights* w, int n_blocks,
     const int N = n_blocks;
     const int Dq = c.n_q_heads * c.head_dim, Dtot = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
     int ks = 1;
-    TRY(launch_rmsnorm(ctx, x, w->g_attn, b.n, N, s));
+    TRY(launch_rmsnorm(ctx, x, false, w->g_attn, b.n, N, s));
     TRY(gemm_partials(ctx, b.n, w->w_qkv, b.partials, N, Dtot, c.d_model, &ks, s));
     TRY(launch_decode_qkv_epilogue(ctx, plan.d_meta, N, step, b.partials, ks, b.q, kv->d_k, kv->d_v, s));
     TRY(run_attn_decode(ctx, plan, N, step, b.q, kv, b.attn_partials, b.o, s));
@@ -507,7 +511,10 @@ static int decode_impl(compact_ctx* ctx, const compact_weights* w, int n_blocks,
         TRY(gemm_partials(ctx, b.act, w->w_down, b.partials, N, c.d_model, c.ffn_dim, &ks, s));
         TRY(launch_residual_reduce(ctx, b.partials, ks, b.h, y, N, c.d_model, s));
     } else {
-        return set_err(ctx, COMPACT_EUNSUPPORTED, "MoE decode not built yet");
+        int32_t* idx = route && route->d_expert_idx ? route->d_expert_idx : b.idx;
+        float* gate = route && route->d_gate ? route->d_gate : b.gate;
+        TRY(launch_moe_route(ctx, b.m, w->w_router, N, idx, gate, b.logits, s));
+        TRY(moe_ffn_rows(ctx, w, b.m, b.h, true, idx, gate, N, b.act, b.plan, b.expert_out, y, s));
     }
     return COMPACT_OK;
 }
@@ -587,10 +594,42 @@ extern "C" int compact_layer_forward(compact_ctx* ctx, const compact_weights* w,
 // ---------------------------------------------------------------------------
 // MoE feed-forward over rows with given routing (shared by prefill and hooks)
 // ---------------------------------------------------------------------------
-static int moe_ffn_rows(compact_ctx* ctx, const compact_weights* w, const void* m, const void* h, const int32_t* idx,
-                        const float* gate, int64_t rows, void* act, const MoePlan& plan, void* expert_out, void* y,
-                        hipStream_t s) {
-    return set_err(ctx, COMPACT_EUNSUPPORTED, "MoE feed-forward not built yet");
+static int moe_ffn_rows(compact_ctx* ctx, const compact_weights* w, const void* m, const void* h, bool h_is_f32,
+                        const int32_t* idx, const float* gate, int64_t rows, void* act, const MoePlan& plan,
+                        void* expert_out, void* y, hipStream_t s) {
+    const compact_layer_cfg& c = ctx->cfg;
+    const int64_t rk = rows * c.top_k;
+    TRY(launch_moe_plan(ctx, idx, gate, rows, moe_mtile(c), plan, s));
+    GroupedArgs g{};
+    g.tile_expert = plan.tile_expert;
+    g.tile_row0 = plan.tile_row0;
+    g.tile_rows = plan.tile_rows;
+    g.n_mtiles = plan.max_mtiles;
+    // gate/up + SwiGLU on the rows gathered per expert
+    g.a_gather = plan.sorted_token;
+    g.row_scale = nullptr;
+    g.b_expert_stride = (int64_t)2 * c.ffn_dim * c.d_model;
+    if (c.dtype == COMPACT_BF16) {
+        ProfileScope ps(ctx, COMPACT_K_GEMM, s);
+        TRY(launch_gemm_bf16(ctx, (const bf16*)m, (const bf16*)w->w_exp_gate_up, nullptr, false, (bf16*)act, rk,
+                             c.ffn_dim, c.d_model, 1, &g, s));
+    } else {
+        TRY(launch_gemm_f32(ctx, (const float*)m, (const float*)w->w_exp_gate_up, nullptr, (float*)act, rk, c.ffn_dim,
+                            c.d_model, 1, &g, s));
+    }
+    // down projection, each row scaled by its gate weight
+    g.a_gather = nullptr;
+    g.row_scale = plan.sorted_gate;
+    g.b_expert_stride = (int64_t)c.d_model * c.ffn_dim;
+    if (c.dtype == COMPACT_BF16) {
+        ProfileScope ps(ctx, COMPACT_K_GEMM, s);
+        TRY(launch_gemm_bf16(ctx, (const bf16*)act, (const bf16*)w->w_exp_down, nullptr, false, (bf16*)expert_out, rk,
+                             c.d_model, c.ffn_dim, 0, &g, s));
+    } else {
+        TRY(launch_gemm_f32(ctx, (const float*)act, (const float*)w->w_exp_down, nullptr, (float*)expert_out, rk,
+                            c.d_model, c.ffn_dim, 0, &g, s));
+    }
+    return launch_moe_combine(ctx, expert_out, h, h_is_f32, plan.slot_of, rows, y, s);
 }
 
 // ---------------------------------------------------------------------------
@@ -600,7 +639,7 @@ extern "C" int compact_rmsnorm(compact_ctx* ctx, const void* d_x, const void* d_
                                void* hip_stream) {
     if (!ctx) return COMPACT_EINVAL;
     if (!d_x || !d_g || !d_y || rows < 0) return set_err(ctx, COMPACT_EINVAL, "null pointer or negative rows");
-    return launch_rmsnorm(ctx, d_x, d_g, d_y, rows, (hipStream_t)hip_stream);
+    return launch_rmsnorm(ctx, d_x, false, d_g, d_y, rows, (hipStream_t)hip_stream);
 }
 
 extern "C" int compact_rope_kvwrite(compact_ctx* ctx, int32_t n_blocks, const int32_t* h_cu_seqlens, void* d_qkv,
@@ -641,7 +680,7 @@ extern "C" int compact_gemm(compact_ctx* ctx, const void* d_a, const void* d_b, 
         }
         return launch_skinny_finish(ctx, (const float*)d_workspace, ks, (const bf16*)d_r, (bf16*)d_c, (int)M, N, s);
     }
-    return gemm_full(ctx, d_a, d_b, d_r, d_c, M, N, K, epilogue, s);
+    return gemm_full(ctx, d_a, d_b, d_r, false, d_c, M, N, K, epilogue, s);
 }
 
 extern "C" int compact_attn_prefill(compact_ctx* ctx, int32_t n_blocks, const int32_t* h_cu_seqlens, const void* d_qkv,
@@ -711,5 +750,5 @@ extern "C" int compact_moe_ffn(compact_ctx* ctx, const compact_weights* w, const
     carve_moe_plan(cv, c, rows, plan);
     void* expert_out = cv.take((size_t)rows * c.top_k * c.d_model * es);
     if (!d_workspace || cv.off > ws_bytes) return set_err(ctx, COMPACT_EWORKSPACE, "workspace too small for the expert feed-forward");
-    return moe_ffn_rows(ctx, w, d_m, d_h, d_expert_idx, d_gate, rows, act, plan, expert_out, d_y, (hipStream_t)hip_stream);
+    return moe_ffn_rows(ctx, w, d_m, d_h, false, d_expert_idx, d_gate, rows, act, plan, expert_out, d_y, (hipStream_t)hip_stream);
 }

@@ -1,0 +1,218 @@
+// Varlen causal flash-style prefill attention (bf16 storage, MFMA).
+// Every block attends only its own tokens; the packed batch is walked through
+// a list of (block, 128-row query tile) items sorted heaviest-first.
+//
+//  * workgroup = 4 wavefronts = one query tile x one query head; wave w owns
+//    32 query rows and keeps Q^T in registers as the MFMA column operand;
+//  * K tiles [64 tok][hd] and V^T tiles [hd][64 tok] (the V slab is stored
+//    transposed, so no transposition happens here) are staged in LDS, double
+//    buffered, register-prefetched, with XOR-swizzled 16-byte chunks;
+//  * S^T = K Q^T and O^T += V^T P^T with v_mfma_f32_32x32x16_bf16.  Working
+//    on the transposed problem puts one query row in one lane column, so the
+//    online-softmax max/sum are in-lane reductions plus one cross-half
+//    shuffle, and P^T feeds the second MFMA straight from the accumulator
+//    registers: the MFMA rows of S^T are assigned to tokens such that each
+//    lane's 8 accumulator values of a k-step are 8 consecutive tokens, which
+//    is one 16-byte read of the V^T tile;
+//  * causal tiles above the diagonal are skipped per wavefront; rows of the
+//    V^T tile past the block's length are zeroed when staged.
+#include "common.h"
+
+#define KV_TILE 64
+#define LOG2E 1.4426950408889634f
+
+template <int HD>
+__global__ __launch_bounds__(256) void attn_prefill_bf16_kernel(const BlockMeta* __restrict__ meta,
+                                                                const TileItem* __restrict__ qtiles,
+                                                                const bf16* __restrict__ qkv, const bf16* __restrict__ kbase,
+                                                                const bf16* __restrict__ vbase, bf16* __restrict__ o, int Hq,
+                                                                int Hkv, float scale_log2) {
+    constexpr int KK = HD / 16;        // k16 steps of S^T
+    constexpr int DT = HD / 32;        // 32-row tiles of O^T
+    constexpr int KCH = HD / 8;        // 16-byte chunks per K row
+    constexpr int KTILE = KV_TILE * HD;   // elements of a K tile == elements of a V^T tile
+    constexpr int NLD = KTILE / 8 / 256;  // chunks per thread per tile
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    bf16* lds = reinterpret_cast<bf16*>(smem);  // [2 stages][K tile | V^T tile]
+
+    const TileItem it = qtiles[blockIdx.x];
+    const BlockMeta bm = meta[it.block];
+    const int head = blockIdx.y, kvh = head / (Hq / Hkv);
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int r = lane & 31, h = lane >> 5;
+    const int ld = (Hq + 2 * Hkv) * HD;
+    const int len = bm.len;
+
+    const bf16* kslab = kbase + bm.slab + (size_t)kvh * bm.capacity * HD;
+    const bf16* vslab = vbase + bm.slab + (size_t)kvh * HD * bm.capacity;
+
+    // ---- Q^T operand: lane (q = r, h) holds Q[q][kk*16 + h*8 .. +7] -----------
+    const int qrow = it.row0 + wave * 32 + r;         // block-local
+    const int qrow_c = min(qrow, len - 1);
+    const bf16* qp = qkv + (size_t)(bm.row0 + qrow_c) * ld + head * HD + h * 8;
+    bf16x8 qf[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16);
+
+    floatx16 oacc[DT];
+#pragma unroll
+    for (int d = 0; d < DT; ++d)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) oacc[d][e] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    const int q_hi_wg = min(it.row0 + PREFILL_QTILE, len) - 1;   // last query row of the workgroup
+    const int q_hi_wave = it.row0 + wave * 32 + 31;              // last query row of this wave
+    const int n_tiles = q_hi_wg / KV_TILE + 1;
+
+    // ---- staging ----------------------------------------------------------------
+    bf16x8 kreg[NLD], vreg[NLD];
+    auto load_tile = [&](int kt) {
+        const int kv0 = kt * KV_TILE;
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const int q = t + i * 256;
+            {   // K: row = token, KCH chunks per row
+                const int row = q / KCH, c = q % KCH;
+                const int tok = min(kv0 + row, len - 1);
+                kreg[i] = *reinterpret_cast<const bf16x8*>(kslab + (size_t)tok * HD + c * 8);
+            }
+            {   // V^T: row = head-dim index, 8 chunks of 8 tokens per row
+                const int row = q >> 3, c = q & 7;
+                const int tok = min(kv0 + c * 8, bm.capacity - 8);
+                bf16x8 v = *reinterpret_cast<const bf16x8*>(vslab + (size_t)row * bm.capacity + tok);
+                if (kv0 + KV_TILE > len) {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if (kv0 + c * 8 + j >= len) v[j] = (bf16)0.f;
+                }
+                vreg[i] = v;
+            }
+        }
+    };
+    auto store_tile = [&](int stage) {
+        bf16* ks = lds + stage * 2 * KTILE;
+        bf16* vs = ks + KTILE;
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const int q = t + i * 256;
+            {
+                const int row = q / KCH, c = q % KCH;
+                *reinterpret_cast<bf16x8*>(ks + row * HD + ((c ^ (row & 7)) << 3)) = kreg[i];
+            }
+            {
+                const int row = q >> 3, c = q & 7;
+                *reinterpret_cast<bf16x8*>(vs + row * KV_TILE + ((c ^ (row & 7)) << 3)) = vreg[i];
+            }
+        }
+    };
+
+    load_tile(0);
+    store_tile(0);
+    __syncthreads();
+
+    // token of MFMA row i of S^T tile tt: tt*32 + pi(i); pi keeps each lane's
+    // accumulator values of one k-step on 8 consecutive tokens
+    const int pi_r = (r >> 4) * 16 + ((r >> 2) & 1) * 8 + ((r >> 3) & 1) * 4 + (r & 3);
+
+    for (int kt = 0; kt < n_tiles; ++kt) {
+        const int kv0 = kt * KV_TILE;
+        const bf16* ks = lds + (kt & 1) * 2 * KTILE;
+        const bf16* vs = ks + KTILE;
+        const bool more = kt + 1 < n_tiles;
+        if (more) load_tile(kt + 1);
+
+        if (kv0 <= q_hi_wave) {   // otherwise the whole tile is above this wave's diagonal
+            // ---- S^T = K Q^T ----------------------------------------------------
+            floatx16 sacc[2];
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) sacc[tt][e] = 0.f;
+                const int row = tt * 32 + pi_r;
+                const bf16* kr = ks + row * HD;
+#pragma unroll
+                for (int kk = 0; kk < KK; ++kk) {
+                    const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kr + (((kk * 2 + h) ^ (row & 7)) << 3));
+                    sacc[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[tt], 0, 0, 0);
+                }
+            }
+            // sacc[tt][e]: query column r, token kv0 + tt*32 + (e/8)*16 + h*8 + (e%8)
+            const bool diag = kv0 + KV_TILE - 1 > it.row0 + wave * 32;   // some entry may be masked
+            float mx = -INFINITY;
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    float s = sacc[tt][e] * scale_log2;
+                    if (diag) {
+                        const int tok = kv0 + tt * 32 + (e >> 3) * 16 + h * 8 + (e & 7);
+                        if (tok > qrow) s = -INFINITY;
+                    }
+                    sacc[tt][e] = s;
+                    mx = fmaxf(mx, s);
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float m_new = fmaxf(m_run, mx);   // finite: tile 0 holds token 0 <= every query row
+            const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
+            float ps = 0.f;
+            bf16x8 pf[4];
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const float p = __builtin_amdgcn_exp2f(sacc[tt][e] - m_new);
+                    ps += p;
+                    pf[tt * 2 + (e >> 3)][e & 7] = (bf16)p;
+                }
+            l_run = l_run * corr + ps;
+            m_run = m_new;
+            // ---- O^T = corr * O^T + V^T P^T ---------------------------------------
+#pragma unroll
+            for (int d = 0; d < DT; ++d) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) oacc[d][e] *= corr;
+                const int row = d * 32 + r;
+                const bf16* vr = vs + row * KV_TILE;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {   // k-step u covers tokens u*16 .. u*16+15 of the tile
+                    const bf16x8 vf = *reinterpret_cast<const bf16x8*>(vr + (((u * 2 + h) ^ (row & 7)) << 3));
+                    oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[u], oacc[d], 0, 0, 0);
+                }
+            }
+        }
+        if (more) store_tile((kt + 1) & 1);
+        __syncthreads();
+    }
+
+    // ---- normalise and store: lane (q = r) holds elements d*32 + (e/4)*8 + h*4 + (e%4) ----
+    l_run += __shfl_xor(l_run, 32, 64);
+    if (qrow < len) {
+        const float inv = 1.0f / l_run;
+        bf16* op = o + (size_t)(bm.row0 + qrow) * Hq * HD + head * HD;
+#pragma unroll
+        for (int d = 0; d < DT; ++d)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                bf16x4 v;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = (bf16)(oacc[d][g * 4 + e] * inv);
+                *reinterpret_cast<bf16x4*>(op + d * 32 + g * 8 + h * 4) = v;
+            }
+    }
+}
+
+int launch_attn_prefill_bf16(compact_ctx* ctx, const BlockMeta* d_meta, const TileItem* d_qtiles, int n_qtiles,
+                             const bf16* qkv, const bf16* d_k, const bf16* d_v, bf16* o, hipStream_t s) {
+    if (n_qtiles == 0) return COMPACT_OK;
+    const compact_layer_cfg& c = ctx->cfg;
+    const float scale_log2 = LOG2E / sqrtf((float)c.head_dim);
+    dim3 grid(n_qtiles, c.n_q_heads);
+    const size_t smem = (size_t)2 * 2 * KV_TILE * c.head_dim * sizeof(bf16);
+    if (c.head_dim == 128)
+        attn_prefill_bf16_kernel<128><<<grid, 256, smem, s>>>(d_meta, d_qtiles, qkv, d_k, d_v, o, c.n_q_heads, c.n_kv_heads, scale_log2);
+    else
+        attn_prefill_bf16_kernel<64><<<grid, 256, smem, s>>>(d_meta, d_qtiles, qkv, d_k, d_v, o, c.n_q_heads, c.n_kv_heads, scale_log2);
+    LAUNCH_CHECK(ctx);
+    return COMPACT_OK;
+}

@@ -86,7 +86,8 @@ static inline size_t dtype_size(int dtype) { return dtype == COMPACT_BF16 ? 2 : 
 // ---------------------------------------------------------------------------
 
 // norm_rope.hip
-int launch_rmsnorm(compact_ctx* ctx, const void* x, const void* g, void* y, int64_t rows, hipStream_t s);
+// x_is_f32: the input rows are fp32 (the prefill residual stream) instead of the storage type
+int launch_rmsnorm(compact_ctx* ctx, const void* x, bool x_is_f32, const void* g, void* y, int64_t rows, hipStream_t s);
 int launch_rope_kvwrite(compact_ctx* ctx, const BlockMeta* d_meta, const TileItem* d_tiles, int n_tiles,
                         void* qkv, void* d_k, void* d_v, hipStream_t s);
 // decode: reduce ks split partials of the QKV projection, rotate, append K/V, emit q
@@ -106,11 +107,7 @@ int launch_residual_reduce(compact_ctx* ctx, const float* partials, int ks, cons
 int launch_gather_last_rows(compact_ctx* ctx, const BlockMeta* d_meta, int n_blocks, const void* y,
                             void* y_last, hipStream_t s);
 
-// gemm_f32.hip : C = A B^T (+R) ; epilogue 1 = SwiGLU on stacked gate/up
-int launch_gemm_f32(compact_ctx* ctx, const float* A, const float* B, const float* R, float* C,
-                    int64_t M, int N, int K, int epilogue, hipStream_t s);
-
-// gemm_bf16.hip
+// row-tile map of a grouped (per-expert) GEMM
 struct GroupedArgs {          // all device pointers; null tile_expert => plain GEMM
     const int32_t* tile_expert;   // [n_mtiles] expert of every row tile (-1 = no work)
     const int32_t* tile_row0;     // [n_mtiles] first row (in expert-sorted order)
@@ -120,8 +117,15 @@ struct GroupedArgs {          // all device pointers; null tile_expert => plain 
     int64_t b_expert_stride;      // elements between consecutive experts' B
     int32_t n_mtiles;
 };
-int launch_gemm_bf16(compact_ctx* ctx, const bf16* A, const bf16* B, const bf16* R, bf16* C, int64_t M,
-                     int N, int K, int epilogue, const GroupedArgs* grouped, hipStream_t s);
+// gemm_f32.hip : C = A B^T (+R) ; epilogue 1 = SwiGLU on stacked gate/up
+int launch_gemm_f32(compact_ctx* ctx, const float* A, const float* B, const float* R, float* C,
+                    int64_t M, int N, int K, int epilogue, const GroupedArgs* grouped, hipStream_t s);
+int gemm_f32_mtile();
+
+// gemm_bf16.hip
+// epilogue 0: bf16 C = acc (+R); 1: SwiGLU on stacked gate/up; 2: fp32 C = acc (+R).  R is bf16, or fp32 if r_f32.
+int launch_gemm_bf16(compact_ctx* ctx, const bf16* A, const bf16* B, const void* R, bool r_f32, bf16* C,
+                     int64_t M, int N, int K, int epilogue, const GroupedArgs* grouped, hipStream_t s);
 int gemm_bf16_mtile();
 
 // gemm_skinny.hip : partials[ks][M][N] (fp32) = A[M,K] B[N,K]^T split over K
@@ -164,5 +168,6 @@ int launch_moe_route(compact_ctx* ctx, const void* m, const void* w_router, int6
                      float* gate, float* logits, hipStream_t s);
 int launch_moe_plan(compact_ctx* ctx, const int32_t* idx, const float* gate, int64_t rows, int mtile,
                     const MoePlan& plan, hipStream_t s);
-int launch_moe_combine(compact_ctx* ctx, const void* expert_out, const void* h, const int32_t* slot_of,
-                       int64_t rows, void* y, hipStream_t s);
+// h_is_f32: the residual h is fp32 (decode) instead of the storage type
+int launch_moe_combine(compact_ctx* ctx, const void* expert_out, const void* h, bool h_is_f32,
+                       const int32_t* slot_of, int64_t rows, void* y, hipStream_t s);

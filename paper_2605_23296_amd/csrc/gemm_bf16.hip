@@ -1,0 +1,290 @@
+// bf16 MFMA GEMM for the prefill-size projections and the grouped expert
+// GEMMs:  C[M, N] = X[M, K] W[N, K]^T, fp32 accumulation, both operands
+// contiguous along K.
+//
+// Shape of the kernel (gfx950):
+//  * one workgroup = BM x BN output tile, K walked in steps of 64;
+//  * X and W tiles are staged in LDS (two stages, register-prefetched from
+//    global with 16-byte loads) in rows of 64 bf16 = 8 chunks of 16 bytes,
+//    chunk index XOR-swizzled with the row so the MFMA fragment reads
+//    (ds_read_b128, 32 rows at one k-offset) spread over all banks;
+//  * v_mfma_f32_32x32x16_bf16 with the WEIGHT rows as the 32 MFMA rows and
+//    the ACTIVATION rows as the 32 MFMA columns, so each lane ends up holding
+//    4 consecutive output columns of one output row: the epilogue stages
+//    32-row slabs in LDS as fp32 and writes 16-byte row-contiguous stores;
+//  * epilogues: 0 = plain / + residual (fp32 add before the bf16 round), 1 =
+//    SwiGLU on a stacked gate/up weight (each wave holds the gate and the up
+//    tile of the same columns), 2 = fp32 output (router logits); per-row
+//    scaling for the routed experts;
+//  * workgroup ids are remapped so that each XCD (own L2) gets a contiguous
+//    range of tiles, walked in groups of 8 row tiles per column tile.
+#include "common.h"
+
+struct GemmParams {
+    const bf16* X;
+    const bf16* W;
+    const bf16* R;
+    bf16* C;
+    int64_t M;
+    int N;  // output columns (F for the SwiGLU epilogue, whose W has 2N rows)
+    int K;
+    int n_mtiles, n_ntiles;
+    int r_f32;  // the residual R is fp32 rather than bf16
+    GroupedArgs g;
+};
+
+template <int BM, int BN, int WM, int WN, int EPI, bool GROUPED>
+__global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmParams p) {
+    constexpr int NT = WM * WN * 64, BK = 64;
+    constexpr int WTM = BM / WM, WTN = BN / WN, TM = WTM / 32, TN = WTN / 32;
+    constexpr int XCH = BM * 8 / NT, WCH = BN * 8 / NT;
+    constexpr int STAGE = (BM + BN) * BK;  // elements
+    constexpr int OUTN = EPI == 1 ? BN / 2 : BN;
+    constexpr int WOUT = EPI == 1 ? WTN / 2 : WTN;  // output columns per wave
+    static_assert(EPI != 1 || TN % 2 == 0, "SwiGLU epilogue needs an even number of column tiles per wave");
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    bf16* lds = reinterpret_cast<bf16*>(smem);
+
+    // ---- which tile -------------------------------------------------------
+    const int total = gridDim.x;
+    const int per = total / 8, rem = total % 8;
+    const int xcd = blockIdx.x % 8, loc = blockIdx.x / 8;
+    const int pid = xcd * per + min(xcd, rem) + loc;
+    constexpr int GM = 8;
+    const int per_group = GM * p.n_ntiles;
+    const int first_m = (pid / per_group) * GM;
+    const int gsize = min(GM, p.n_mtiles - first_m);
+    const int tm = first_m + (pid % per_group) % gsize;
+    const int tn = (pid % per_group) / gsize;
+
+    int64_t m0;
+    int rows_valid;
+    const bf16* Wb = p.W;
+    if (GROUPED) {
+        const int e = p.g.tile_expert[tm];
+        if (e < 0) return;
+        m0 = p.g.tile_row0[tm];
+        rows_valid = p.g.tile_rows[tm];
+        Wb += (int64_t)e * p.g.b_expert_stride;
+    } else {
+        m0 = (int64_t)tm * BM;
+        rows_valid = (int)min((int64_t)BM, p.M - m0);
+    }
+    const int n0 = tn * OUTN;
+
+    const int t = threadIdx.x;
+    const int lane = t & 63, wave = t >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int r = lane & 31, h = lane >> 5;
+
+    // ---- global -> register -> LDS staging ----------------------------------
+    const bf16* xptr[XCH];
+    const bf16* wptr[WCH];
+    int xoff[XCH], woff[WCH];
+#pragma unroll
+    for (int i = 0; i < XCH; ++i) {
+        const int q = t + i * NT, row = q >> 3, c = q & 7;
+        const int rr = min(row, rows_valid - 1);
+        int64_t src = m0 + rr;
+        if (GROUPED && p.g.a_gather) src = p.g.a_gather[src];
+        xptr[i] = p.X + src * p.K + c * 8;
+        xoff[i] = row * BK + ((c ^ (row & 7)) << 3);
+    }
+#pragma unroll
+    for (int i = 0; i < WCH; ++i) {
+        const int q = t + i * NT, row = q >> 3, c = q & 7;
+        int n;
+        if (EPI == 1)
+            n = row < BN / 2 ? min(n0 + row, p.N - 1) : p.N + min(n0 + row - BN / 2, p.N - 1);
+        else
+            n = min(n0 + row, p.N - 1);
+        wptr[i] = Wb + (int64_t)n * p.K + c * 8;
+        woff[i] = BM * BK + row * BK + ((c ^ (row & 7)) << 3);
+    }
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    bf16x8 xr[XCH], wr[WCH];
+#pragma unroll
+    for (int i = 0; i < XCH; ++i) xr[i] = *reinterpret_cast<const bf16x8*>(xptr[i]);
+#pragma unroll
+    for (int i = 0; i < WCH; ++i) wr[i] = *reinterpret_cast<const bf16x8*>(wptr[i]);
+#pragma unroll
+    for (int i = 0; i < XCH; ++i) *reinterpret_cast<bf16x8*>(lds + xoff[i]) = xr[i];
+#pragma unroll
+    for (int i = 0; i < WCH; ++i) *reinterpret_cast<bf16x8*>(lds + woff[i]) = wr[i];
+    __syncthreads();
+
+    // fragment row offsets inside a stage (elements), swizzle term r & 7
+    int xrow[TM], wrow[TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) xrow[i] = (wm * WTM + i * 32 + r) * BK;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        int row;
+        if (EPI == 1)
+            row = j < TN / 2 ? wn * (WTN / 2) + j * 32 + r : BN / 2 + wn * (WTN / 2) + (j - TN / 2) * 32 + r;
+        else
+            row = wn * WTN + j * 32 + r;
+        wrow[j] = BM * BK + row * BK;
+    }
+    const int sw = r & 7;
+
+    const int nk = p.K / BK;
+    for (int kt = 0; kt < nk; ++kt) {
+        const bf16* cur = lds + (kt & 1) * STAGE;
+        bf16* nxt = lds + ((kt + 1) & 1) * STAGE;
+        const bool more = kt + 1 < nk;
+        if (more) {
+#pragma unroll
+            for (int i = 0; i < XCH; ++i) xr[i] = *reinterpret_cast<const bf16x8*>(xptr[i] + (kt + 1) * BK);
+#pragma unroll
+            for (int i = 0; i < WCH; ++i) wr[i] = *reinterpret_cast<const bf16x8*>(wptr[i] + (kt + 1) * BK);
+        }
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const int ch = ((2 * kk + h) ^ sw) << 3;
+            bf16x8 xf[TM], wf[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) xf[i] = *reinterpret_cast<const bf16x8*>(cur + xrow[i] + ch);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) wf[j] = *reinterpret_cast<const bf16x8*>(cur + wrow[j] + ch);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], xf[i], acc[i][j], 0, 0, 0);
+        }
+        if (more) {
+#pragma unroll
+            for (int i = 0; i < XCH; ++i) *reinterpret_cast<bf16x8*>(nxt + xoff[i]) = xr[i];
+#pragma unroll
+            for (int i = 0; i < WCH; ++i) *reinterpret_cast<bf16x8*>(nxt + woff[i]) = wr[i];
+        }
+        __syncthreads();
+    }
+
+    // ---- epilogue: 32 output rows per pass through a wave-private fp32 slab ----
+    // acc[i][j][e]: output row m = wm*WTM + i*32 + r, column n = j*32 + (e/4)*8 + h*4 + (e%4)
+    constexpr int SLD = WOUT + 4;
+    float* slab = reinterpret_cast<float*>(smem) + wave * 32 * SLD;
+    constexpr int NCH = WOUT / 8;  // 8-column chunks per row
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        __syncthreads();
+        constexpr int TJ = EPI == 1 ? TN / 2 : TN;
+#pragma unroll
+        for (int j = 0; j < TJ; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                floatx4 v;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float a = acc[i][j][g * 4 + e];
+                    if (EPI == 1) {
+                        const float u = acc[i][j + TN / 2][g * 4 + e];
+                        a = a / (1.0f + __expf(-a)) * u;
+                    }
+                    v[e] = a;
+                }
+                *reinterpret_cast<floatx4*>(slab + r * SLD + j * 32 + g * 8 + h * 4) = v;
+            }
+        __syncthreads();
+        for (int q = lane; q < 32 * NCH; q += 64) {
+            const int row = q / NCH, c = q % NCH;
+            const int lm = wm * WTM + i * 32 + row;  // row inside the tile
+            const int n = n0 + wn * WOUT + c * 8;
+            if (lm >= rows_valid || n >= p.N) continue;
+            const int64_t gm = m0 + lm;
+            float v[8];
+            const floatx4 a = *reinterpret_cast<const floatx4*>(slab + row * SLD + c * 8);
+            const floatx4 b = *reinterpret_cast<const floatx4*>(slab + row * SLD + c * 8 + 4);
+            v[0] = a[0]; v[1] = a[1]; v[2] = a[2]; v[3] = a[3];
+            v[4] = b[0]; v[5] = b[1]; v[6] = b[2]; v[7] = b[3];
+            if (GROUPED && p.g.row_scale) {
+                const float sc = p.g.row_scale[gm];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] *= sc;
+            }
+            if (p.R && p.r_f32) {
+                const float* rf = reinterpret_cast<const float*>(p.R) + gm * p.N + n;
+                const floatx4 r0 = *reinterpret_cast<const floatx4*>(rf);
+                const floatx4 r1 = *reinterpret_cast<const floatx4*>(rf + 4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    v[e] += r0[e];
+                    v[4 + e] += r1[e];
+                }
+            } else if (p.R) {
+                const bf16x8 rv = *reinterpret_cast<const bf16x8*>(p.R + gm * p.N + n);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] += (float)rv[e];
+            }
+            if (EPI == 2) {   // fp32 output (router logits)
+                float* cf = reinterpret_cast<float*>(p.C) + gm * p.N + n;
+                *reinterpret_cast<floatx4*>(cf) = floatx4{v[0], v[1], v[2], v[3]};
+                *reinterpret_cast<floatx4*>(cf + 4) = floatx4{v[4], v[5], v[6], v[7]};
+            } else {
+                bf16x8 o;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] = (bf16)v[e];
+                *reinterpret_cast<bf16x8*>(p.C + gm * p.N + n) = o;
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int WM, int WN, int EPI, bool GROUPED>
+static int launch_cfg(compact_ctx* ctx, GemmParams& p, hipStream_t s) {
+    constexpr int OUTN = EPI == 1 ? BN / 2 : BN;
+    constexpr int WOUT = (EPI == 1 ? BN / 2 : BN) / WN;
+    if (!GROUPED) p.n_mtiles = (int)((p.M + BM - 1) / BM);
+    p.n_ntiles = (p.N + OUTN - 1) / OUTN;
+    const size_t stage_bytes = (size_t)2 * (BM + BN) * 64 * sizeof(bf16);
+    const size_t slab_bytes = (size_t)WM * WN * 32 * (WOUT + 4) * sizeof(float);
+    const size_t smem = std::max(stage_bytes, slab_bytes);
+    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, EPI, GROUPED>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+        attr_set = true;
+    }
+    const int64_t tiles = (int64_t)p.n_mtiles * p.n_ntiles;
+    if (tiles == 0) return COMPACT_OK;
+    kern<<<dim3((unsigned)tiles), WM * WN * 64, smem, s>>>(p);
+    LAUNCH_CHECK(ctx);
+    return COMPACT_OK;
+}
+
+// Row-tile height used for the grouped expert GEMMs.
+int gemm_bf16_mtile() { return 256; }
+
+int launch_gemm_bf16(compact_ctx* ctx, const bf16* A, const bf16* B, const void* R, bool r_f32, bf16* C, int64_t M, int N,
+                     int K, int epilogue, const GroupedArgs* grouped, hipStream_t s) {
+    if (M == 0) return COMPACT_OK;
+    if (K % 64 != 0 || N % 8 != 0) return set_err(ctx, COMPACT_ESHAPE, "bf16 GEMM needs K % 64 == 0 and N % 8 == 0");
+    GemmParams p{};
+    p.X = A;
+    p.W = B;
+    p.R = reinterpret_cast<const bf16*>(R);
+    p.r_f32 = r_f32 ? 1 : 0;
+    p.C = C;
+    p.M = M;
+    p.N = N;
+    p.K = K;
+    if (grouped) {
+        p.g = *grouped;
+        p.n_mtiles = grouped->n_mtiles;
+        if (epilogue == 1) return launch_cfg<256, 256, 2, 4, 1, true>(ctx, p, s);
+        return launch_cfg<256, 256, 2, 4, 0, true>(ctx, p, s);
+    }
+    if (epilogue == 1) return launch_cfg<256, 256, 2, 4, 1, false>(ctx, p, s);
+    if (epilogue == 2) return launch_cfg<256, 256, 2, 4, 2, false>(ctx, p, s);
+    return launch_cfg<256, 256, 2, 4, 0, false>(ctx, p, s);
+}

@@ -9,14 +9,24 @@
 #define TK 16
 
 // EPI 0: C = acc (+R).  EPI 1: B is [2N, K] (gate rows then up rows); C = silu(A Bg^T) * (A Bu^T)
+// With a GroupedArgs map, row tile blockIdx.y covers rows tile_row0 .. +tile_rows of
+// the expert-sorted order, reads A rows through a_gather and uses expert
+// tile_expert's slice of B.
 template <int EPI>
 __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__ A, const float* __restrict__ B,
                                                        const float* __restrict__ R, float* __restrict__ C, int64_t M,
-                                                       int N, int K) {
+                                                       int N, int K, const GroupedArgs g) {
     __shared__ float As[TK][TM + 4];
     __shared__ float Bs[EPI == 1 ? 2 : 1][TK][TN + 4];
     const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
-    const int64_t m0 = (int64_t)blockIdx.y * TM;
+    int64_t m0 = (int64_t)blockIdx.y * TM;
+    if (g.tile_expert) {
+        const int e = g.tile_expert[blockIdx.y];
+        if (e < 0) return;
+        m0 = g.tile_row0[blockIdx.y];
+        M = m0 + g.tile_rows[blockIdx.y];
+        B += (int64_t)e * g.b_expert_stride;
+    }
     const int n0 = blockIdx.x * TN;
     float acc[4][4] = {};
     float acc2[4][4] = {};
@@ -26,7 +36,9 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
         for (int i = threadIdx.x; i < TM * TK; i += 256) {
             const int r = i / TK, kk = i % TK;
             const int64_t gm = m0 + r;
-            As[kk][r] = (gm < M && k0 + kk < K) ? A[gm * K + k0 + kk] : 0.f;
+            float av = 0.f;
+            if (gm < M && k0 + kk < K) av = A[(g.a_gather ? (int64_t)g.a_gather[gm] : gm) * K + k0 + kk];
+            As[kk][r] = av;
             const int gn = n0 + r;
             const bool ok = gn < N && k0 + kk < K;
             Bs[0][kk][r] = ok ? B[(int64_t)gn * K + k0 + kk] : 0.f;
@@ -67,19 +79,24 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
             } else if (R != nullptr) {
                 v += R[gm * N + gn];
             }
+            if (g.row_scale) v *= g.row_scale[gm];
             C[gm * N + gn] = v;
         }
     }
 }
 
+int gemm_f32_mtile() { return TM; }
+
 int launch_gemm_f32(compact_ctx* ctx, const float* A, const float* B, const float* R, float* C, int64_t M, int N,
-                    int K, int epilogue, hipStream_t s) {
+                    int K, int epilogue, const GroupedArgs* grouped, hipStream_t s) {
     if (M == 0) return COMPACT_OK;
-    dim3 grid((N + TN - 1) / TN, (unsigned)((M + TM - 1) / TM));
+    GroupedArgs g{};
+    if (grouped) g = *grouped;
+    dim3 grid((N + TN - 1) / TN, grouped ? (unsigned)grouped->n_mtiles : (unsigned)((M + TM - 1) / TM));
     if (epilogue == 1)
-        gemm_f32_kernel<1><<<grid, 256, 0, s>>>(A, B, nullptr, C, M, N, K);
+        gemm_f32_kernel<1><<<grid, 256, 0, s>>>(A, B, nullptr, C, M, N, K, g);
     else
-        gemm_f32_kernel<0><<<grid, 256, 0, s>>>(A, B, R, C, M, N, K);
+        gemm_f32_kernel<0><<<grid, 256, 0, s>>>(A, B, R, C, M, N, K, g);
     LAUNCH_CHECK(ctx);
     return COMPACT_OK;
 }

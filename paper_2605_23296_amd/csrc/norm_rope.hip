@@ -22,11 +22,11 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
 // ---------------------------------------------------------------------------
 // y = x / sqrt(mean(x^2) + eps) * g
 // ---------------------------------------------------------------------------
-template <typename T>
-__global__ __launch_bounds__(NT) void rmsnorm_kernel(const T* __restrict__ x, const T* __restrict__ g,
+template <typename TI, typename T>
+__global__ __launch_bounds__(NT) void rmsnorm_kernel(const TI* __restrict__ x, const T* __restrict__ g,
                                                      T* __restrict__ y, int d, float eps) {
     __shared__ float red[NT / WAVE];
-    const T* xr = x + (size_t)blockIdx.x * d;
+    const TI* xr = x + (size_t)blockIdx.x * d;
     T* yr = y + (size_t)blockIdx.x * d;
     float ss = 0.f;
     for (int c = threadIdx.x * 8; c < d; c += NT * 8) {
@@ -47,13 +47,16 @@ __global__ __launch_bounds__(NT) void rmsnorm_kernel(const T* __restrict__ x, co
     }
 }
 
-int launch_rmsnorm(compact_ctx* ctx, const void* x, const void* g, void* y, int64_t rows, hipStream_t s) {
+int launch_rmsnorm(compact_ctx* ctx, const void* x, bool x_is_f32, const void* g, void* y, int64_t rows, hipStream_t s) {
     if (rows == 0) return COMPACT_OK;
     const int d = ctx->cfg.d_model;
-    if (ctx->cfg.dtype == COMPACT_BF16)
-        rmsnorm_kernel<bf16><<<dim3((unsigned)rows), NT, 0, s>>>((const bf16*)x, (const bf16*)g, (bf16*)y, d, ctx->cfg.rms_eps);
+    const dim3 grid((unsigned)rows);
+    if (ctx->cfg.dtype == COMPACT_BF16 && x_is_f32)
+        rmsnorm_kernel<float, bf16><<<grid, NT, 0, s>>>((const float*)x, (const bf16*)g, (bf16*)y, d, ctx->cfg.rms_eps);
+    else if (ctx->cfg.dtype == COMPACT_BF16)
+        rmsnorm_kernel<bf16, bf16><<<grid, NT, 0, s>>>((const bf16*)x, (const bf16*)g, (bf16*)y, d, ctx->cfg.rms_eps);
     else
-        rmsnorm_kernel<float><<<dim3((unsigned)rows), NT, 0, s>>>((const float*)x, (const float*)g, (float*)y, d, ctx->cfg.rms_eps);
+        rmsnorm_kernel<float, float><<<grid, NT, 0, s>>>((const float*)x, (const float*)g, (float*)y, d, ctx->cfg.rms_eps);
     LAUNCH_CHECK(ctx);
     return COMPACT_OK;
 }

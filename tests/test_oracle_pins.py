@@ -370,3 +370,33 @@ def test_whole_layer_against_library_routines(rng, theta):
     gu = TF.linear(m, tw["w_gate_up"])
     y = h + TF.linear(TF.silu(gu[:, :F]) * gu[:, F:], tw["w_down"])
     np.testing.assert_allclose(got, y.numpy(), atol=1e-11)
+
+
+@pytest.mark.parametrize("moe", [False, True])
+def test_sampled_forward_equals_full_forward(rng, moe):
+    cfg = small_cfg(n_experts=4, top_k=2) if moe else small_cfg()
+    lay = O.Layer(cfg, small_weights(cfg, rng))
+    lens = [6, 2, 9]
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    x = rng.standard_normal((cu[-1], cfg["d_model"]))
+    xd = rng.standard_normal((5, 3, cfg["d_model"]))
+    pos = [0, 11, 3]
+    pre, yd, Ks, Vs, routes = lay.forward(x, cu, xd, pos_offset=pos)
+    rows = [[0, 5], [1], [3, 8]]
+    spre, syd, sK, sV, sroutes = lay.forward_sampled(x, cu, xd, rows, steps=[0, 3, 4], pos_offset=pos)
+    for b in range(3):
+        np.testing.assert_allclose(spre[b]["y"], pre[b]["y"][rows[b]], atol=1e-12)
+        np.testing.assert_allclose(sK[b], Ks[b], atol=1e-13)
+        np.testing.assert_allclose(sV[b], Vs[b], atol=1e-13)
+    for s in (0, 3, 4):
+        np.testing.assert_allclose(syd[s], yd[s], atol=1e-12)
+        if moe:
+            for b in range(3):
+                assert np.array_equal(sroutes[s][0][b], routes[s][b][0])
+
+
+def test_linear_is_x_times_w_transposed(rng):
+    x = rng.standard_normal((3, 5))
+    w = rng.standard_normal((4, 5))
+    want = np.array([[sum(x[i, k] * w[j, k] for k in range(5)) for j in range(4)] for i in range(3)])
+    np.testing.assert_allclose(O.linear(x, w), want, atol=1e-14)
