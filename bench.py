@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched block-compaction layer on one MI355X.
+
+One "step" = one whole compaction pass of one layer over one batch of blocks:
+varlen prefill of every block, then S batched decode steps (compact_layer_forward).
+Workload = the dense 8B-shaped bf16 layer, a 32 k-token history cut into 8 blocks
+of 4096 tokens, 256 decoded tokens per block (synthetic seeded Gaussians).
+
+Prints ONE JSON line.  `value` is the compaction throughput in the paper's sense
+(Sec. V: decode tokens produced per second of compaction time, prefill
+included); prefill and decode rates are reported beside it, as are the
+per-kernel-class times, the roofline figure of the dominant kernel, the
+one-block-at-a-time run and the CPU checker timed on the host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2605_23296_amd import binding as B                       # noqa: E402
+from paper_2605_23296_amd.workloads import WORKLOADS, make_inputs  # noqa: E402
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def layer_params(layer):
+    d, F = layer.d_model, layer.ffn_dim
+    attn = (layer.Dq + 2 * layer.Dkv) * d + d * layer.Dq
+    if layer.n_experts == 0:
+        return attn + 3 * F * d
+    return attn + layer.n_experts * d + layer.top_k * 3 * F * d      # parameters touched per token
+
+
+def algorithmic_work(layer, lens, S):
+    """Work the method must do, per pass (each weight once per call, the causal
+    half of attention, each cached KV byte once per decode step)."""
+    T, N = sum(lens), len(lens)
+    P = layer_params(layer)
+    w = {}
+    w["gemm_flops"] = 2.0 * P * T
+    w["attn_prefill_flops"] = sum(L * (L + 1) / 2 for L in lens) * 4.0 * layer.head_dim * layer.n_q_heads
+    kv_tok = 2 * layer.Dkv * 2                                       # bytes per cached token (K and V, bf16)
+    w["attn_decode_bytes"] = float(sum(sum((L + s + 1) * kv_tok for L in lens) for s in range(S)))
+    w["skinny_bytes"] = float(S) * P * 2                             # every weight once per step
+    return w
+
+
+def run_pass(lay, inp, kv, bufs, n_steps=None):
+    S = inp.x_decode.shape[0] if n_steps is None else n_steps
+    lay.compact_layer_forward(inp.cu_seqlens, bufs["x"], bufs["xd"][:S] if S > 0 else None, kv,
+                              bufs["y_pre"], bufs["y_last"], bufs["y_dec"] if S > 0 else None)
+
+
+def timed(fn, reps):
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / reps
+
+
+def cpu_baseline(inp, n_dec=8):
+    """The fp64 checker as it stands, on the host cores: prefill of one whole
+    block and n_dec decode steps of that block, extrapolated linearly over the
+    independent blocks (exact in work, not in cache behaviour)."""
+    import numpy as np
+    from oracle import layer as O
+    from paper_2605_23296_amd.workloads import to_numpy_f64
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    lay = O.Layer(inp.layer.as_dict(), {k: to_numpy_f64(v) for k, v in inp.weights.items()})
+    L = inp.block_lens[0]
+    x = to_numpy_f64(inp.x_prefill[:L])
+    t0 = time.perf_counter()
+    pre = lay.prefill_block(x)
+    t_pre = time.perf_counter() - t0
+    K, V = pre["K"], pre["V"]
+    xd = to_numpy_f64(inp.x_decode[:n_dec, 0])
+    t0 = time.perf_counter()
+    for s in range(n_dec):
+        st = lay.decode_block(xd[s], K, V)
+        K, V = st["K"], st["V"]
+    t_dec = (time.perf_counter() - t0) / n_dec
+    N, S = len(inp.block_lens), inp.x_decode.shape[0]
+    total = N * t_pre + N * S * t_dec
+    return {
+        "value": N * S / total, "unit": "decode tokens/s (prefill time included)",
+        "cores": int(cores), "kind": "oracle",
+        "sample": "fp64 numpy checker: full prefill of 1 of %d blocks (%d tokens, %.1f s) + %d of %d decode steps of "
+                  "that block (%.3f s/step); extrapolated linearly to all blocks and steps" % (N, L, t_pre, n_dec, S, t_dec),
+        "prefill_tokens_per_s": L / t_pre, "decode_tokens_per_s": 1.0 / t_dec,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="dense_8x4096")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sequential", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (blocks are independent; sharding is a design note, "
+              "not code). Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+
+    wl = WORKLOADS[args.workload]
+    dev = "cuda"
+    inp = make_inputs(wl, device=dev, gen_device=dev)
+    layer = inp.layer
+    lens, S, N, T = inp.block_lens, inp.x_decode.shape[0], len(inp.block_lens), inp.cu_seqlens[-1]
+    lay = B.Layer(layer, inp.weights)
+    dt = lay.torch_dtype
+    kv = B.KVCache(layer, [L + S for L in lens], dev, dt)
+    lay.ensure_workspace(T, N, max(lens) + S, dev)
+    bufs = dict(x=inp.x_prefill, xd=inp.x_decode.contiguous(),
+                y_pre=torch.empty(T, layer.d_model, dtype=dt, device=dev),
+                y_last=torch.empty(N, layer.d_model, dtype=dt, device=dev),
+                y_dec=torch.empty(S, N, layer.d_model, dtype=dt, device=dev))
+
+    for _ in range(args.warmup):
+        run_pass(lay, inp, kv, bufs)
+    t_pass = timed(lambda: run_pass(lay, inp, kv, bufs), args.steps)
+
+    # split of the pass (extra, untimed for `value`): prefill-only passes
+    t_prefill = timed(lambda: run_pass(lay, inp, kv, bufs, 0), max(2, args.steps // 2))
+    t_decode = max(t_pass - t_prefill, 1e-9)
+
+    # per-kernel-class durations from HIP events on the launch stream, one class per extra pass
+    work = algorithmic_work(layer, lens, S)
+    classes = {
+        "gemm_bf16": (B.K_GEMM, "mfma", work["gemm_flops"], PEAK_BF16_TFLOPS),
+        "attn_prefill": (B.K_ATTN_PREFILL, "mfma", work["attn_prefill_flops"], PEAK_BF16_TFLOPS),
+        "attn_decode": (B.K_ATTN_DECODE, "hbm", work["attn_decode_bytes"], PEAK_HBM_GBS),
+        "gemm_skinny": (B.K_GEMM_SKINNY, "hbm", work["skinny_bytes"], PEAK_HBM_GBS),
+    }
+    kernels = {}
+    reps = max(1, min(3, args.steps))
+    for name, (klass, bound, units, peak) in classes.items():
+        lay.compact_profile_select(klass)
+        for _ in range(reps):
+            run_pass(lay, inp, kv, bufs)
+        torch.cuda.synchronize()
+        n, ms = lay.compact_profile_read()
+        lay.compact_profile_select(B.K_NONE)
+        if n == 0:
+            continue
+        per_pass_s = ms / 1e3 / reps
+        achieved = units / per_pass_s / (1e12 if bound == "mfma" else 1e9)
+        kernels[name] = dict(bound=bound, launches_per_pass=n // reps, ms_per_pass=per_pass_s * 1e3,
+                             avg_launch_us=ms * 1e3 / n, achieved=achieved, peak=peak,
+                             unit="TFLOP/s" if bound == "mfma" else "GB/s", frac=achieved / peak)
+    dom = max(kernels, key=lambda k: kernels[k]["ms_per_pass"])
+    roofline = dict(kernel=dom, bound=kernels[dom]["bound"], achieved=kernels[dom]["achieved"], peak=kernels[dom]["peak"],
+                    unit=kernels[dom]["unit"], frac=kernels[dom]["frac"], traffic=None,
+                    avg_launch_us=kernels[dom]["avg_launch_us"], launches_per_pass=kernels[dom]["launches_per_pass"])
+
+    out = {
+        "metric": "compaction_decode_tokens_per_s", "value": N * S / t_pass, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": t_pass * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": layer.dtype, "data": "synthetic",
+        "config": {"workload": "%s: %d blocks x %d tokens prefill + %d decode steps/block, d_model %d, %dq/%dkv heads x %d, "
+                               "FFN %d, one layer" % (wl.name, N, lens[0], S, layer.d_model, layer.n_q_heads,
+                                                      layer.n_kv_heads, layer.head_dim, layer.ffn_dim),
+                   "total_prefill_tokens": T, "decode_tokens": N * S},
+        "prefill_tokens_per_s": T / t_prefill, "decode_tokens_per_s": N * S / t_decode,
+        "ms_prefill": t_prefill * 1e3, "ms_decode": t_decode * 1e3, "us_per_decode_step": t_decode * 1e6 / max(S, 1),
+        "roofline": roofline, "kernels": kernels,
+    }
+
+    if not args.no_sequential:
+        # the same decode volume, one block at a time (N calls with one block each)
+        import copy
+        seq_t = seq_pre = 0.0
+        for b in range(N):
+            one = copy.copy(inp)
+            one.block_lens, one.cu_seqlens = [lens[b]], [0, lens[b]]
+            kv1 = B.KVCache(layer, [lens[b] + S], dev, dt)
+            b1 = dict(x=inp.x_prefill[inp.cu_seqlens[b]:inp.cu_seqlens[b + 1]], xd=inp.x_decode[:, b:b + 1].contiguous(),
+                      y_pre=bufs["y_pre"][:lens[b]], y_last=bufs["y_last"][:1],
+                      y_dec=torch.empty(S, 1, layer.d_model, dtype=dt, device=dev))
+            run_pass(lay, one, kv1, b1)
+            seq_t += timed(lambda: run_pass(lay, one, kv1, b1), 1)
+            seq_pre += timed(lambda: run_pass(lay, one, kv1, b1, 0), 1)
+        seq_dec = max(seq_t - seq_pre, 1e-9)
+        out["sequential_one_block_at_a_time"] = {
+            "ms_per_step": seq_t * 1e3, "value": N * S / seq_t, "batched_speedup": seq_t / t_pass,
+            "decode_tokens_per_s": N * S / seq_dec, "batched_decode_speedup": seq_dec / t_decode,
+            "prefill_tokens_per_s": T / seq_pre}
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(inp)
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
