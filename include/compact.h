@@ -60,7 +60,7 @@ enum { COMPACT_FP32 = 0, COMPACT_BF16 = 1 };
  * Rotary pairing is rotate-half: (x_i, x_{i+hd/2}) turned by pos * theta^(-2i/hd).
  * Query head h reads KV head h / (n_q_heads / n_kv_heads).
  * Constraints: head_dim in {64, 128}; n_q_heads % n_kv_heads == 0 with a
- * group of at most 16; d_model, ffn_dim multiples of 64; top_k <= 8;
+ * group of at most 16; d_model, ffn_dim multiples of 64; d_model <= 8192; top_k <= 8;
  * n_experts <= 256.                                                        */
 typedef struct compact_layer_cfg {
     int32_t d_model;

@@ -80,8 +80,8 @@ static int validate_cfg(const compact_layer_cfg* c, std::string& why) {
         why = "n_q_heads must be a multiple of n_kv_heads with a group of at most 16";
         return COMPACT_ESHAPE;
     }
-    if (c->d_model % 64 != 0 || c->ffn_dim % 64 != 0) {
-        why = "d_model and ffn_dim must be multiples of 64";
+    if (c->d_model % 64 != 0 || c->ffn_dim % 64 != 0 || c->d_model > 8192) {
+        why = "d_model and ffn_dim must be multiples of 64, d_model at most 8192";
         return COMPACT_ESHAPE;
     }
     if (c->n_experts < 0 || c->n_experts > 256) {
@@ -491,23 +491,34 @@ static int run_attn_decode(compact_ctx* ctx, const Plan& p, int n_blocks, int st
                                   (const float*)kv->d_v, (float*)o, s);
 }
 
-// one decode step for all blocks; plan.meta.len = cached tokens before step 0
+// one decode step for all blocks; plan.meta.len = cached tokens before step 0.
+// n_pre (nullable) = RMSNorm(x; g_attn) already computed for this step's rows.
 static int decode_impl(compact_ctx* ctx, const compact_weights* w, int n_blocks, int step, const void* x,
-                       compact_kv* kv, void* y, const compact_route_out* route, const DecodeBufs& b, const Plan& plan,
-                       hipStream_t s) {
+                       const void* n_pre, compact_kv* kv, void* y, const compact_route_out* route, const DecodeBufs& b,
+                       const Plan& plan, hipStream_t s) {
     const compact_layer_cfg& c = ctx->cfg;
     const int N = n_blocks;
     const int Dq = c.n_q_heads * c.head_dim, Dtot = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
     int ks = 1;
-    TRY(launch_rmsnorm(ctx, x, false, w->g_attn, b.n, N, s));
-    TRY(gemm_partials(ctx, b.n, w->w_qkv, b.partials, N, Dtot, c.d_model, &ks, s));
+    const void* n = n_pre;
+    if (!n) {
+        TRY(launch_rmsnorm(ctx, x, false, w->g_attn, b.n, N, s));
+        n = b.n;
+    }
+    TRY(gemm_partials(ctx, n, w->w_qkv, b.partials, N, Dtot, c.d_model, &ks, s));
     TRY(launch_decode_qkv_epilogue(ctx, plan.d_meta, N, step, b.partials, ks, b.q, kv->d_k, kv->d_v, s));
     TRY(run_attn_decode(ctx, plan, N, step, b.q, kv, b.attn_partials, b.o, s));
     TRY(gemm_partials(ctx, b.o, w->w_o, b.partials, N, c.d_model, Dq, &ks, s));
     TRY(launch_residual_norm(ctx, b.partials, ks, x, w->g_ffn, b.h, b.m, N, s));
     if (c.n_experts == 0) {
-        TRY(gemm_partials(ctx, b.m, w->w_gate_up, b.partials, N, 2 * c.ffn_dim, c.d_model, &ks, s));
-        TRY(launch_swiglu_reduce(ctx, b.partials, ks, b.act, N, c.ffn_dim, s));
+        if (c.dtype == COMPACT_BF16 && skinny_swiglu_supported(N, c.ffn_dim, c.d_model)) {
+            ProfileScope ps(ctx, COMPACT_K_GEMM_SKINNY, s);
+            TRY(launch_gemm_skinny_swiglu(ctx, (const bf16*)b.m, (const bf16*)w->w_gate_up, (bf16*)b.act, N, c.ffn_dim,
+                                          c.d_model, s));
+        } else {
+            TRY(gemm_partials(ctx, b.m, w->w_gate_up, b.partials, N, 2 * c.ffn_dim, c.d_model, &ks, s));
+            TRY(launch_swiglu_reduce(ctx, b.partials, ks, b.act, N, c.ffn_dim, s));
+        }
         TRY(gemm_partials(ctx, b.act, w->w_down, b.partials, N, c.d_model, c.ffn_dim, &ks, s));
         TRY(launch_residual_reduce(ctx, b.partials, ks, b.h, y, N, c.d_model, s));
     } else {
@@ -547,7 +558,7 @@ extern "C" int compact_decode_step(compact_ctx* ctx, const compact_weights* w, i
     carve_decode(cv, ctx->cfg, n_blocks, chunks_for(plan.max_len + 1), b);
     if (cv.off > ws_bytes) return set_err(ctx, COMPACT_EWORKSPACE, "workspace too small for this decode step");
     TRY(upload_plan(ctx, plan, s));
-    TRY(decode_impl(ctx, w, n_blocks, 0, d_x, kv, d_y, route, b, plan, s));
+    TRY(decode_impl(ctx, w, n_blocks, 0, d_x, nullptr, kv, d_y, route, b, plan, s));
     for (int b2 = 0; b2 < n_blocks; ++b2) kv->h_len[b2] += 1;
     return COMPACT_OK;
 }
@@ -583,9 +594,17 @@ extern "C" int compact_layer_forward(compact_ctx* ctx, const compact_weights* w,
 
     TRY(prefill_impl(ctx, w, n_blocks, h_cu_seqlens, d_x_prefill, kv, y_pre, d_y_last, nullptr, d_workspace, off, plan, s));
     const size_t row_bytes = (size_t)n_blocks * c.d_model * dtype_size(c.dtype);
+    // the step inputs are all known up front: their first RMSNorm is one launch over
+    // all S*N rows, into the prefill scratch that is dead by now (when it is large enough)
+    const char* n_all = nullptr;
+    if (n_steps > 0 && (int64_t)n_steps * n_blocks <= T) {
+        TRY(launch_rmsnorm(ctx, d_x_decode, false, w->g_attn, pb.n, (int64_t)n_steps * n_blocks, s));
+        n_all = (const char*)pb.n;
+    }
     for (int st = 0; st < n_steps; ++st) {
-        TRY(decode_impl(ctx, w, n_blocks, st, (const char*)d_x_decode + st * row_bytes, kv,
-                        (char*)d_y_decode + st * row_bytes, nullptr, db, plan, s));
+        TRY(decode_impl(ctx, w, n_blocks, st, (const char*)d_x_decode + st * row_bytes,
+                        n_all ? n_all + st * row_bytes : nullptr, kv, (char*)d_y_decode + st * row_bytes, nullptr, db,
+                        plan, s));
     }
     for (int b = 0; b < n_blocks; ++b) kv->h_len[b] = h_cu_seqlens[b + 1] - h_cu_seqlens[b] + n_steps;
     return COMPACT_OK;

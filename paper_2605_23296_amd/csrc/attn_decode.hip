@@ -60,74 +60,82 @@ __global__ __launch_bounds__(256) void attn_decode_bf16_kernel(const BlockMeta* 
     float m_run = -INFINITY, l_run = 0.f;
 
     const int w0 = c0 + wave * (DECODE_CHUNK / 4);
+    constexpr int NWIN = DECODE_CHUNK / 4 / 32;
+    // ---- all loads of the wavefront's windows are issued before any arithmetic ----
+    // S^T tile tt, MFMA row m  <->  token t0 + 8*(m/4) + 4*tt + (m%4)
+    // V^T tile d: lane (row dd = d*16 + r, c) holds tokens t0 + 8c .. +7
+    bf16x8 kf[NWIN][2][KS];
+    bf16x8 vf[NWIN][DT];
 #pragma unroll
-    for (int win = 0; win < DECODE_CHUNK / 4 / 32; ++win) {
+    for (int win = 0; win < NWIN; ++win) {
         const int t0 = w0 + win * 32;
-        if (t0 >= n_keys) break;
-        // ---- loads ----------------------------------------------------------
-        // S^T tile tt, MFMA row m  <->  token t0 + 8*(m/4) + 4*tt + (m%4)
-        bf16x8 kf[2][KS];
+        if (t0 < n_keys) {
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-            const int tok = min(t0 + 8 * (r >> 2) + 4 * tt + (r & 3), n_keys - 1);
-            const bf16* kp = kslab + (size_t)tok * HD + c * 8;
+            for (int tt = 0; tt < 2; ++tt) {
+                const int tok = min(t0 + 8 * (r >> 2) + 4 * tt + (r & 3), n_keys - 1);
+                const bf16* kp = kslab + (size_t)tok * HD + c * 8;
 #pragma unroll
-            for (int s = 0; s < KS; ++s) kf[tt][s] = *reinterpret_cast<const bf16x8*>(kp + s * 32);
-        }
-        // V^T tile d: lane (row dd = d*16 + r, c) holds tokens t0 + 8c .. +7
-        bf16x8 vf[DT];
-        const int voff = min(t0 + 8 * c, bm.capacity - 8);
-#pragma unroll
-        for (int d = 0; d < DT; ++d)
-            vf[d] = *reinterpret_cast<const bf16x8*>(vslab + (size_t)(d * 16 + r) * bm.capacity + voff);
-        if (t0 + 32 > n_keys) {  // ragged tail: rows past the cache end must not reach the MFMA
+                for (int s = 0; s < KS; ++s) kf[win][tt][s] = *reinterpret_cast<const bf16x8*>(kp + s * 32);
+            }
+            const int voff = min(t0 + 8 * c, bm.capacity - 8);
 #pragma unroll
             for (int d = 0; d < DT; ++d)
-#pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    if (t0 + 8 * c + j >= n_keys) vf[d][j] = (bf16)0.f;
+                vf[win][d] = *reinterpret_cast<const bf16x8*>(vslab + (size_t)(d * 16 + r) * bm.capacity + voff);
         }
-        // ---- S^T = K Q^T ------------------------------------------------------
-        floatx4 sacc[2];
+    }
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-            sacc[tt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int win = 0; win < NWIN; ++win) {
+        const int t0 = w0 + win * 32;
+        if (t0 < n_keys) {
+            if (t0 + 32 > n_keys) {  // ragged tail: rows past the cache end must not reach the MFMA
 #pragma unroll
-            for (int s = 0; s < KS; ++s)
-                sacc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[tt][s], qf[s], sacc[tt], 0, 0, 0);
-        }
-        // sacc[tt][e]: column g = r, token t0 + 8c + 4tt + e
-        float sv[8];
-        float mx = -INFINITY;
+                for (int d = 0; d < DT; ++d)
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int tok = t0 + 8 * c + 4 * tt + e;
-                const float s = tok < n_keys ? sacc[tt][e] * scale_log2 : -INFINITY;
-                sv[tt * 4 + e] = s;
-                mx = fmaxf(mx, s);
+                    for (int j = 0; j < 8; ++j)
+                        if (t0 + 8 * c + j >= n_keys) vf[win][d][j] = (bf16)0.f;
             }
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run, mx);  // finite: the window holds at least one valid token
-        const float corr = fast_exp2(m_run - m_new);
-        bf16x8 pf;
-        float ps = 0.f;
+            // ---- S^T = K Q^T --------------------------------------------------
+            floatx4 sacc[2];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const float p = fast_exp2(sv[j] - m_new);
-            ps += p;
-            pf[j] = (bf16)p;
-        }
-        l_run = l_run * corr + ps;
-        m_run = m_new;
-        // ---- O^T = O^T * corr + V^T P^T ---------------------------------------
+            for (int tt = 0; tt < 2; ++tt) {
+                sacc[tt] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int d = 0; d < DT; ++d) {
+                for (int s = 0; s < KS; ++s)
+                    sacc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[win][tt][s], qf[s], sacc[tt], 0, 0, 0);
+            }
+            // sacc[tt][e]: column g = r, token t0 + 8c + 4tt + e
+            float sv[8];
+            float mx = -INFINITY;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) oacc[d][e] *= corr;
-            oacc[d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[d], pf, oacc[d], 0, 0, 0);
+            for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int tok = t0 + 8 * c + 4 * tt + e;
+                    const float sc = tok < n_keys ? sacc[tt][e] * scale_log2 : -INFINITY;
+                    sv[tt * 4 + e] = sc;
+                    mx = fmaxf(mx, sc);
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float m_new = fmaxf(m_run, mx);  // finite: the window holds at least one valid token
+            const float corr = fast_exp2(m_run - m_new);
+            bf16x8 pf;
+            float ps = 0.f;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float p = fast_exp2(sv[j] - m_new);
+                ps += p;
+                pf[j] = (bf16)p;
+            }
+            l_run = l_run * corr + ps;
+            m_run = m_new;
+            // ---- O^T = O^T * corr + V^T P^T -------------------------------------
+#pragma unroll
+            for (int d = 0; d < DT; ++d) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) oacc[d][e] *= corr;
+                oacc[d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[win][d], pf, oacc[d], 0, 0, 0);
+            }
         }
     }
     // sum of p over the four lane groups of the column

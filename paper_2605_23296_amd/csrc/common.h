@@ -132,6 +132,10 @@ int gemm_bf16_mtile();
 int skinny_ksplit(int M, int N, int K);
 int launch_gemm_skinny(compact_ctx* ctx, const bf16* A, const bf16* B, float* partials, int M, int N, int K,
                        int ks, hipStream_t s);
+// decode gate/up projection with the SwiGLU fused in (no partials): act[M, F]
+bool skinny_swiglu_supported(int M, int F, int K);
+int launch_gemm_skinny_swiglu(compact_ctx* ctx, const bf16* X, const bf16* W, bf16* act, int M, int F, int K,
+                              hipStream_t s);
 // C = sum of partials (+R), rounded to bf16
 int launch_skinny_finish(compact_ctx* ctx, const float* partials, int ks, const bf16* R, bf16* C, int M, int N,
                          hipStream_t s);

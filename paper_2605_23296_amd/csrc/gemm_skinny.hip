@@ -30,31 +30,35 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16* __restrict
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16* xs = reinterpret_cast<bf16*>(smem);  // [MT*16][LDX]
     const int t = threadIdx.x;
+    const int lane = t & 63, wave = t >> 6;
     const int slice = blockIdx.y;
     const int k0 = slice * SKINNY_KSLICE;
     const int klen = min(SKINNY_KSLICE, K - k0);
+    const int nsteps = klen / 32;
+    const int r = lane & 15, c = lane >> 4;
+    const int n0 = (blockIdx.x * 4 + wave) * 16;
+    const bool active = n0 < N;
+
+    // the weight stream goes first: everything below overlaps with it
+    bf16x8 a[SKINNY_STEPS];
+    if (active) {
+        const bf16* wp = W + (size_t)(n0 + r) * K + k0 + c * 8;
+#pragma unroll
+        for (int s = 0; s < SKINNY_STEPS; ++s)
+            if (s < nsteps) a[s] = *reinterpret_cast<const bf16x8*>(wp + s * 32);
+    }
+
     const int cpr = klen / 8;  // 16-byte chunks per row
     for (int q = t; q < MT * 16 * cpr; q += 256) {
-        const int row = q / cpr, c = q - row * cpr;
+        const int row = q / cpr, cc = q - row * cpr;
         bf16x8 v;
 #pragma unroll
         for (int j = 0; j < 8; ++j) v[j] = (bf16)0.f;
-        if (row < M) v = *reinterpret_cast<const bf16x8*>(X + (size_t)row * K + k0 + c * 8);
-        *reinterpret_cast<bf16x8*>(xs + row * LDX + c * 8) = v;
+        if (row < M) v = *reinterpret_cast<const bf16x8*>(X + (size_t)row * K + k0 + cc * 8);
+        *reinterpret_cast<bf16x8*>(xs + row * LDX + cc * 8) = v;
     }
     __syncthreads();
-
-    const int lane = t & 63, wave = t >> 6;
-    const int n0 = (blockIdx.x * 4 + wave) * 16;
-    if (n0 >= N) return;
-    const int r = lane & 15, c = lane >> 4;
-    const bf16* wp = W + (size_t)(n0 + r) * K + k0 + c * 8;
-    const int nsteps = klen / 32;
-
-    bf16x8 a[SKINNY_STEPS];
-#pragma unroll
-    for (int s = 0; s < SKINNY_STEPS; ++s)
-        if (s < nsteps) a[s] = *reinterpret_cast<const bf16x8*>(wp + s * 32);
+    if (!active) return;
 
     floatx4 acc[MT];
 #pragma unroll
@@ -74,6 +78,130 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16* __restrict
     for (int mt = 0; mt < MT; ++mt) {
         const int m = mt * 16 + r;
         if (m < M) *reinterpret_cast<floatx4*>(P + ((size_t)slice * M + m) * N + n0 + 4 * c) = acc[mt];
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Gate/up projection of the decode step with the SwiGLU fused in:
+// act[M, F] = silu(X Wg^T) * (X Wu^T) for M <= MROWS activation rows.
+// A workgroup owns 16 act columns (two MFMA tiles of 8 gate + 8 up weight
+// rows) over the whole K: wavefront w streams the k-range [w K/4, (w+1) K/4)
+// of those 32 weight rows through a ring of 32 in-flight 16-byte loads per
+// lane (32 KB per wavefront); the four partial tiles are added in wavefront
+// order through LDS, then gate and up values (32 lanes apart in the
+// accumulator layout) are paired by shuffle.  No split-K partials leave the
+// kernel.  SPT = k-steps of 32 per wavefront and tile = K / 128.
+// ---------------------------------------------------------------------------
+#define SG_RING 32
+template <int MROWS, int SPT>
+__global__ __launch_bounds__(256) void gemm_skinny_swiglu_kernel(const bf16* __restrict__ X, const bf16* __restrict__ W,
+                                                                 bf16* __restrict__ act, int M, int F) {
+    constexpr int K = SPT * 128;
+    constexpr int LDX = K + 8;
+    constexpr int TOTAL = 2 * SPT;   // steps of one wavefront: tile 0 then tile 1
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    bf16* xs = reinterpret_cast<bf16*>(smem);                                          // [MROWS][LDX]
+    float* red = reinterpret_cast<float*>(smem + (size_t)MROWS * LDX * sizeof(bf16));  // [4][2][64][4]
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int r = lane & 15, c = lane >> 4;
+    const int j0 = blockIdx.x * 16;
+    const int kbeg = wave * (K / 4);
+
+    // weight row of MFMA row r in tile rt: 8 gate rows then the 8 matching up rows
+    const bf16* wrow[2];
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt) {
+        const int col = j0 + rt * 8 + (r & 7);
+        wrow[rt] = W + (size_t)(r < 8 ? col : F + col) * K + kbeg + c * 8;
+    }
+    bf16x8 ring[SG_RING];
+#pragma unroll
+    for (int i = 0; i < SG_RING && i < TOTAL; ++i)
+        ring[i] = *reinterpret_cast<const bf16x8*>(wrow[i / SPT] + (i % SPT) * 32);
+
+    // activations: all of K for the M rows
+    constexpr int CPR = K / 8;
+    for (int q = t; q < MROWS * CPR; q += 256) {
+        const int row = q / CPR, cc = q - row * CPR;
+        bf16x8 v;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = (bf16)0.f;
+        if (row < M) v = *reinterpret_cast<const bf16x8*>(X + (size_t)row * K + cc * 8);
+        *reinterpret_cast<bf16x8*>(xs + row * LDX + cc * 8) = v;
+    }
+    __syncthreads();
+
+    floatx4 acc[2] = {floatx4{0.f, 0.f, 0.f, 0.f}, floatx4{0.f, 0.f, 0.f, 0.f}};
+    const bool xvalid = r < MROWS;
+    const bf16* xrow = xs + (xvalid ? r : 0) * LDX + kbeg + c * 8;
+#pragma unroll
+    for (int i = 0; i < TOTAL; ++i) {
+        bf16x8 b = *reinterpret_cast<const bf16x8*>(xrow + (i % SPT) * 32);
+        if (MROWS < 16 && !xvalid) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) b[j] = (bf16)0.f;
+        }
+        acc[i / SPT] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[i % SG_RING], b, acc[i / SPT], 0, 0, 0);
+        if (i + SG_RING < TOTAL)
+            ring[i % SG_RING] = *reinterpret_cast<const bf16x8*>(wrow[(i + SG_RING) / SPT] + ((i + SG_RING) % SPT) * 32);
+    }
+
+    // add the four k-ranges in wavefront order
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt) *reinterpret_cast<floatx4*>(red + ((wave * 2 + rt) * 64 + lane) * 4) = acc[rt];
+    __syncthreads();
+    if (wave != 0) return;
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt) {
+        floatx4 v = *reinterpret_cast<const floatx4*>(red + ((0 * 2 + rt) * 64 + lane) * 4);
+#pragma unroll
+        for (int w = 1; w < 4; ++w) {
+            const floatx4 o = *reinterpret_cast<const floatx4*>(red + ((w * 2 + rt) * 64 + lane) * 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] += o[e];
+        }
+        // v[e]: activation row r, MFMA row 4c + e: c < 2 gate of column 4c + e, c >= 2 up of column 4(c-2) + e
+        bf16x4 out;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float up = __shfl_xor(v[e], 32, 64);
+            const float g = v[e];
+            out[e] = (bf16)(g / (1.0f + __expf(-g)) * up);
+        }
+        if (c < 2 && r < M) *reinterpret_cast<bf16x4*>(act + (size_t)r * F + j0 + rt * 8 + 4 * c) = out;
+    }
+}
+
+static size_t swiglu_smem(int mrows, int K) { return (size_t)mrows * (K + 8) * sizeof(bf16) + 4 * 2 * 64 * 4 * sizeof(float); }
+
+// whether the fused SwiGLU kernel covers this shape (K in {2048, 4096, 8192}, the LDS holds the activations)
+bool skinny_swiglu_supported(int M, int F, int K) {
+    if (M < 1 || M > 16 || F % 16 != 0) return false;
+    if (K != 2048 && K != 4096 && K != 8192) return false;
+    return swiglu_smem(M <= 8 ? 8 : 16, K) <= 160 * 1024;
+}
+
+template <int MROWS, int SPT>
+static int launch_swiglu_cfg(compact_ctx* ctx, const bf16* X, const bf16* W, bf16* act, int M, int F, hipStream_t s) {
+    const size_t smem = swiglu_smem(MROWS, SPT * 128);
+    static bool attr = false;
+    if (!attr) {
+        HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_swiglu_kernel<MROWS, SPT>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+        attr = true;
+    }
+    gemm_skinny_swiglu_kernel<MROWS, SPT><<<F / 16, 256, smem, s>>>(X, W, act, M, F);
+    LAUNCH_CHECK(ctx);
+    return COMPACT_OK;
+}
+
+int launch_gemm_skinny_swiglu(compact_ctx* ctx, const bf16* X, const bf16* W, bf16* act, int M, int F, int K, hipStream_t s) {
+    if (!skinny_swiglu_supported(M, F, K)) return set_err(ctx, COMPACT_ESHAPE, "fused gate/up decode kernel does not cover this shape");
+    const bool small = M <= 8;
+    switch (K) {
+        case 2048: return small ? launch_swiglu_cfg<8, 16>(ctx, X, W, act, M, F, s) : launch_swiglu_cfg<16, 16>(ctx, X, W, act, M, F, s);
+        case 4096: return small ? launch_swiglu_cfg<8, 32>(ctx, X, W, act, M, F, s) : launch_swiglu_cfg<16, 32>(ctx, X, W, act, M, F, s);
+        default: return launch_swiglu_cfg<8, 64>(ctx, X, W, act, M, F, s);   // K = 8192 fits 8 rows only
     }
 }
 

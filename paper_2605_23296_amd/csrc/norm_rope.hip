@@ -167,59 +167,63 @@ int launch_rope_kvwrite(compact_ctx* ctx, const BlockMeta* d_meta, const TileIte
 }
 
 // ---------------------------------------------------------------------------
-// Decode: sum the split-K partials of the QKV projection for one block's
-// token, rotate q and k at position pos_offset + len + step, write q, append
-// the K row and the V column at cache row len + step.
+// Decode row epilogues.  The weight-streaming GEMM leaves ks split-K partials
+// [ks][rows][cols] in fp32; these kernels sum them in slice order (all slice
+// loads of a thread are issued together) and apply the step that follows.
 // ---------------------------------------------------------------------------
-template <typename T>
-__global__ __launch_bounds__(NT) void decode_qkv_epilogue_kernel(const BlockMeta* __restrict__ meta, int n_rows, int step,
-                                                                 const float* __restrict__ partials, int ks,
-                                                                 T* __restrict__ q_out, T* __restrict__ kbase,
-                                                                 T* __restrict__ vbase, int Hq, int Hkv, int hd,
-                                                                 double log2_theta) {
-    __shared__ float2 cs[64];  // half <= 64
-    const int b = blockIdx.x;
-    const BlockMeta bm = meta[b];
+
+// One workgroup (one wavefront) per (head, block token): q heads and k heads are
+// rotated at position pos_offset + len + step, q goes to q_out, the K row and
+// the V column are appended at cache row len + step.
+template <typename T, int KS_UNROLL>
+__global__ __launch_bounds__(64) void decode_qkv_epilogue_kernel(const BlockMeta* __restrict__ meta, int n_rows, int step,
+                                                                const float* __restrict__ partials, int ks,
+                                                                T* __restrict__ q_out, T* __restrict__ kbase,
+                                                                T* __restrict__ vbase, int Hq, int Hkv, int hd,
+                                                                double log2_theta) {
+    const int head = blockIdx.x, b = blockIdx.y;
+    const int i = threadIdx.x;
     const int half = hd / 2;
+    if (i >= half) return;
+    const BlockMeta bm = meta[b];
     const int p = bm.len + step;
     const int ld = (Hq + 2 * Hkv) * hd;
     const size_t ps = (size_t)n_rows * ld;  // stride between split partials
-    const float* row = partials + (size_t)b * ld;
-
-    if (threadIdx.x < half) {
-        const int i = threadIdx.x;
+    const float* row = partials + (size_t)b * ld + head * hd;
+    float lo = 0.f, hi = 0.f;
+    int s = 0;
+    for (; s + KS_UNROLL <= ks; s += KS_UNROLL) {
+        float a[KS_UNROLL], c[KS_UNROLL];
+#pragma unroll
+        for (int u = 0; u < KS_UNROLL; ++u) {
+            a[u] = row[(s + u) * ps + i];
+            c[u] = row[(s + u) * ps + half + i];
+        }
+#pragma unroll
+        for (int u = 0; u < KS_UNROLL; ++u) {
+            lo += a[u];
+            hi += c[u];
+        }
+    }
+    for (; s < ks; ++s) {
+        lo += row[s * ps + i];
+        hi += row[s * ps + half + i];
+    }
+    if (head < Hq + Hkv) {
         const double inv_freq = exp2(-2.0 * (double)i / (double)hd * log2_theta);
         double sn, cn;
         sincos((double)(bm.pos_offset + p) * inv_freq, &sn, &cn);
-        cs[i] = make_float2((float)cn, (float)sn);
-    }
-    __syncthreads();
-    T* kslab = kbase + bm.slab;
-    T* vslab = vbase + bm.slab;
-    for (int idx = threadIdx.x; idx < (Hq + Hkv) * half; idx += NT) {
-        const int head = idx / half, i = idx - head * half;
-        float lo = 0.f, hi = 0.f;
-        for (int s = 0; s < ks; ++s) {
-            lo += row[s * ps + head * hd + i];
-            hi += row[s * ps + head * hd + half + i];
-        }
-        const float2 t = cs[i];
-        const float olo = lo * t.x - hi * t.y;
-        const float ohi = hi * t.x + lo * t.y;
-        if (head < Hq) {
-            T* dst = q_out + (size_t)b * Hq * hd + head * hd + i;
-            dst[0] = from_f32<T>(olo);
-            dst[half] = from_f32<T>(ohi);
-        } else {
-            T* dst = kslab + ((size_t)(head - Hq) * bm.capacity + p) * hd + i;
-            dst[0] = from_f32<T>(olo);
-            dst[half] = from_f32<T>(ohi);
-        }
-    }
-    for (int idx = threadIdx.x; idx < Hkv * hd; idx += NT) {
-        float v = 0.f;
-        for (int s = 0; s < ks; ++s) v += row[s * ps + (Hq + Hkv) * hd + idx];
-        vslab[(size_t)idx * bm.capacity + p] = from_f32<T>(v);  // idx = kvh*hd + dd
+        const float cf = (float)cn, sf = (float)sn;
+        const float olo = lo * cf - hi * sf;
+        const float ohi = hi * cf + lo * sf;
+        T* dst = head < Hq ? q_out + ((size_t)b * Hq + head) * hd + i
+                           : kbase + bm.slab + ((size_t)(head - Hq) * bm.capacity + p) * hd + i;
+        dst[0] = from_f32<T>(olo);
+        dst[half] = from_f32<T>(ohi);
+    } else {
+        T* vcol = vbase + bm.slab + (size_t)(head - Hq - Hkv) * hd * bm.capacity + p;
+        vcol[(size_t)i * bm.capacity] = from_f32<T>(lo);
+        vcol[(size_t)(i + half) * bm.capacity] = from_f32<T>(hi);
     }
 }
 
@@ -227,55 +231,90 @@ int launch_decode_qkv_epilogue(compact_ctx* ctx, const BlockMeta* d_meta, int n_
                                int ks, void* q_out, void* d_k, void* d_v, hipStream_t s) {
     const compact_layer_cfg& c = ctx->cfg;
     const double l2t = log2((double)c.rope_theta);
+    dim3 grid(c.n_q_heads + 2 * c.n_kv_heads, n_blocks);
     if (c.dtype == COMPACT_BF16)
-        decode_qkv_epilogue_kernel<bf16><<<n_blocks, NT, 0, s>>>(d_meta, n_blocks, step, partials, ks, (bf16*)q_out,
-                                                                (bf16*)d_k, (bf16*)d_v, c.n_q_heads, c.n_kv_heads,
-                                                                c.head_dim, l2t);
+        decode_qkv_epilogue_kernel<bf16, 8><<<grid, 64, 0, s>>>(d_meta, n_blocks, step, partials, ks, (bf16*)q_out,
+                                                               (bf16*)d_k, (bf16*)d_v, c.n_q_heads, c.n_kv_heads,
+                                                               c.head_dim, l2t);
     else
-        decode_qkv_epilogue_kernel<float><<<n_blocks, NT, 0, s>>>(d_meta, n_blocks, step, partials, ks, (float*)q_out,
-                                                                 (float*)d_k, (float*)d_v, c.n_q_heads, c.n_kv_heads,
-                                                                 c.head_dim, l2t);
+        decode_qkv_epilogue_kernel<float, 1><<<grid, 64, 0, s>>>(d_meta, n_blocks, step, partials, ks, (float*)q_out,
+                                                                (float*)d_k, (float*)d_v, c.n_q_heads, c.n_kv_heads,
+                                                                c.head_dim, l2t);
     LAUNCH_CHECK(ctx);
     return COMPACT_OK;
 }
 
+// sum of ks partial float4s at p, p + ps, ... in slice order, loads issued in groups of 8
+__device__ __forceinline__ float4 sum_slices4(const float* __restrict__ p, size_t ps, int ks, float4 acc) {
+    int s = 0;
+    for (; s + 8 <= ks; s += 8) {
+        float4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const float4*>(p + (s + u) * ps);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w;
+        }
+    }
+    for (; s < ks; ++s) {
+        const float4 v = *reinterpret_cast<const float4*>(p + s * ps);
+        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    return acc;
+}
+
 // ---------------------------------------------------------------------------
-// Decode: h = resid + sum_s partial_s (kept in fp32), m = RMSNorm(h; g)
+// Decode: h = resid + sum_s partial_s (kept in fp32), m = RMSNorm(h; g).
+// One workgroup per row, 4 columns per thread and trip (d <= RN_TRIPS * NT * 4 = 8192).
 // ---------------------------------------------------------------------------
+#define RN_TRIPS 8
 template <typename T>
 __global__ __launch_bounds__(NT) void residual_norm_kernel(const float* __restrict__ partials, int ks, int rows,
                                                            const T* __restrict__ resid, const T* __restrict__ g,
                                                            float* __restrict__ h_out, T* __restrict__ m_out, int d,
                                                            float eps) {
-    extern __shared__ char smem[];
-    float* hrow = reinterpret_cast<float*>(smem);  // [d]
     __shared__ float red[NT / WAVE];
     const int r = blockIdx.x;
     const size_t ps = (size_t)rows * d;
+    float4 hv[RN_TRIPS];
     float ss = 0.f;
-    for (int c = threadIdx.x; c < d; c += NT) {
-        float v = to_f32(resid[(size_t)r * d + c]);
-        for (int s = 0; s < ks; ++s) v += partials[s * ps + (size_t)r * d + c];
-        hrow[c] = v;
-        h_out[(size_t)r * d + c] = v;
-        ss += v * v;
+#pragma unroll
+    for (int it = 0; it < RN_TRIPS; ++it) {
+        const int c = (it * NT + threadIdx.x) * 4;
+        if (c < d) {
+            const T* rp = resid + (size_t)r * d + c;
+            float4 a = make_float4(to_f32(rp[0]), to_f32(rp[1]), to_f32(rp[2]), to_f32(rp[3]));
+            a = sum_slices4(partials + (size_t)r * d + c, ps, ks, a);
+            hv[it] = a;
+            *reinterpret_cast<float4*>(h_out + (size_t)r * d + c) = a;
+            ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
+        }
     }
     ss = block_sum(ss, red);
     const float inv = 1.0f / sqrtf(ss / (float)d + eps);
-    for (int c = threadIdx.x; c < d; c += NT)
-        m_out[(size_t)r * d + c] = from_f32<T>(hrow[c] * inv * to_f32(g[c]));
+#pragma unroll
+    for (int it = 0; it < RN_TRIPS; ++it) {
+        const int c = (it * NT + threadIdx.x) * 4;
+        if (c < d) {
+            T* mp = m_out + (size_t)r * d + c;
+            mp[0] = from_f32<T>(hv[it].x * inv * to_f32(g[c]));
+            mp[1] = from_f32<T>(hv[it].y * inv * to_f32(g[c + 1]));
+            mp[2] = from_f32<T>(hv[it].z * inv * to_f32(g[c + 2]));
+            mp[3] = from_f32<T>(hv[it].w * inv * to_f32(g[c + 3]));
+        }
+    }
 }
 
 int launch_residual_norm(compact_ctx* ctx, const float* partials, int ks, const void* resid, const void* g,
                          void* h_out, void* m_out, int rows, hipStream_t s) {
     const compact_layer_cfg& c = ctx->cfg;
-    const size_t smem = (size_t)c.d_model * 4;
+    if (c.d_model > RN_TRIPS * NT * 4) return set_err(ctx, COMPACT_ESHAPE, "d_model above 8192 is not supported by the decode row kernels");
     if (c.dtype == COMPACT_BF16)
-        residual_norm_kernel<bf16><<<rows, NT, smem, s>>>(partials, ks, rows, (const bf16*)resid, (const bf16*)g,
-                                                         (float*)h_out, (bf16*)m_out, c.d_model, c.rms_eps);
+        residual_norm_kernel<bf16><<<rows, NT, 0, s>>>(partials, ks, rows, (const bf16*)resid, (const bf16*)g,
+                                                      (float*)h_out, (bf16*)m_out, c.d_model, c.rms_eps);
     else
-        residual_norm_kernel<float><<<rows, NT, smem, s>>>(partials, ks, rows, (const float*)resid, (const float*)g,
-                                                          (float*)h_out, (float*)m_out, c.d_model, c.rms_eps);
+        residual_norm_kernel<float><<<rows, NT, 0, s>>>(partials, ks, rows, (const float*)resid, (const float*)g,
+                                                       (float*)h_out, (float*)m_out, c.d_model, c.rms_eps);
     LAUNCH_CHECK(ctx);
     return COMPACT_OK;
 }
@@ -311,24 +350,27 @@ int launch_swiglu_reduce(compact_ctx* ctx, const float* partials, int ks, void* 
 }
 
 // ---------------------------------------------------------------------------
-// Decode: y = resid (fp32) + sum_s partial_s
+// Decode: y = resid (fp32) + sum_s partial_s ; 4 columns per thread
 // ---------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(NT) void residual_reduce_kernel(const float* __restrict__ partials, int ks, int rows,
                                                              const float* __restrict__ resid, T* __restrict__ y,
                                                              int cols) {
-    const int r = blockIdx.y;
-    const int c = blockIdx.x * NT + threadIdx.x;
-    if (c >= cols) return;
-    const size_t ps = (size_t)rows * cols;
-    float v = resid[(size_t)r * cols + c];
-    for (int s = 0; s < ks; ++s) v += partials[s * ps + (size_t)r * cols + c];
-    y[(size_t)r * cols + c] = from_f32<T>(v);
+    const size_t i = ((size_t)blockIdx.x * NT + threadIdx.x) * 4;
+    const size_t total = (size_t)rows * cols;
+    if (i >= total) return;
+    float4 a = *reinterpret_cast<const float4*>(resid + i);
+    a = sum_slices4(partials + i, total, ks, a);
+    y[i] = from_f32<T>(a.x);
+    y[i + 1] = from_f32<T>(a.y);
+    y[i + 2] = from_f32<T>(a.z);
+    y[i + 3] = from_f32<T>(a.w);
 }
 
 int launch_residual_reduce(compact_ctx* ctx, const float* partials, int ks, const void* resid, void* y, int rows,
                            int cols, hipStream_t s) {
-    dim3 grid((cols + NT - 1) / NT, rows);
+    const size_t total = (size_t)rows * cols;  // cols is a multiple of 64
+    const unsigned grid = (unsigned)((total / 4 + NT - 1) / NT);
     if (ctx->cfg.dtype == COMPACT_BF16)
         residual_reduce_kernel<bf16><<<grid, NT, 0, s>>>(partials, ks, rows, (const float*)resid, (bf16*)y, cols);
     else
