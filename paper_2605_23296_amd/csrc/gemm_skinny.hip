@@ -31,12 +31,15 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16* __restrict
     bf16* xs = reinterpret_cast<bf16*>(smem);  // [MT*16][LDX]
     const int t = threadIdx.x;
     const int lane = t & 63, wave = t >> 6;
-    const int slice = blockIdx.y;
+    // the K-slice is the fastest grid index: workgroups that run together read
+    // neighbouring slices of the same weight rows (whole DRAM pages), not the same
+    // slice of far-apart rows
+    const int slice = blockIdx.x;
     const int k0 = slice * SKINNY_KSLICE;
     const int klen = min(SKINNY_KSLICE, K - k0);
     const int nsteps = klen / 32;
     const int r = lane & 15, c = lane >> 4;
-    const int n0 = (blockIdx.x * 4 + wave) * 16;
+    const int n0 = (blockIdx.y * 4 + wave) * 16;
     const bool active = n0 < N;
 
     // the weight stream goes first: everything below overlaps with it
@@ -84,44 +87,39 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16* __restrict
 // ---------------------------------------------------------------------------
 // Gate/up projection of the decode step with the SwiGLU fused in:
 // act[M, F] = silu(X Wg^T) * (X Wu^T) for M <= MROWS activation rows.
-// A workgroup owns 16 act columns (two MFMA tiles of 8 gate + 8 up weight
-// rows) over the whole K: wavefront w streams the k-range [w K/4, (w+1) K/4)
-// of those 32 weight rows through a ring of 32 in-flight 16-byte loads per
-// lane (32 KB per wavefront); the four partial tiles are added in wavefront
-// order through LDS, then gate and up values (32 lanes apart in the
-// accumulator layout) are paired by shuffle.  No split-K partials leave the
-// kernel.  SPT = k-steps of 32 per wavefront and tile = K / 128.
+// A workgroup (8 wavefronts) owns 16 act columns = two MFMA tiles of 8 gate +
+// 8 up weight rows, over the whole K.  Wavefront (rt, kw) streams tile rt's
+// k-steps kw, kw+4, kw+8, ... so that the four wavefronts of a tile read
+// neighbouring 64-byte pieces of the same weight rows at the same time; each
+// keeps a ring of 16 loads in flight.  The partial tiles are added in kw order
+// through LDS, then gate and up values (32 lanes apart in the accumulator
+// layout) are paired by shuffle.  No split-K partials leave the kernel.
+// SPW = k-steps of 32 per wavefront = K / 128.
 // ---------------------------------------------------------------------------
-#define SG_RING 32
-template <int MROWS, int SPT>
-__global__ __launch_bounds__(256) void gemm_skinny_swiglu_kernel(const bf16* __restrict__ X, const bf16* __restrict__ W,
+#define SG_RING 16
+template <int MROWS, int SPW>
+__global__ __launch_bounds__(512) void gemm_skinny_swiglu_kernel(const bf16* __restrict__ X, const bf16* __restrict__ W,
                                                                  bf16* __restrict__ act, int M, int F) {
-    constexpr int K = SPT * 128;
+    constexpr int K = SPW * 128;
     constexpr int LDX = K + 8;
-    constexpr int TOTAL = 2 * SPT;   // steps of one wavefront: tile 0 then tile 1
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16* xs = reinterpret_cast<bf16*>(smem);                                          // [MROWS][LDX]
-    float* red = reinterpret_cast<float*>(smem + (size_t)MROWS * LDX * sizeof(bf16));  // [4][2][64][4]
+    float* red = reinterpret_cast<float*>(smem + (size_t)MROWS * LDX * sizeof(bf16));  // [8][64][4]
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int rt = wave >> 2, kw = wave & 3;
     const int r = lane & 15, c = lane >> 4;
     const int j0 = blockIdx.x * 16;
-    const int kbeg = wave * (K / 4);
 
-    // weight row of MFMA row r in tile rt: 8 gate rows then the 8 matching up rows
-    const bf16* wrow[2];
-#pragma unroll
-    for (int rt = 0; rt < 2; ++rt) {
-        const int col = j0 + rt * 8 + (r & 7);
-        wrow[rt] = W + (size_t)(r < 8 ? col : F + col) * K + kbeg + c * 8;
-    }
+    // weight row of MFMA row r: 8 gate rows then the 8 matching up rows
+    const int col = j0 + rt * 8 + (r & 7);
+    const bf16* wrow = W + (size_t)(r < 8 ? col : F + col) * K + kw * 32 + c * 8;
     bf16x8 ring[SG_RING];
 #pragma unroll
-    for (int i = 0; i < SG_RING && i < TOTAL; ++i)
-        ring[i] = *reinterpret_cast<const bf16x8*>(wrow[i / SPT] + (i % SPT) * 32);
+    for (int i = 0; i < SG_RING && i < SPW; ++i) ring[i] = *reinterpret_cast<const bf16x8*>(wrow + i * 128);
 
     // activations: all of K for the M rows
     constexpr int CPR = K / 8;
-    for (int q = t; q < MROWS * CPR; q += 256) {
+    for (int q = t; q < MROWS * CPR; q += 512) {
         const int row = q / CPR, cc = q - row * CPR;
         bf16x8 v;
 #pragma unroll
@@ -131,48 +129,43 @@ __global__ __launch_bounds__(256) void gemm_skinny_swiglu_kernel(const bf16* __r
     }
     __syncthreads();
 
-    floatx4 acc[2] = {floatx4{0.f, 0.f, 0.f, 0.f}, floatx4{0.f, 0.f, 0.f, 0.f}};
+    floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
     const bool xvalid = r < MROWS;
-    const bf16* xrow = xs + (xvalid ? r : 0) * LDX + kbeg + c * 8;
+    const bf16* xrow = xs + (xvalid ? r : 0) * LDX + kw * 32 + c * 8;
 #pragma unroll
-    for (int i = 0; i < TOTAL; ++i) {
-        bf16x8 b = *reinterpret_cast<const bf16x8*>(xrow + (i % SPT) * 32);
+    for (int i = 0; i < SPW; ++i) {
+        bf16x8 b = *reinterpret_cast<const bf16x8*>(xrow + i * 128);
         if (MROWS < 16 && !xvalid) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) b[j] = (bf16)0.f;
         }
-        acc[i / SPT] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[i % SG_RING], b, acc[i / SPT], 0, 0, 0);
-        if (i + SG_RING < TOTAL)
-            ring[i % SG_RING] = *reinterpret_cast<const bf16x8*>(wrow[(i + SG_RING) / SPT] + ((i + SG_RING) % SPT) * 32);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[i % SG_RING], b, acc, 0, 0, 0);
+        if (i + SG_RING < SPW) ring[i % SG_RING] = *reinterpret_cast<const bf16x8*>(wrow + (i + SG_RING) * 128);
     }
 
-    // add the four k-ranges in wavefront order
-#pragma unroll
-    for (int rt = 0; rt < 2; ++rt) *reinterpret_cast<floatx4*>(red + ((wave * 2 + rt) * 64 + lane) * 4) = acc[rt];
+    // add the four k-interleaves of each tile in kw order
+    *reinterpret_cast<floatx4*>(red + (wave * 64 + lane) * 4) = acc;
     __syncthreads();
-    if (wave != 0) return;
+    if (kw != 0) return;
+    floatx4 v = acc;
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt) {
-        floatx4 v = *reinterpret_cast<const floatx4*>(red + ((0 * 2 + rt) * 64 + lane) * 4);
+    for (int w = 1; w < 4; ++w) {
+        const floatx4 o = *reinterpret_cast<const floatx4*>(red + ((rt * 4 + w) * 64 + lane) * 4);
 #pragma unroll
-        for (int w = 1; w < 4; ++w) {
-            const floatx4 o = *reinterpret_cast<const floatx4*>(red + ((w * 2 + rt) * 64 + lane) * 4);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] += o[e];
-        }
-        // v[e]: activation row r, MFMA row 4c + e: c < 2 gate of column 4c + e, c >= 2 up of column 4(c-2) + e
-        bf16x4 out;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const float up = __shfl_xor(v[e], 32, 64);
-            const float g = v[e];
-            out[e] = (bf16)(g / (1.0f + __expf(-g)) * up);
-        }
-        if (c < 2 && r < M) *reinterpret_cast<bf16x4*>(act + (size_t)r * F + j0 + rt * 8 + 4 * c) = out;
+        for (int e = 0; e < 4; ++e) v[e] += o[e];
     }
+    // v[e]: activation row r, MFMA row 4c + e: c < 2 gate of column 4c + e, c >= 2 up of column 4(c-2) + e
+    bf16x4 out;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float up = __shfl_xor(v[e], 32, 64);
+        const float g = v[e];
+        out[e] = (bf16)(g / (1.0f + __expf(-g)) * up);
+    }
+    if (c < 2 && r < M) *reinterpret_cast<bf16x4*>(act + (size_t)r * F + j0 + rt * 8 + 4 * c) = out;
 }
 
-static size_t swiglu_smem(int mrows, int K) { return (size_t)mrows * (K + 8) * sizeof(bf16) + 4 * 2 * 64 * 4 * sizeof(float); }
+static size_t swiglu_smem(int mrows, int K) { return (size_t)mrows * (K + 8) * sizeof(bf16) + 8 * 64 * 4 * sizeof(float); }
 
 // whether the fused SwiGLU kernel covers this shape (K in {2048, 4096, 8192}, the LDS holds the activations)
 bool skinny_swiglu_supported(int M, int F, int K) {
@@ -190,7 +183,7 @@ static int launch_swiglu_cfg(compact_ctx* ctx, const bf16* X, const bf16* W, bf1
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
         attr = true;
     }
-    gemm_skinny_swiglu_kernel<MROWS, SPT><<<F / 16, 256, smem, s>>>(X, W, act, M, F);
+    gemm_skinny_swiglu_kernel<MROWS, SPT><<<F / 16, 512, smem, s>>>(X, W, act, M, F);
     LAUNCH_CHECK(ctx);
     return COMPACT_OK;
 }
@@ -210,7 +203,7 @@ int launch_gemm_skinny(compact_ctx* ctx, const bf16* A, const bf16* B, float* pa
     if (M < 1 || M > 64) return set_err(ctx, COMPACT_ESHAPE, "weight-streaming GEMM takes 1..64 activation rows");
     if (N % 16 != 0 || K % 64 != 0) return set_err(ctx, COMPACT_ESHAPE, "weight-streaming GEMM needs N % 16 == 0 and K % 64 == 0");
     if (ks != skinny_ksplit(M, N, K)) return set_err(ctx, COMPACT_EINVAL, "unexpected K split");
-    dim3 grid((N + 63) / 64, ks);
+    dim3 grid(ks, (N + 63) / 64);
     const int mt = (M + 15) / 16;
     const size_t smem = (size_t)mt * 16 * (SKINNY_KSLICE + 8) * sizeof(bf16);
     switch (mt) {
