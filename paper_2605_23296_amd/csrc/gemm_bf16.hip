@@ -110,17 +110,6 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmParams
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    bf16x8 xr[XCH], wr[WCH];
-#pragma unroll
-    for (int i = 0; i < XCH; ++i) xr[i] = *reinterpret_cast<const bf16x8*>(xptr[i]);
-#pragma unroll
-    for (int i = 0; i < WCH; ++i) wr[i] = *reinterpret_cast<const bf16x8*>(wptr[i]);
-#pragma unroll
-    for (int i = 0; i < XCH; ++i) *reinterpret_cast<bf16x8*>(lds + xoff[i]) = xr[i];
-#pragma unroll
-    for (int i = 0; i < WCH; ++i) *reinterpret_cast<bf16x8*>(lds + woff[i]) = wr[i];
-    __syncthreads();
-
     // fragment row offsets inside a stage (elements), swizzle term r & 7
     int xrow[TM], wrow[TN];
 #pragma unroll
@@ -135,40 +124,72 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmParams
         wrow[j] = BM * BK + row * BK;
     }
     const int sw = r & 7;
-
     const int nk = p.K / BK;
+
+    // Software pipeline.  Global loads run two k-tiles ahead (one tile waits in
+    // registers, one in LDS); MFMA fragments are double-buffered in registers so
+    // the LDS reads of k-step kk+1 are in flight under the MFMAs of k-step kk;
+    // the one barrier per k-tile sits before the last MFMA group, whose shadow
+    // also covers the first fragment reads of the next tile.
+    bf16x8 xr[XCH], wr[WCH];
+    auto gload = [&](int kt) {
+#pragma unroll
+        for (int i = 0; i < XCH; ++i) xr[i] = *reinterpret_cast<const bf16x8*>(xptr[i] + kt * BK);
+#pragma unroll
+        for (int i = 0; i < WCH; ++i) wr[i] = *reinterpret_cast<const bf16x8*>(wptr[i] + kt * BK);
+    };
+    auto lstore = [&](bf16* stage) {
+#pragma unroll
+        for (int i = 0; i < XCH; ++i) *reinterpret_cast<bf16x8*>(stage + xoff[i]) = xr[i];
+#pragma unroll
+        for (int i = 0; i < WCH; ++i) *reinterpret_cast<bf16x8*>(stage + woff[i]) = wr[i];
+    };
+    auto frags = [&](const bf16* stage, int kk, bf16x8 (&xf)[TM], bf16x8 (&wf)[TN]) {
+        const int ch = ((2 * kk + h) ^ sw) << 3;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) xf[i] = *reinterpret_cast<const bf16x8*>(stage + xrow[i] + ch);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) wf[j] = *reinterpret_cast<const bf16x8*>(stage + wrow[j] + ch);
+    };
+    auto mfmas = [&](const bf16x8 (&xf)[TM], const bf16x8 (&wf)[TN]) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], xf[i], acc[i][j], 0, 0, 0);
+    };
+
+    gload(0);
+    lstore(lds);
+    __syncthreads();
+    if (nk > 1) gload(1);
+    bf16x8 xfA[TM], wfA[TN], xfB[TM], wfB[TN];
+    frags(lds, 0, xfA, wfA);
+
     for (int kt = 0; kt < nk; ++kt) {
         const bf16* cur = lds + (kt & 1) * STAGE;
         bf16* nxt = lds + ((kt + 1) & 1) * STAGE;
-        const bool more = kt + 1 < nk;
-        if (more) {
-#pragma unroll
-            for (int i = 0; i < XCH; ++i) xr[i] = *reinterpret_cast<const bf16x8*>(xptr[i] + (kt + 1) * BK);
-#pragma unroll
-            for (int i = 0; i < WCH; ++i) wr[i] = *reinterpret_cast<const bf16x8*>(wptr[i] + (kt + 1) * BK);
-        }
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            const int ch = ((2 * kk + h) ^ sw) << 3;
-            bf16x8 xf[TM], wf[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) xf[i] = *reinterpret_cast<const bf16x8*>(cur + xrow[i] + ch);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) wf[j] = *reinterpret_cast<const bf16x8*>(cur + wrow[j] + ch);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], xf[i], acc[i][j], 0, 0, 0);
-        }
-        if (more) {
-#pragma unroll
-            for (int i = 0; i < XCH; ++i) *reinterpret_cast<bf16x8*>(nxt + xoff[i]) = xr[i];
-#pragma unroll
-            for (int i = 0; i < WCH; ++i) *reinterpret_cast<bf16x8*>(nxt + woff[i]) = wr[i];
-        }
+        // k-step 0: next fragments, park the waiting tile in the other LDS stage
+        frags(cur, 1, xfB, wfB);
+        if (kt + 1 < nk) lstore(nxt);
+        mfmas(xfA, wfA);
+        __builtin_amdgcn_sched_barrier(0);
+        // k-step 1: next fragments, start the global loads two tiles ahead
+        frags(cur, 2, xfA, wfA);
+        if (kt + 2 < nk) gload(kt + 2);
+        mfmas(xfB, wfB);
+        __builtin_amdgcn_sched_barrier(0);
+        // k-step 2
+        frags(cur, 3, xfB, wfB);
+        mfmas(xfA, wfA);
+        __builtin_amdgcn_sched_barrier(0);
+        // k-step 3: everyone has read `cur` and written `nxt`
         __syncthreads();
+        if (kt + 1 < nk) frags(nxt, 0, xfA, wfA);
+        mfmas(xfB, wfB);
+        __builtin_amdgcn_sched_barrier(0);
     }
+    __syncthreads();
 
     // ---- epilogue: 32 output rows per pass through a wave-private fp32 slab ----
     // acc[i][j][e]: output row m = wm*WTM + i*32 + r, column n = j*32 + (e/4)*8 + h*4 + (e%4)
