@@ -52,6 +52,23 @@ def algorithmic_work(layer, lens, S):
     return w
 
 
+def recorded_traffic(workload, kernel_class):
+    """HBM bytes per launch from the committed rocprofv3 counter summary, or None
+    when there is none for this kernel class or its source changed since."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.json" % workload)
+    try:
+        rec = json.load(open(path))
+        if rec.get("kernel_class") != kernel_class:
+            return None
+        blob = b"".join(open(os.path.join(ROOT, f), "rb").read() for f in rec["sources"])
+        if hashlib.sha256(blob).hexdigest() != rec["sources_sha256"]:
+            return None
+        return rec["traffic_bytes_per_launch"]
+    except (OSError, ValueError, KeyError):
+        return None
+
+
 def run_pass(lay, inp, kv, bufs, n_steps=None):
     S = inp.x_decode.shape[0] if n_steps is None else n_steps
     lay.compact_layer_forward(inp.cu_seqlens, bufs["x"], bufs["xd"][:S] if S > 0 else None, kv,
@@ -111,6 +128,9 @@ def main():
     ap.add_argument("--workload", default="dense_8x4096")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sequential", action="store_true")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="first run one plain device copy of this many MiB (a kernel of known HBM traffic, "
+                         "used to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (blocks are independent; sharding is a design note, "
@@ -122,6 +142,12 @@ def main():
 
     wl = WORKLOADS[args.workload]
     dev = "cuda"
+    if args.copy_probe_mib > 0:
+        src = torch.ones(args.copy_probe_mib << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     inp = make_inputs(wl, device=dev, gen_device=dev)
     layer = inp.layer
     lens, S, N, T = inp.block_lens, inp.x_decode.shape[0], len(inp.block_lens), inp.cu_seqlens[-1]
@@ -168,7 +194,7 @@ def main():
                              unit="TFLOP/s" if bound == "mfma" else "GB/s", frac=achieved / peak)
     dom = max(kernels, key=lambda k: kernels[k]["ms_per_pass"])
     roofline = dict(kernel=dom, bound=kernels[dom]["bound"], achieved=kernels[dom]["achieved"], peak=kernels[dom]["peak"],
-                    unit=kernels[dom]["unit"], frac=kernels[dom]["frac"], traffic=None,
+                    unit=kernels[dom]["unit"], frac=kernels[dom]["frac"], traffic=recorded_traffic(wl.name, dom),
                     avg_launch_us=kernels[dom]["avg_launch_us"], launches_per_pass=kernels[dom]["launches_per_pass"])
 
     out = {
