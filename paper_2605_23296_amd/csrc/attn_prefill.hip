@@ -21,8 +21,22 @@
 #define KV_TILE 64
 #define LOG2E 1.4426950408889634f
 
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// eight floats to eight bf16 with four packed conversions
+__device__ __forceinline__ bf16x8 pack_bf16x8(const float (&v)[8]) {
+    union {
+        bf16x8 v8;
+        bf16x2 v2[4];
+    } u;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) u.v2[j] = __builtin_convertvector(floatx2{v[2 * j], v[2 * j + 1]}, bf16x2);
+    return u.v8;
+}
+
 template <int HD>
-__global__ __launch_bounds__(256) void attn_prefill_bf16_kernel(const BlockMeta* __restrict__ meta,
+__global__ __launch_bounds__(256, 2) void attn_prefill_bf16_kernel(const BlockMeta* __restrict__ meta,
                                                                 const TileItem* __restrict__ qtiles,
                                                                 const bf16* __restrict__ qkv, const bf16* __restrict__ kbase,
                                                                 const bf16* __restrict__ vbase, bf16* __restrict__ o, int Hq,
@@ -115,6 +129,84 @@ __global__ __launch_bounds__(256) void attn_prefill_bf16_kernel(const BlockMeta*
     // accumulator values of one k-step on 8 consecutive tokens
     const int pi_r = (r >> 4) * 16 + ((r >> 2) & 1) * 8 + ((r >> 3) & 1) * 4 + (r & 3);
 
+    // One KV tile for this wavefront.  `diag` (wavefront-uniform) is set only for
+    // tiles that straddle the wavefront's diagonal, so the tiles below it carry no
+    // compare/select.
+    auto tile_step = [&](bool diag, int kv0, const bf16* ks, const bf16* vs) {
+        // ---- S^T = K Q^T ----------------------------------------------------
+        floatx16 sacc[2];
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) sacc[tt][e] = 0.f;
+            const int row = tt * 32 + pi_r;
+            const bf16* kr = ks + row * HD;
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) {
+                const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kr + (((kk * 2 + h) ^ (row & 7)) << 3));
+                sacc[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[tt], 0, 0, 0);
+            }
+        }
+        // sacc[tt][e]: query column r, token kv0 + tt*32 + (e/8)*16 + h*8 + (e%8)
+        if (__builtin_amdgcn_readfirstlane((int)diag)) {
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int tok = kv0 + tt * 32 + (e >> 3) * 16 + h * 8 + (e & 7);
+                    if (tok > qrow) sacc[tt][e] = -INFINITY;
+                }
+        }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[tt][e]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;
+        // The running maximum is only a scaling reference: it is moved (and the
+        // accumulators rescaled) when some row's scores outgrow it by more than 2^8;
+        // until then exp2 stays within a factor 256 of 1, which fp32 sums and bf16
+        // probabilities carry without loss.  The first tile always takes this path.
+        if (__any(mx > m_run + 8.0f)) {
+            const float m_new = fmaxf(m_run, mx);   // finite: tile 0 holds token 0 <= every query row
+            const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
+            l_run *= corr;
+            m_run = m_new;
+#pragma unroll
+            for (int d = 0; d < DT; ++d)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) oacc[d][e] *= corr;
+        }
+        const float neg_m = -m_run;
+        float ps = 0.f;
+        bf16x8 pf[4];
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+            for (int g8 = 0; g8 < 2; ++g8) {
+                float pv[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    pv[j] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[tt][g8 * 8 + j], scale_log2, neg_m));
+                    ps += pv[j];
+                }
+                pf[tt * 2 + g8] = pack_bf16x8(pv);
+            }
+        l_run += ps;
+        // ---- O^T += V^T P^T ---------------------------------------------------
+#pragma unroll
+        for (int d = 0; d < DT; ++d) {
+            const int row = d * 32 + r;
+            const bf16* vr = vs + row * KV_TILE;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {   // k-step u covers tokens u*16 .. u*16+15 of the tile
+                const bf16x8 vf = *reinterpret_cast<const bf16x8*>(vr + (((u * 2 + h) ^ (row & 7)) << 3));
+                oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[u], oacc[d], 0, 0, 0);
+            }
+        }
+    };
+
+    const int q_lo_wave = it.row0 + wave * 32;   // first query row of this wave
     for (int kt = 0; kt < n_tiles; ++kt) {
         const int kv0 = kt * KV_TILE;
         const bf16* ks = lds + (kt & 1) * 2 * KTILE;
@@ -123,63 +215,7 @@ __global__ __launch_bounds__(256) void attn_prefill_bf16_kernel(const BlockMeta*
         if (more) load_tile(kt + 1);
 
         if (kv0 <= q_hi_wave) {   // otherwise the whole tile is above this wave's diagonal
-            // ---- S^T = K Q^T ----------------------------------------------------
-            floatx16 sacc[2];
-#pragma unroll
-            for (int tt = 0; tt < 2; ++tt) {
-#pragma unroll
-                for (int e = 0; e < 16; ++e) sacc[tt][e] = 0.f;
-                const int row = tt * 32 + pi_r;
-                const bf16* kr = ks + row * HD;
-#pragma unroll
-                for (int kk = 0; kk < KK; ++kk) {
-                    const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kr + (((kk * 2 + h) ^ (row & 7)) << 3));
-                    sacc[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[tt], 0, 0, 0);
-                }
-            }
-            // sacc[tt][e]: query column r, token kv0 + tt*32 + (e/8)*16 + h*8 + (e%8)
-            const bool diag = kv0 + KV_TILE - 1 > it.row0 + wave * 32;   // some entry may be masked
-            float mx = -INFINITY;
-#pragma unroll
-            for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    float s = sacc[tt][e] * scale_log2;
-                    if (diag) {
-                        const int tok = kv0 + tt * 32 + (e >> 3) * 16 + h * 8 + (e & 7);
-                        if (tok > qrow) s = -INFINITY;
-                    }
-                    sacc[tt][e] = s;
-                    mx = fmaxf(mx, s);
-                }
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m_run, mx);   // finite: tile 0 holds token 0 <= every query row
-            const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
-            float ps = 0.f;
-            bf16x8 pf[4];
-#pragma unroll
-            for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const float p = __builtin_amdgcn_exp2f(sacc[tt][e] - m_new);
-                    ps += p;
-                    pf[tt * 2 + (e >> 3)][e & 7] = (bf16)p;
-                }
-            l_run = l_run * corr + ps;
-            m_run = m_new;
-            // ---- O^T = corr * O^T + V^T P^T ---------------------------------------
-#pragma unroll
-            for (int d = 0; d < DT; ++d) {
-#pragma unroll
-                for (int e = 0; e < 16; ++e) oacc[d][e] *= corr;
-                const int row = d * 32 + r;
-                const bf16* vr = vs + row * KV_TILE;
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {   // k-step u covers tokens u*16 .. u*16+15 of the tile
-                    const bf16x8 vf = *reinterpret_cast<const bf16x8*>(vr + (((u * 2 + h) ^ (row & 7)) << 3));
-                    oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[u], oacc[d], 0, 0, 0);
-                }
-            }
+            tile_step(kv0 + KV_TILE - 1 > q_lo_wave, kv0, ks, vs);   // diag: some entry may be masked
         }
         if (more) store_tile((kt + 1) & 1);
         __syncthreads();
