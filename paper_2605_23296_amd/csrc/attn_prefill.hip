@@ -24,6 +24,12 @@
 typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
+// Chunk swizzle of K-tile row `row`.  The S^T MFMA rows are a permutation of the
+// tile's tokens in which eight neighbouring lanes read rows {0..3, 8..11} (+4,
+// +16, ...): bits 0, 1 and 3 of the row tell those eight apart, so XOR-ing the
+// 16-byte chunk index with them spreads the eight reads over all LDS banks.
+__device__ __forceinline__ int kswz(int row) { return (row & 3) | ((row >> 1) & 4); }
+
 // eight floats to eight bf16 with four packed conversions
 __device__ __forceinline__ bf16x8 pack_bf16x8(const float (&v)[8]) {
     union {
@@ -112,7 +118,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_bf16_kernel(const BlockMe
             const int q = t + i * 256;
             {
                 const int row = q / KCH, c = q % KCH;
-                *reinterpret_cast<bf16x8*>(ks + row * HD + ((c ^ (row & 7)) << 3)) = kreg[i];
+                *reinterpret_cast<bf16x8*>(ks + row * HD + ((c ^ kswz(row)) << 3)) = kreg[i];
             }
             {
                 const int row = q >> 3, c = q & 7;
@@ -143,7 +149,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_bf16_kernel(const BlockMe
             const bf16* kr = ks + row * HD;
 #pragma unroll
             for (int kk = 0; kk < KK; ++kk) {
-                const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kr + (((kk * 2 + h) ^ (row & 7)) << 3));
+                const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kr + (((kk * 2 + h) ^ kswz(row)) << 3));
                 sacc[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[tt], 0, 0, 0);
             }
         }
