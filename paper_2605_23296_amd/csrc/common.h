@@ -78,6 +78,24 @@ int set_err(compact_ctx* ctx, int code, const std::string& msg);
     } while (0)
 #define LAUNCH_CHECK(ctx) HIP_TRY(ctx, hipGetLastError())
 
+// 16-byte global load whose result goes straight into LDS: lane l of the wave
+// deposits its 16 bytes at lds_base + 16 * l (lds_base is wave-uniform); the
+// global address is per lane.  Completion is tracked by the vector-memory counter.
+__device__ __forceinline__ void load16_to_lds(const void* gptr, void* lds_base) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gptr,
+                                     (__attribute__((address_space(3))) void*)lds_base, 16, 0, 0);
+#else
+    (void)gptr;
+    (void)lds_base;
+#endif
+}
+__device__ __forceinline__ void wait_all_memory() {
+#if defined(__HIP_DEVICE_COMPILE__)
+    __builtin_amdgcn_s_waitcnt(0);
+#endif
+}
+
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static inline size_t dtype_size(int dtype) { return dtype == COMPACT_BF16 ? 2 : 4; }
 

@@ -4,10 +4,11 @@
 //
 // Shape of the kernel (gfx950):
 //  * one workgroup = BM x BN output tile, K walked in steps of 64;
-//  * X and W tiles are staged in LDS (two stages, register-prefetched from
-//    global with 16-byte loads) in rows of 64 bf16 = 8 chunks of 16 bytes,
-//    chunk index XOR-swizzled with the row so the MFMA fragment reads
-//    (ds_read_b128, 32 rows at one k-offset) spread over all banks;
+//  * X and W tiles are staged in LDS (two stages, filled by 16-byte
+//    direct-to-LDS global loads, no register hop) in rows of 64 bf16 = 8
+//    chunks of 16 bytes, chunk index XOR-swizzled with the row so the MFMA
+//    fragment reads (ds_read_b128, 32 rows at one k-offset) spread over all
+//    banks;
 //  * v_mfma_f32_32x32x16_bf16 with the WEIGHT rows as the 32 MFMA rows and
 //    the ACTIVATION rows as the 32 MFMA columns, so each lane ends up holding
 //    4 consecutive output columns of one output row: the epilogue stages
@@ -37,7 +38,6 @@ template <int BM, int BN, int WM, int WN, int EPI, bool GROUPED>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmParams p) {
     constexpr int NT = WM * WN * 64, BK = 64;
     constexpr int WTM = BM / WM, WTN = BN / WN, TM = WTM / 32, TN = WTN / 32;
-    constexpr int XCH = BM * 8 / NT, WCH = BN * 8 / NT;
     constexpr int STAGE = (BM + BN) * BK;  // elements
     constexpr int OUTN = EPI == 1 ? BN / 2 : BN;
     constexpr int WOUT = EPI == 1 ? WTN / 2 : WTN;  // output columns per wave
@@ -77,29 +77,35 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmParams
     const int wm = wave / WN, wn = wave % WN;
     const int r = lane & 31, h = lane >> 5;
 
-    // ---- global -> register -> LDS staging ----------------------------------
-    const bf16* xptr[XCH];
-    const bf16* wptr[WCH];
-    int xoff[XCH], woff[WCH];
+    // ---- global -> LDS staging (direct-to-LDS 16-byte loads) ---------------------
+    // One wave instruction fills 1 KB of LDS = 8 tile rows of 8 chunks, lane l at
+    // (row l / 8, chunk position l % 8); the position is the XOR-swizzled one, so
+    // the lane fetches global chunk (l % 8) ^ (row & 7) of its row.  The tile's
+    // BM + BN rows are dealt to the waves in units of 8 rows.
+    constexpr int XU = BM / 8 / (WM * WN), WU = BN / 8 / (WM * WN);   // units per wave
+    static_assert(BM % (8 * WM * WN) == 0 && BN % (8 * WM * WN) == 0, "tile rows must split into 8-row units per wave");
+    const bf16* xptr[XU];
+    const bf16* wptr[WU];
+    const int lrow = lane >> 3, lpos = lane & 7;
 #pragma unroll
-    for (int i = 0; i < XCH; ++i) {
-        const int q = t + i * NT, row = q >> 3, c = q & 7;
+    for (int i = 0; i < XU; ++i) {
+        const int row = (wave * XU + i) * 8 + lrow;
+        const int c = lpos ^ (row & 7);
         const int rr = min(row, rows_valid - 1);
         int64_t src = m0 + rr;
         if (GROUPED && p.g.a_gather) src = p.g.a_gather[src];
         xptr[i] = p.X + src * p.K + c * 8;
-        xoff[i] = row * BK + ((c ^ (row & 7)) << 3);
     }
 #pragma unroll
-    for (int i = 0; i < WCH; ++i) {
-        const int q = t + i * NT, row = q >> 3, c = q & 7;
+    for (int i = 0; i < WU; ++i) {
+        const int row = (wave * WU + i) * 8 + lrow;
+        const int c = lpos ^ (row & 7);
         int n;
         if (EPI == 1)
             n = row < BN / 2 ? min(n0 + row, p.N - 1) : p.N + min(n0 + row - BN / 2, p.N - 1);
         else
             n = min(n0 + row, p.N - 1);
         wptr[i] = Wb + (int64_t)n * p.K + c * 8;
-        woff[i] = BM * BK + row * BK + ((c ^ (row & 7)) << 3);
     }
 
     floatx16 acc[TM][TN];
@@ -126,23 +132,19 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmParams
     const int sw = r & 7;
     const int nk = p.K / BK;
 
-    // Software pipeline.  Global loads run two k-tiles ahead (one tile waits in
-    // registers, one in LDS); MFMA fragments are double-buffered in registers so
-    // the LDS reads of k-step kk+1 are in flight under the MFMAs of k-step kk;
-    // the one barrier per k-tile sits before the last MFMA group, whose shadow
-    // also covers the first fragment reads of the next tile.
-    bf16x8 xr[XCH], wr[WCH];
-    auto gload = [&](int kt) {
+    // Software pipeline.  The loads of k-tile kt+1 go straight into the other
+    // LDS stage while k-tile kt is multiplied; MFMA fragments are double-buffered
+    // in registers so the LDS reads of k-step kk+1 are in flight under the MFMAs
+    // of k-step kk; the one barrier per k-tile (after this wave's loads have
+    // landed) sits before the last MFMA group, whose shadow also covers the first
+    // fragment reads of the next tile.
+    auto gload = [&](int kt, bf16* stage) {
 #pragma unroll
-        for (int i = 0; i < XCH; ++i) xr[i] = *reinterpret_cast<const bf16x8*>(xptr[i] + kt * BK);
+        for (int i = 0; i < XU; ++i)
+            load16_to_lds(xptr[i] + kt * BK, stage + (wave * XU + i) * 8 * BK);
 #pragma unroll
-        for (int i = 0; i < WCH; ++i) wr[i] = *reinterpret_cast<const bf16x8*>(wptr[i] + kt * BK);
-    };
-    auto lstore = [&](bf16* stage) {
-#pragma unroll
-        for (int i = 0; i < XCH; ++i) *reinterpret_cast<bf16x8*>(stage + xoff[i]) = xr[i];
-#pragma unroll
-        for (int i = 0; i < WCH; ++i) *reinterpret_cast<bf16x8*>(stage + woff[i]) = wr[i];
+        for (int i = 0; i < WU; ++i)
+            load16_to_lds(wptr[i] + kt * BK, stage + BM * BK + (wave * WU + i) * 8 * BK);
     };
     auto frags = [&](const bf16* stage, int kk, bf16x8 (&xf)[TM], bf16x8 (&wf)[TN]) {
         const int ch = ((2 * kk + h) ^ sw) << 3;
@@ -159,31 +161,45 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmParams
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], xf[i], acc[i][j], 0, 0, 0);
     };
 
-    gload(0);
-    lstore(lds);
+    // Pins the instruction order of one k-step: the LDS reads of the next k-step's
+    // fragments go out two per MFMA at the start of the group, so the last of them
+    // still has most of the group (not one MFMA) to land before it is needed.
+    constexpr int NRD = TM + TN, NMF = TM * TN;
+    static_assert(NRD % 2 == 0 && NMF >= NRD / 2, "k-step shape not covered by the pinned order");
+    auto pin_order = [&]() {
+#pragma unroll
+        for (int i = 0; i < NRD / 2; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // two LDS reads
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, NMF - NRD / 2, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    gload(0, lds);
+    wait_all_memory();
     __syncthreads();
-    if (nk > 1) gload(1);
     bf16x8 xfA[TM], wfA[TN], xfB[TM], wfB[TN];
     frags(lds, 0, xfA, wfA);
 
     for (int kt = 0; kt < nk; ++kt) {
         const bf16* cur = lds + (kt & 1) * STAGE;
         bf16* nxt = lds + ((kt + 1) & 1) * STAGE;
-        // k-step 0: next fragments, park the waiting tile in the other LDS stage
+        // k-step 0: start the next tile's loads, next fragments
+        if (kt + 1 < nk) gload(kt + 1, nxt);
         frags(cur, 1, xfB, wfB);
-        if (kt + 1 < nk) lstore(nxt);
         mfmas(xfA, wfA);
-        __builtin_amdgcn_sched_barrier(0);
-        // k-step 1: next fragments, start the global loads two tiles ahead
+        pin_order();
+        // k-step 1
         frags(cur, 2, xfA, wfA);
-        if (kt + 2 < nk) gload(kt + 2);
         mfmas(xfB, wfB);
-        __builtin_amdgcn_sched_barrier(0);
+        pin_order();
         // k-step 2
         frags(cur, 3, xfB, wfB);
         mfmas(xfA, wfA);
-        __builtin_amdgcn_sched_barrier(0);
-        // k-step 3: everyone has read `cur` and written `nxt`
+        pin_order();
+        // k-step 3: everyone has read `cur` and filled `nxt`
+        wait_all_memory();
         __syncthreads();
         if (kt + 1 < nk) frags(nxt, 0, xfA, wfA);
         mfmas(xfB, wfB);
