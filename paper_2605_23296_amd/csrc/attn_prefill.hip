@@ -24,11 +24,15 @@
 typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
-// Chunk swizzle of K-tile row `row`.  The S^T MFMA rows are a permutation of the
-// tile's tokens in which eight neighbouring lanes read rows {0..3, 8..11} (+4,
-// +16, ...): bits 0, 1 and 3 of the row tell those eight apart, so XOR-ing the
-// 16-byte chunk index with them spreads the eight reads over all LDS banks.
-__device__ __forceinline__ int kswz(int row) { return (row & 3) | ((row >> 1) & 4); }
+// Chunk swizzles.  The LDS has 64 banks of 4 bytes (256 bytes per cycle) and a
+// 16-byte read is served 16 lanes at a time, so the 16 lanes must land in 16
+// different 16-byte bank groups.  K-tile rows of 256 bytes (16 chunks) cover all
+// groups by themselves: the 16 lanes read 16 different rows (a permutation of
+// 0..15, +16), so the chunk index is XOR-ed with row % 16.  Rows of 128 bytes (8
+// chunks: K at head_dim 64, every V^T tile) fill the banks two rows at a time:
+// the chunk index is XOR-ed with (row / 2) % 8.
+template <int CHUNKS>
+__device__ __forceinline__ int swz(int row) { return CHUNKS == 16 ? (row & 15) : ((row >> 1) & 7); }
 
 // eight floats to eight bf16 with four packed conversions
 __device__ __forceinline__ bf16x8 pack_bf16x8(const float (&v)[8]) {
@@ -118,11 +122,11 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_bf16_kernel(const BlockMe
             const int q = t + i * 256;
             {
                 const int row = q / KCH, c = q % KCH;
-                *reinterpret_cast<bf16x8*>(ks + row * HD + ((c ^ kswz(row)) << 3)) = kreg[i];
+                *reinterpret_cast<bf16x8*>(ks + row * HD + ((c ^ swz<KCH>(row)) << 3)) = kreg[i];
             }
             {
                 const int row = q >> 3, c = q & 7;
-                *reinterpret_cast<bf16x8*>(vs + row * KV_TILE + ((c ^ (row & 7)) << 3)) = vreg[i];
+                *reinterpret_cast<bf16x8*>(vs + row * KV_TILE + ((c ^ swz<8>(row)) << 3)) = vreg[i];
             }
         }
     };
@@ -149,7 +153,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_bf16_kernel(const BlockMe
             const bf16* kr = ks + row * HD;
 #pragma unroll
             for (int kk = 0; kk < KK; ++kk) {
-                const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kr + (((kk * 2 + h) ^ kswz(row)) << 3));
+                const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kr + (((kk * 2 + h) ^ swz<KCH>(row)) << 3));
                 sacc[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[tt], 0, 0, 0);
             }
         }
@@ -206,7 +210,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_bf16_kernel(const BlockMe
             const bf16* vr = vs + row * KV_TILE;
 #pragma unroll
             for (int u = 0; u < 4; ++u) {   // k-step u covers tokens u*16 .. u*16+15 of the tile
-                const bf16x8 vf = *reinterpret_cast<const bf16x8*>(vr + (((u * 2 + h) ^ (row & 7)) << 3));
+                const bf16x8 vf = *reinterpret_cast<const bf16x8*>(vr + (((u * 2 + h) ^ swz<8>(row)) << 3));
                 oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[u], oacc[d], 0, 0, 0);
             }
         }

@@ -6,9 +6,10 @@
 //  * one workgroup = BM x BN output tile, K walked in steps of 64;
 //  * X and W tiles are staged in LDS (two stages, filled by 16-byte
 //    direct-to-LDS global loads, no register hop) in rows of 64 bf16 = 8
-//    chunks of 16 bytes, chunk index XOR-swizzled with the row so the MFMA
-//    fragment reads (ds_read_b128, 32 rows at one k-offset) spread over all
-//    banks;
+//    chunks of 16 bytes, chunk index XOR-ed with (row / 2) % 8: the LDS has 64
+//    banks of 4 bytes, so two 128-byte rows fill them once, and 16 lanes reading
+//    16 consecutive rows at one k-offset (an MFMA fragment read, ds_read_b128)
+//    touch 16 different 16-byte bank groups;
 //  * v_mfma_f32_32x32x16_bf16 with the WEIGHT rows as the 32 MFMA rows and
 //    the ACTIVATION rows as the 32 MFMA columns, so each lane ends up holding
 //    4 consecutive output columns of one output row: the epilogue stages
@@ -80,7 +81,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmParams
     // ---- global -> LDS staging (direct-to-LDS 16-byte loads) ---------------------
     // One wave instruction fills 1 KB of LDS = 8 tile rows of 8 chunks, lane l at
     // (row l / 8, chunk position l % 8); the position is the XOR-swizzled one, so
-    // the lane fetches global chunk (l % 8) ^ (row & 7) of its row.  The tile's
+    // the lane fetches global chunk (l % 8) ^ ((row >> 1) & 7) of its row.  The tile's
     // BM + BN rows are dealt to the waves in units of 8 rows.
     constexpr int XU = BM / 8 / (WM * WN), WU = BN / 8 / (WM * WN);   // units per wave
     static_assert(BM % (8 * WM * WN) == 0 && BN % (8 * WM * WN) == 0, "tile rows must split into 8-row units per wave");
@@ -90,7 +91,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmParams
 #pragma unroll
     for (int i = 0; i < XU; ++i) {
         const int row = (wave * XU + i) * 8 + lrow;
-        const int c = lpos ^ (row & 7);
+        const int c = lpos ^ ((row >> 1) & 7);
         const int rr = min(row, rows_valid - 1);
         int64_t src = m0 + rr;
         if (GROUPED && p.g.a_gather) src = p.g.a_gather[src];
@@ -99,7 +100,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmParams
 #pragma unroll
     for (int i = 0; i < WU; ++i) {
         const int row = (wave * WU + i) * 8 + lrow;
-        const int c = lpos ^ (row & 7);
+        const int c = lpos ^ ((row >> 1) & 7);
         int n;
         if (EPI == 1)
             n = row < BN / 2 ? min(n0 + row, p.N - 1) : p.N + min(n0 + row - BN / 2, p.N - 1);
@@ -116,7 +117,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmParams
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    // fragment row offsets inside a stage (elements), swizzle term r & 7
+    // fragment row offsets inside a stage (elements), swizzle term (r / 2) % 8
     int xrow[TM], wrow[TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i) xrow[i] = (wm * WTM + i * 32 + r) * BK;
@@ -129,7 +130,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmParams
             row = wn * WTN + j * 32 + r;
         wrow[j] = BM * BK + row * BK;
     }
-    const int sw = r & 7;
+    const int sw = (r >> 1) & 7;
     const int nk = p.K / BK;
 
     // Software pipeline.  The loads of k-tile kt+1 go straight into the other
