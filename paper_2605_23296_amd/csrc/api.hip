@@ -152,6 +152,8 @@ struct PrefillBufs {
 
 struct DecodeBufs {
     void *n, *q, *o, *m, *act;
+    void* hg;          // bf16(h * g_ffn): the FFN input before its 1/rms factor
+    float* ssq_parts;  // [d_model / 16][N] column-group sums of squares of h
     float *h, *partials, *attn_partials;
     float* logits;
     int32_t* idx;
@@ -210,6 +212,8 @@ static void carve_decode(Carver& cv, const compact_layer_cfg& c, int N, int max_
     b.q = cv.take((size_t)N * c.n_q_heads * c.head_dim * es);
     b.o = cv.take((size_t)N * c.n_q_heads * c.head_dim * es);
     b.m = cv.take((size_t)N * c.d_model * es);
+    b.hg = cv.take((size_t)N * c.d_model * es);
+    b.ssq_parts = (float*)cv.take((size_t)((c.d_model + 15) / 16) * N * 4);
     b.h = (float*)cv.take((size_t)N * c.d_model * 4);
     const int rows = c.n_experts == 0 ? N : N * c.top_k;
     b.act = cv.take((size_t)rows * c.ffn_dim * es);
@@ -508,20 +512,44 @@ static int decode_impl(compact_ctx* ctx, const compact_weights* w, int n_blocks,
     TRY(gemm_partials(ctx, n, w->w_qkv, b.partials, N, Dtot, c.d_model, &ks, s));
     TRY(launch_decode_qkv_epilogue(ctx, plan.d_meta, N, step, b.partials, ks, b.q, kv->d_k, kv->d_v, s));
     TRY(run_attn_decode(ctx, plan, N, step, b.q, kv, b.attn_partials, b.o, s));
-    TRY(gemm_partials(ctx, b.o, w->w_o, b.partials, N, c.d_model, Dq, &ks, s));
-    TRY(launch_residual_norm(ctx, b.partials, ks, x, w->g_ffn, b.h, b.m, N, s));
+    // O projection + residual, and the RMSNorm that feeds the FFN.  bf16 storage with
+    // few rows: one whole-K kernel leaves h, the un-normalised FFN input h * g and the
+    // row sums of squares; whoever consumes the input applies 1/rms.
+    const bool bf = c.dtype == COMPACT_BF16;
+    const void* ffn_in = b.m;
+    RowNorm rn{};
+    bool pending_norm = false;
+    if (bf && resid_norm_stream_supported(N, c.d_model, Dq)) {
+        ProfileScope ps(ctx, COMPACT_K_GEMM_SKINNY, s);
+        TRY(launch_resid_norm_stream(ctx, (const bf16*)b.o, (const bf16*)w->w_o, (const bf16*)x, (const bf16*)w->g_ffn, b.h,
+                                     (bf16*)b.hg, b.ssq_parts, N, c.d_model, Dq, s));
+        rn.ssq_parts = b.ssq_parts;
+        rn.nparts = c.d_model / 16;
+        rn.inv_d = 1.0f / (float)c.d_model;
+        rn.eps = c.rms_eps;
+        pending_norm = true;
+        ffn_in = b.hg;
+    } else {
+        TRY(gemm_partials(ctx, b.o, w->w_o, b.partials, N, c.d_model, Dq, &ks, s));
+        TRY(launch_residual_norm(ctx, b.partials, ks, x, w->g_ffn, b.h, b.m, N, s));
+    }
     if (c.n_experts == 0) {
-        if (c.dtype == COMPACT_BF16 && skinny_swiglu_supported(N, c.ffn_dim, c.d_model)) {
+        if (bf && skinny_swiglu_supported(N, c.ffn_dim, c.d_model)) {
             ProfileScope ps(ctx, COMPACT_K_GEMM_SKINNY, s);
-            TRY(launch_gemm_skinny_swiglu(ctx, (const bf16*)b.m, (const bf16*)w->w_gate_up, (bf16*)b.act, N, c.ffn_dim,
-                                          c.d_model, s));
+            TRY(launch_gemm_skinny_swiglu(ctx, (const bf16*)ffn_in, (const bf16*)w->w_gate_up, (bf16*)b.act, N, c.ffn_dim,
+                                          c.d_model, pending_norm ? &rn : nullptr, s));
         } else {
-            TRY(gemm_partials(ctx, b.m, w->w_gate_up, b.partials, N, 2 * c.ffn_dim, c.d_model, &ks, s));
+            if (pending_norm) {
+                TRY(launch_rownorm_apply(ctx, (const bf16*)b.hg, rn, (bf16*)b.m, N, c.d_model, s));
+                ffn_in = b.m;
+            }
+            TRY(gemm_partials(ctx, ffn_in, w->w_gate_up, b.partials, N, 2 * c.ffn_dim, c.d_model, &ks, s));
             TRY(launch_swiglu_reduce(ctx, b.partials, ks, b.act, N, c.ffn_dim, s));
         }
         TRY(gemm_partials(ctx, b.act, w->w_down, b.partials, N, c.d_model, c.ffn_dim, &ks, s));
         TRY(launch_residual_reduce(ctx, b.partials, ks, b.h, y, N, c.d_model, s));
     } else {
+        if (pending_norm) TRY(launch_rownorm_apply(ctx, (const bf16*)b.hg, rn, (bf16*)b.m, N, c.d_model, s));
         int32_t* idx = route && route->d_expert_idx ? route->d_expert_idx : b.idx;
         float* gate = route && route->d_gate ? route->d_gate : b.gate;
         TRY(launch_moe_route(ctx, b.m, w->w_router, N, idx, gate, b.logits, s));

@@ -32,6 +32,14 @@ struct BlockMeta {
     int64_t slab;        // element offset of the block's slabs in d_k / d_v
 };
 
+// Per-row 1/rms handed from one kernel to the next as per-column-group sums of
+// squares [nparts][rows] (null ssq_parts: the rows are already normalised).
+struct RowNorm {
+    const float* ssq_parts = nullptr;
+    int nparts = 0;
+    float inv_d = 0.f, eps = 0.f;
+};
+
 struct TileItem {  // (block, first block-local row) of a row tile
     int32_t block;
     int32_t row0;
@@ -150,13 +158,23 @@ int gemm_bf16_mtile();
 int skinny_ksplit(int M, int N, int K);
 int launch_gemm_skinny(compact_ctx* ctx, const bf16* A, const bf16* B, float* partials, int M, int N, int K,
                        int ks, hipStream_t s);
-// decode gate/up projection with the SwiGLU fused in (no partials): act[M, F]
+// decode gate/up projection with the SwiGLU fused in (no partials): act[M, F] =
+// silu(r X Wg^T) * (r X Wu^T); X may hold un-normalised rows (x * g) whose 1/rms r
+// comes from `norm` (null: r = 1)
 bool skinny_swiglu_supported(int M, int F, int K);
 int launch_gemm_skinny_swiglu(compact_ctx* ctx, const bf16* X, const bf16* W, bf16* act, int M, int F, int K,
-                              hipStream_t s);
+                              const RowNorm* norm, hipStream_t s);
 // C = sum of partials (+R), rounded to bf16
 int launch_skinny_finish(compact_ctx* ctx, const float* partials, int ks, const bf16* R, bf16* C, int M, int N,
                          hipStream_t s);
+
+// gemv_stream.hip : whole-K decode projections with the following step fused in (bf16, <= 16 rows)
+// h = resid + X W^T (fp32), hg = bf16(h * g), ssq_parts[N / 16][M] = column-group sums of h^2
+bool resid_norm_stream_supported(int M, int N, int K);
+int launch_resid_norm_stream(compact_ctx* ctx, const bf16* X, const bf16* W, const bf16* resid, const bf16* g, float* h_out,
+                             bf16* hg_out, float* ssq_parts, int M, int N, int K, hipStream_t s);
+// m = bf16(hg / rms): finishes the RMSNorm whose sums of squares are in `norm`
+int launch_rownorm_apply(compact_ctx* ctx, const bf16* hg, const RowNorm& norm, bf16* m, int rows, int d, hipStream_t s);
 
 // attn_f32.hip
 int launch_attn_prefill_f32(compact_ctx* ctx, const BlockMeta* d_meta, int n_blocks, int max_len,

@@ -99,12 +99,13 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16* __restrict
 #define SG_RING 16
 template <int MROWS, int SPW>
 __global__ __launch_bounds__(512) void gemm_skinny_swiglu_kernel(const bf16* __restrict__ X, const bf16* __restrict__ W,
-                                                                 bf16* __restrict__ act, int M, int F) {
+                                                                 bf16* __restrict__ act, int M, int F, const RowNorm norm) {
     constexpr int K = SPW * 128;
     constexpr int LDX = K + 8;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16* xs = reinterpret_cast<bf16*>(smem);                                          // [MROWS][LDX]
     float* red = reinterpret_cast<float*>(smem + (size_t)MROWS * LDX * sizeof(bf16));  // [8][64][4]
+    __shared__ float rinv[16];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int rt = wave >> 2, kw = wave & 3;
     const int r = lane & 15, c = lane >> 4;
@@ -116,6 +117,17 @@ __global__ __launch_bounds__(512) void gemm_skinny_swiglu_kernel(const bf16* __r
     bf16x8 ring[SG_RING];
 #pragma unroll
     for (int i = 0; i < SG_RING && i < SPW; ++i) ring[i] = *reinterpret_cast<const bf16x8*>(wrow + i * 128);
+
+    // 1/rms of the rows from the column-group sums of squares, added in a fixed
+    // order (lane-strided, then a butterfly): wavefront w finishes rows w and w + 8
+    for (int row = wave; row < MROWS; row += 8) {
+        float ss = 0.f;
+        if (norm.ssq_parts && row < M)
+            for (int pidx = lane; pidx < norm.nparts; pidx += 64) ss += norm.ssq_parts[(size_t)pidx * M + row];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+        if (lane == 0) rinv[row] = norm.ssq_parts ? 1.0f / sqrtf(ss * norm.inv_d + norm.eps) : 1.0f;
+    }
 
     // activations: all of K for the M rows
     constexpr int CPR = K / 8;
@@ -155,11 +167,12 @@ __global__ __launch_bounds__(512) void gemm_skinny_swiglu_kernel(const bf16* __r
         for (int e = 0; e < 4; ++e) v[e] += o[e];
     }
     // v[e]: activation row r, MFMA row 4c + e: c < 2 gate of column 4c + e, c >= 2 up of column 4(c-2) + e
+    const float rs = rinv[xvalid ? r : 0];
     bf16x4 out;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-        const float up = __shfl_xor(v[e], 32, 64);
-        const float g = v[e];
+        const float up = __shfl_xor(v[e], 32, 64) * rs;
+        const float g = v[e] * rs;
         out[e] = (bf16)(g / (1.0f + __expf(-g)) * up);
     }
     if (c < 2 && r < M) *reinterpret_cast<bf16x4*>(act + (size_t)r * F + j0 + rt * 8 + 4 * c) = out;
@@ -175,7 +188,8 @@ bool skinny_swiglu_supported(int M, int F, int K) {
 }
 
 template <int MROWS, int SPT>
-static int launch_swiglu_cfg(compact_ctx* ctx, const bf16* X, const bf16* W, bf16* act, int M, int F, hipStream_t s) {
+static int launch_swiglu_cfg(compact_ctx* ctx, const bf16* X, const bf16* W, bf16* act, int M, int F, const RowNorm& norm,
+                             hipStream_t s) {
     const size_t smem = swiglu_smem(MROWS, SPT * 128);
     static bool attr = false;
     if (!attr) {
@@ -183,18 +197,20 @@ static int launch_swiglu_cfg(compact_ctx* ctx, const bf16* X, const bf16* W, bf1
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
         attr = true;
     }
-    gemm_skinny_swiglu_kernel<MROWS, SPT><<<F / 16, 512, smem, s>>>(X, W, act, M, F);
+    gemm_skinny_swiglu_kernel<MROWS, SPT><<<F / 16, 512, smem, s>>>(X, W, act, M, F, norm);
     LAUNCH_CHECK(ctx);
     return COMPACT_OK;
 }
 
-int launch_gemm_skinny_swiglu(compact_ctx* ctx, const bf16* X, const bf16* W, bf16* act, int M, int F, int K, hipStream_t s) {
+int launch_gemm_skinny_swiglu(compact_ctx* ctx, const bf16* X, const bf16* W, bf16* act, int M, int F, int K,
+                              const RowNorm* norm, hipStream_t s) {
     if (!skinny_swiglu_supported(M, F, K)) return set_err(ctx, COMPACT_ESHAPE, "fused gate/up decode kernel does not cover this shape");
+    const RowNorm rn = norm ? *norm : RowNorm{};
     const bool small = M <= 8;
     switch (K) {
-        case 2048: return small ? launch_swiglu_cfg<8, 16>(ctx, X, W, act, M, F, s) : launch_swiglu_cfg<16, 16>(ctx, X, W, act, M, F, s);
-        case 4096: return small ? launch_swiglu_cfg<8, 32>(ctx, X, W, act, M, F, s) : launch_swiglu_cfg<16, 32>(ctx, X, W, act, M, F, s);
-        default: return launch_swiglu_cfg<8, 64>(ctx, X, W, act, M, F, s);   // K = 8192 fits 8 rows only
+        case 2048: return small ? launch_swiglu_cfg<8, 16>(ctx, X, W, act, M, F, rn, s) : launch_swiglu_cfg<16, 16>(ctx, X, W, act, M, F, rn, s);
+        case 4096: return small ? launch_swiglu_cfg<8, 32>(ctx, X, W, act, M, F, rn, s) : launch_swiglu_cfg<16, 32>(ctx, X, W, act, M, F, rn, s);
+        default: return launch_swiglu_cfg<8, 64>(ctx, X, W, act, M, F, rn, s);   // K = 8192 fits 8 rows only
     }
 }
 
