@@ -553,7 +553,31 @@ static int decode_impl(compact_ctx* ctx, const compact_weights* w, int n_blocks,
         int32_t* idx = route && route->d_expert_idx ? route->d_expert_idx : b.idx;
         float* gate = route && route->d_gate ? route->d_gate : b.gate;
         TRY(launch_moe_route(ctx, b.m, w->w_router, N, idx, gate, b.logits, s));
-        TRY(moe_ffn_rows(ctx, w, b.m, b.h, true, idx, gate, N, b.act, b.plan, b.expert_out, y, s));
+        if (bf && N <= 16) {
+            // few rows per expert: stream every routed expert's weights once (split-K
+            // partials in the expert-sorted row order), SwiGLU, down projection, and a
+            // combine that applies the gate weights to the fp32 sums
+            const int rk = N * c.top_k;
+            TRY(launch_moe_plan(ctx, idx, gate, N, moe_mtile(c), b.plan, s));
+            int ks1 = skinny_ksplit(1, 2 * c.ffn_dim, c.d_model);
+            {
+                ProfileScope ps(ctx, COMPACT_K_GEMM_SKINNY, s);
+                TRY(launch_gemm_skinny_grouped(ctx, (const bf16*)b.m, b.plan.sorted_token, (const bf16*)w->w_exp_gate_up,
+                                               (int64_t)2 * c.ffn_dim * c.d_model, b.plan.offsets, c.n_experts, rk, b.partials,
+                                               2 * c.ffn_dim, c.d_model, ks1, s));
+            }
+            TRY(launch_swiglu_reduce(ctx, b.partials, ks1, b.act, rk, c.ffn_dim, s));
+            int ks2 = skinny_ksplit(1, c.d_model, c.ffn_dim);
+            {
+                ProfileScope ps(ctx, COMPACT_K_GEMM_SKINNY, s);
+                TRY(launch_gemm_skinny_grouped(ctx, (const bf16*)b.act, nullptr, (const bf16*)w->w_exp_down,
+                                               (int64_t)c.d_model * c.ffn_dim, b.plan.offsets, c.n_experts, rk, b.partials,
+                                               c.d_model, c.ffn_dim, ks2, s));
+            }
+            TRY(launch_moe_combine_partials(ctx, b.partials, ks2, rk, b.h, b.plan.slot_of, b.plan.sorted_gate, N, y, s));
+        } else {
+            TRY(moe_ffn_rows(ctx, w, b.m, b.h, true, idx, gate, N, b.act, b.plan, b.expert_out, y, s));
+        }
     }
     return COMPACT_OK;
 }

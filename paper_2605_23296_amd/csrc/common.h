@@ -158,6 +158,12 @@ int gemm_bf16_mtile();
 int skinny_ksplit(int M, int N, int K);
 int launch_gemm_skinny(compact_ctx* ctx, const bf16* A, const bf16* B, float* partials, int M, int N, int K,
                        int ks, hipStream_t s);
+// the same per expert, for routed decode rows: expert e multiplies the rows offsets[e] ..
+// offsets[e+1]-1 of the expert-sorted order (at most 16; X is read through a_gather when
+// given); partials[ks][total_rows][N] keep the sorted order
+int launch_gemm_skinny_grouped(compact_ctx* ctx, const bf16* X, const int32_t* a_gather, const bf16* W, int64_t w_expert_stride,
+                               const int32_t* offsets, int n_experts, int total_rows, float* partials, int N, int K, int ks,
+                               hipStream_t s);
 // decode gate/up projection with the SwiGLU fused in (no partials): act[M, F] =
 // silu(r X Wg^T) * (r X Wu^T); X may hold un-normalised rows (x * g) whose 1/rms r
 // comes from `norm` (null: r = 1)
@@ -208,6 +214,9 @@ int launch_moe_route(compact_ctx* ctx, const void* m, const void* w_router, int6
                      float* gate, float* logits, hipStream_t s);
 int launch_moe_plan(compact_ctx* ctx, const int32_t* idx, const float* gate, int64_t rows, int mtile,
                     const MoePlan& plan, hipStream_t s);
+// decode: y[t] = h[t] + sum_j gate * (sum over K-slices of partials[slot_of[t*k + j]]), one rounding
+int launch_moe_combine_partials(compact_ctx* ctx, const float* partials, int ks, int64_t total_rows, const float* h,
+                                const int32_t* slot_of, const float* sorted_gate, int64_t rows, void* y, hipStream_t s);
 // h_is_f32: the residual h is fp32 (decode) instead of the storage type
 int launch_moe_combine(compact_ctx* ctx, const void* expert_out, const void* h, bool h_is_f32,
                        const int32_t* slot_of, int64_t rows, void* y, hipStream_t s);

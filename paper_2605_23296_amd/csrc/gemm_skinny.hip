@@ -23,14 +23,35 @@ int skinny_ksplit(int M, int N, int K) {
     return (K + SKINNY_KSLICE - 1) / SKINNY_KSLICE;
 }
 
-template <int MT>
+// GROUPED: blockIdx.z is an expert; its rows are rows offsets[e] .. offsets[e+1]-1
+// of the expert-sorted order (at most MT*16 of them), read from X through
+// a_gather (null: X is already in sorted order), multiplied with that expert's
+// weight matrix, and the partials keep the sorted order: P[slice][sorted row][N].
+// Experts nobody was routed to leave at once.
+struct SkinnyGroup {
+    const int32_t* offsets;   // [E + 1]
+    const int32_t* a_gather;  // [total_rows] or null
+    int64_t w_expert_stride;  // elements
+    int total_rows;
+};
+
+template <int MT, bool GROUPED>
 __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16* __restrict__ X, const bf16* __restrict__ W,
-                                                          float* __restrict__ P, int M, int N, int K) {
+                                                          float* __restrict__ P, int M, int N, int K, const SkinnyGroup grp) {
     constexpr int LDX = SKINNY_KSLICE + 8;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16* xs = reinterpret_cast<bf16*>(smem);  // [MT*16][LDX]
     const int t = threadIdx.x;
     const int lane = t & 63, wave = t >> 6;
+    int row_base = 0, p_rows = M;
+    if (GROUPED) {
+        const int e = blockIdx.z;
+        row_base = grp.offsets[e];
+        M = min(grp.offsets[e + 1] - row_base, MT * 16);
+        if (M <= 0) return;
+        W += (size_t)e * grp.w_expert_stride;
+        p_rows = grp.total_rows;
+    }
     // the K-slice is the fastest grid index: workgroups that run together read
     // neighbouring slices of the same weight rows (whole DRAM pages), not the same
     // slice of far-apart rows
@@ -57,7 +78,11 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16* __restrict
         bf16x8 v;
 #pragma unroll
         for (int j = 0; j < 8; ++j) v[j] = (bf16)0.f;
-        if (row < M) v = *reinterpret_cast<const bf16x8*>(X + (size_t)row * K + k0 + cc * 8);
+        if (row < M) {
+            size_t src = row_base + row;
+            if (GROUPED && grp.a_gather) src = grp.a_gather[src];
+            v = *reinterpret_cast<const bf16x8*>(X + src * K + k0 + cc * 8);
+        }
         *reinterpret_cast<bf16x8*>(xs + row * LDX + cc * 8) = v;
     }
     __syncthreads();
@@ -80,7 +105,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16* __restrict
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int m = mt * 16 + r;
-        if (m < M) *reinterpret_cast<floatx4*>(P + ((size_t)slice * M + m) * N + n0 + 4 * c) = acc[mt];
+        if (m < M) *reinterpret_cast<floatx4*>(P + ((size_t)slice * p_rows + row_base + m) * N + n0 + 4 * c) = acc[mt];
     }
 }
 
@@ -223,27 +248,42 @@ int launch_gemm_skinny(compact_ctx* ctx, const bf16* A, const bf16* B, float* pa
     const int mt = (M + 15) / 16;
     const size_t smem = (size_t)mt * 16 * (SKINNY_KSLICE + 8) * sizeof(bf16);
     switch (mt) {
-        case 1: gemm_skinny_kernel<1><<<grid, 256, smem, s>>>(A, B, partials, M, N, K); break;
-        case 2: gemm_skinny_kernel<2><<<grid, 256, smem, s>>>(A, B, partials, M, N, K); break;
+        case 1: gemm_skinny_kernel<1, false><<<grid, 256, smem, s>>>(A, B, partials, M, N, K, SkinnyGroup{}); break;
+        case 2: gemm_skinny_kernel<2, false><<<grid, 256, smem, s>>>(A, B, partials, M, N, K, SkinnyGroup{}); break;
         case 3: {
             static bool set3 = false;
             if (!set3) {
-                HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel<3>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+                HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel<3, false>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
                 set3 = true;
             }
-            gemm_skinny_kernel<3><<<grid, 256, smem, s>>>(A, B, partials, M, N, K);
+            gemm_skinny_kernel<3, false><<<grid, 256, smem, s>>>(A, B, partials, M, N, K, SkinnyGroup{});
             break;
         }
         default: {
             static bool set4 = false;
             if (!set4) {
-                HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel<4>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+                HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel<4, false>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
                 set4 = true;
             }
-            gemm_skinny_kernel<4><<<grid, 256, smem, s>>>(A, B, partials, M, N, K);
+            gemm_skinny_kernel<4, false><<<grid, 256, smem, s>>>(A, B, partials, M, N, K, SkinnyGroup{});
             break;
         }
     }
+    LAUNCH_CHECK(ctx);
+    return COMPACT_OK;
+}
+
+// Per-expert weight streaming for routed decode rows (at most 16 rows per expert):
+// partials[ks][total_rows][N], rows in expert-sorted order.
+int launch_gemm_skinny_grouped(compact_ctx* ctx, const bf16* X, const int32_t* a_gather, const bf16* W, int64_t w_expert_stride,
+                               const int32_t* offsets, int n_experts, int total_rows, float* partials, int N, int K, int ks,
+                               hipStream_t s) {
+    if (N % 16 != 0 || K % 64 != 0) return set_err(ctx, COMPACT_ESHAPE, "weight-streaming GEMM needs N % 16 == 0 and K % 64 == 0");
+    if (ks != skinny_ksplit(1, N, K)) return set_err(ctx, COMPACT_EINVAL, "unexpected K split");
+    SkinnyGroup g{offsets, a_gather, w_expert_stride, total_rows};
+    dim3 grid(ks, (N + 63) / 64, n_experts);
+    const size_t smem = (size_t)16 * (SKINNY_KSLICE + 8) * sizeof(bf16);
+    gemm_skinny_kernel<1, true><<<grid, 256, smem, s>>>(X, W, partials, 0, N, K, g);
     LAUNCH_CHECK(ctx);
     return COMPACT_OK;
 }

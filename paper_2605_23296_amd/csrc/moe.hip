@@ -213,3 +213,42 @@ int launch_moe_combine(compact_ctx* ctx, const void* expert_out, const void* h, 
     LAUNCH_CHECK(ctx);
     return COMPACT_OK;
 }
+
+// ---------------------------------------------------------------------------
+// Decode: y[t] = h[t] + sum_j gate_j * (sum_s P[s][slot_of[t*k + j]]), with the
+// split-K partials of the routed down projection still in fp32: one rounding.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void moe_combine_partials_kernel(const float* __restrict__ P, int ks, int64_t total_rows,
+                                                                   const float* __restrict__ hres,
+                                                                   const int32_t* __restrict__ slot_of,
+                                                                   const float* __restrict__ sorted_gate, int k, int d,
+                                                                   bf16* __restrict__ y) {
+    const int64_t row = blockIdx.y;
+    const int c = (blockIdx.x * 256 + threadIdx.x) * 4;
+    if (c >= d) return;
+    float4 acc = *reinterpret_cast<const float4*>(hres + row * d + c);
+    for (int j = 0; j < k; ++j) {
+        const int64_t slot = slot_of[row * k + j];
+        const float gw = sorted_gate[slot];
+        float4 e = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int s = 0; s < ks; ++s) {
+            const float4 v = *reinterpret_cast<const float4*>(P + ((int64_t)s * total_rows + slot) * d + c);
+            e.x += v.x; e.y += v.y; e.z += v.z; e.w += v.w;
+        }
+        acc.x += gw * e.x; acc.y += gw * e.y; acc.z += gw * e.z; acc.w += gw * e.w;
+    }
+    bf16x4 o;
+    o[0] = (bf16)acc.x; o[1] = (bf16)acc.y; o[2] = (bf16)acc.z; o[3] = (bf16)acc.w;
+    *reinterpret_cast<bf16x4*>(y + row * d + c) = o;
+}
+
+int launch_moe_combine_partials(compact_ctx* ctx, const float* partials, int ks, int64_t total_rows, const float* h,
+                                const int32_t* slot_of, const float* sorted_gate, int64_t rows, void* y, hipStream_t s) {
+    if (rows == 0) return COMPACT_OK;
+    const compact_layer_cfg& c = ctx->cfg;
+    dim3 grid((c.d_model / 4 + 255) / 256, (unsigned)rows);
+    moe_combine_partials_kernel<<<grid, 256, 0, s>>>(partials, ks, total_rows, h, slot_of, sorted_gate, c.top_k, c.d_model,
+                                                     (bf16*)y);
+    LAUNCH_CHECK(ctx);
+    return COMPACT_OK;
+}
