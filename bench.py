@@ -38,9 +38,12 @@ def layer_params(layer):
     return attn + layer.n_experts * d + layer.top_k * 3 * F * d      # parameters touched per token
 
 
-def algorithmic_work(layer, lens, S):
+def algorithmic_work(layer, lens, S, distinct_experts_per_step=None):
     """Work the method must do, per pass (each weight once per call, the causal
-    half of attention, each cached KV byte once per decode step)."""
+    half of attention, each cached KV byte once per decode step).  For a routed
+    layer a decode step must read the weights of every expert that some row of
+    the step was routed to, once: distinct_experts_per_step (measured on the
+    same inputs) gives their number per step."""
     T, N = sum(lens), len(lens)
     P = layer_params(layer)
     w = {}
@@ -48,8 +51,29 @@ def algorithmic_work(layer, lens, S):
     w["attn_prefill_flops"] = sum(L * (L + 1) / 2 for L in lens) * 4.0 * layer.head_dim * layer.n_q_heads
     kv_tok = 2 * layer.Dkv * 2                                       # bytes per cached token (K and V, bf16)
     w["attn_decode_bytes"] = float(sum(sum((L + s + 1) * kv_tok for L in lens) for s in range(S)))
-    w["skinny_bytes"] = float(S) * P * 2                             # every weight once per step
+    if layer.n_experts == 0:
+        w["skinny_bytes"] = float(S) * P * 2                         # every weight once per step
+    else:
+        d, F = layer.d_model, layer.ffn_dim
+        attn = (layer.Dq + 2 * layer.Dkv) * d + d * layer.Dq
+        experts = sum(distinct_experts_per_step) if distinct_experts_per_step else S * min(layer.n_experts, N * layer.top_k)
+        # the router (E x d) runs through the prefill-size GEMM class and is not counted here
+        w["skinny_bytes"] = 2.0 * (S * attn + experts * 3 * F * d)
     return w
+
+
+def distinct_experts(lay, inp, kv, bufs):
+    """Experts touched by each decode step of a routed layer (one untimed pass
+    through compact_prefill + compact_decode_step with the routing read back)."""
+    layer, dev = inp.layer, bufs["x"].device
+    N, S, T = len(inp.block_lens), inp.x_decode.shape[0], inp.cu_seqlens[-1]
+    lay.compact_prefill(inp.cu_seqlens, bufs["x"], kv, bufs["y_pre"])
+    idx = torch.empty(S, N, layer.top_k, dtype=torch.int32, device=dev)
+    gate = torch.empty(S, N, layer.top_k, dtype=torch.float32, device=dev)
+    for s in range(S):
+        lay.compact_decode_step(bufs["xd"][s], kv, bufs["y_dec"][s], (idx[s], gate[s]))
+    torch.cuda.synchronize()
+    return [int(torch.unique(idx[s]).numel()) for s in range(S)]
 
 
 def recorded_traffic(workload, kernel_class):
@@ -169,7 +193,8 @@ def main():
     t_decode = max(t_pass - t_prefill, 1e-9)
 
     # per-kernel-class durations from HIP events on the launch stream, one class per extra pass
-    work = algorithmic_work(layer, lens, S)
+    n_distinct = distinct_experts(lay, inp, kv, bufs) if layer.n_experts > 0 else None
+    work = algorithmic_work(layer, lens, S, n_distinct)
     classes = {
         "gemm_bf16": (B.K_GEMM, "mfma", work["gemm_flops"], PEAK_BF16_TFLOPS),
         "attn_prefill": (B.K_ATTN_PREFILL, "mfma", work["attn_prefill_flops"], PEAK_BF16_TFLOPS),
@@ -201,9 +226,12 @@ def main():
         "metric": "compaction_decode_tokens_per_s", "value": N * S / t_pass, "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": t_pass * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": layer.dtype, "data": "synthetic",
-        "config": {"workload": "%s: %d blocks x %d tokens prefill + %d decode steps/block, d_model %d, %dq/%dkv heads x %d, "
-                               "FFN %d, one layer" % (wl.name, N, lens[0], S, layer.d_model, layer.n_q_heads,
-                                                      layer.n_kv_heads, layer.head_dim, layer.ffn_dim),
+        "config": {"workload": "%s: %d blocks x %s tokens prefill + %d decode steps/block, d_model %d, %dq/%dkv heads x %d, "
+                               "FFN %d%s, one layer" % (wl.name, N, str(lens[0]) if min(lens) == max(lens) else
+                                                        "%d..%d" % (min(lens), max(lens)), S, layer.d_model,
+                                                        layer.n_q_heads, layer.n_kv_heads, layer.head_dim, layer.ffn_dim,
+                                                        "" if layer.n_experts == 0 else
+                                                        " x %d experts top-%d" % (layer.n_experts, layer.top_k)),
                    "total_prefill_tokens": T, "decode_tokens": N * S},
         "prefill_tokens_per_s": T / t_prefill, "decode_tokens_per_s": N * S / t_decode,
         "ms_prefill": t_prefill * 1e3, "ms_decode": t_decode * 1e3, "us_per_decode_step": t_decode * 1e6 / max(S, 1),

@@ -3,13 +3,15 @@
 // contiguous along K.
 //
 // Shape of the kernel (gfx950):
-//  * one workgroup = BM x BN output tile, K walked in steps of 64;
-//  * X and W tiles are staged in LDS (two stages, filled by 16-byte
-//    direct-to-LDS global loads, no register hop) in rows of 64 bf16 = 8
-//    chunks of 16 bytes, chunk index XOR-ed with (row / 2) % 8: the LDS has 64
-//    banks of 4 bytes, so two 128-byte rows fill them once, and 16 lanes reading
-//    16 consecutive rows at one k-offset (an MFMA fragment read, ds_read_b128)
-//    touch 16 different 16-byte bank groups;
+//  * one workgroup = BM x BN output tile, K walked in tiles of 32;
+//  * X and W k-tiles are staged in a ring of four LDS stages, filled by
+//    16-byte direct-to-LDS global loads (no register hop) issued three k-tiles
+//    ahead of their use: a load's round trip is about as long as the MFMAs of
+//    two k-tiles, so anything shallower leaves the matrix pipe waiting;
+//  * a tile row is 32 bf16 = 4 chunks of 16 bytes, chunk index XOR-ed with
+//    (row / 4) % 4: the LDS has 64 banks of 4 bytes, four 64-byte rows fill
+//    them once, and 16 lanes reading 16 consecutive rows at one k-offset (an
+//    MFMA fragment read, ds_read_b128) touch 16 different 16-byte bank groups;
 //  * v_mfma_f32_32x32x16_bf16 with the WEIGHT rows as the 32 MFMA rows and
 //    the ACTIVATION rows as the 32 MFMA columns, so each lane ends up holding
 //    4 consecutive output columns of one output row: the epilogue stages
@@ -20,7 +22,12 @@
 //    scaling for the routed experts;
 //  * workgroup ids are remapped so that each XCD (own L2) gets a contiguous
 //    range of tiles, walked in groups of 8 row tiles per column tile.
+#include <type_traits>
+
 #include "common.h"
+
+#define GEMM_BK 32       // k-tile
+#define GEMM_STAGES 4   // LDS ring
 
 struct GemmParams {
     const bf16* X;
@@ -35,9 +42,26 @@ struct GemmParams {
     GroupedArgs g;
 };
 
+// Workgroup barrier for the LDS ring: waits until at most `n` of this wave's
+// global loads are still in flight (the older ones, whose data the others are
+// about to read, have landed in LDS) and all of its LDS reads have returned (the
+// stage they read is about to be refilled), then joins the barrier.  Unlike
+// __syncthreads() it does not drain the newer loads.
+template <int N_IN_FLIGHT>
+__device__ __forceinline__ void ring_barrier() {
+#if defined(__HIP_DEVICE_COMPILE__)
+    static_assert(N_IN_FLIGHT >= 0 && N_IN_FLIGHT < 64, "vector-memory counter is 6 bits");
+    __builtin_amdgcn_sched_barrier(0);
+    // simm16: vmcnt[3:0] | expcnt (7 = no wait) << 4 | lgkmcnt (0) << 8 | vmcnt[5:4] << 14
+    __builtin_amdgcn_s_waitcnt((N_IN_FLIGHT & 15) | (7 << 4) | (0 << 8) | ((N_IN_FLIGHT >> 4) << 14));
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+#endif
+}
+
 template <int BM, int BN, int WM, int WN, int EPI, bool GROUPED>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmParams p) {
-    constexpr int NT = WM * WN * 64, BK = 64;
+    constexpr int NT = WM * WN * 64, BK = GEMM_BK, NSTAGE = GEMM_STAGES, AHEAD = NSTAGE - 1;
     constexpr int WTM = BM / WM, WTN = BN / WN, TM = WTM / 32, TN = WTN / 32;
     constexpr int STAGE = (BM + BN) * BK;  // elements
     constexpr int OUTN = EPI == 1 ? BN / 2 : BN;
@@ -79,19 +103,19 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmParams
     const int r = lane & 31, h = lane >> 5;
 
     // ---- global -> LDS staging (direct-to-LDS 16-byte loads) ---------------------
-    // One wave instruction fills 1 KB of LDS = 8 tile rows of 8 chunks, lane l at
-    // (row l / 8, chunk position l % 8); the position is the XOR-swizzled one, so
-    // the lane fetches global chunk (l % 8) ^ ((row >> 1) & 7) of its row.  The tile's
-    // BM + BN rows are dealt to the waves in units of 8 rows.
-    constexpr int XU = BM / 8 / (WM * WN), WU = BN / 8 / (WM * WN);   // units per wave
-    static_assert(BM % (8 * WM * WN) == 0 && BN % (8 * WM * WN) == 0, "tile rows must split into 8-row units per wave");
+    // One wave instruction fills 1 KB of LDS = 16 tile rows of 4 chunks, lane l at
+    // (row l / 4, chunk position l % 4); the position is the XOR-swizzled one, so
+    // the lane fetches global chunk (l % 4) ^ ((row / 4) % 4) of its row.  The
+    // tile's BM + BN rows are dealt to the waves in units of 16 rows.
+    constexpr int XU = BM / 16 / (WM * WN), WU = BN / 16 / (WM * WN);   // units per wave
+    static_assert(BM % (16 * WM * WN) == 0 && BN % (16 * WM * WN) == 0, "tile rows must split into 16-row units per wave");
     const bf16* xptr[XU];
     const bf16* wptr[WU];
-    const int lrow = lane >> 3, lpos = lane & 7;
+    const int lrow = lane >> 2, lpos = lane & 3;
 #pragma unroll
     for (int i = 0; i < XU; ++i) {
-        const int row = (wave * XU + i) * 8 + lrow;
-        const int c = lpos ^ ((row >> 1) & 7);
+        const int row = (wave * XU + i) * 16 + lrow;
+        const int c = lpos ^ ((row >> 2) & 3);
         const int rr = min(row, rows_valid - 1);
         int64_t src = m0 + rr;
         if (GROUPED && p.g.a_gather) src = p.g.a_gather[src];
@@ -99,8 +123,8 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmParams
     }
 #pragma unroll
     for (int i = 0; i < WU; ++i) {
-        const int row = (wave * WU + i) * 8 + lrow;
-        const int c = lpos ^ ((row >> 1) & 7);
+        const int row = (wave * WU + i) * 16 + lrow;
+        const int c = lpos ^ ((row >> 2) & 3);
         int n;
         if (EPI == 1)
             n = row < BN / 2 ? min(n0 + row, p.N - 1) : p.N + min(n0 + row - BN / 2, p.N - 1);
@@ -117,7 +141,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmParams
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    // fragment row offsets inside a stage (elements), swizzle term (r / 2) % 8
+    // fragment row offsets inside a stage (elements), swizzle term (r / 4) % 4
     int xrow[TM], wrow[TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i) xrow[i] = (wm * WTM + i * 32 + r) * BK;
@@ -130,22 +154,24 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmParams
             row = wn * WTN + j * 32 + r;
         wrow[j] = BM * BK + row * BK;
     }
-    const int sw = (r >> 1) & 7;
+    const int sw = (r >> 2) & 3;
     const int nk = p.K / BK;
 
-    // Software pipeline.  The loads of k-tile kt+1 go straight into the other
-    // LDS stage while k-tile kt is multiplied; MFMA fragments are double-buffered
-    // in registers so the LDS reads of k-step kk+1 are in flight under the MFMAs
-    // of k-step kk; the one barrier per k-tile (after this wave's loads have
-    // landed) sits before the last MFMA group, whose shadow also covers the first
-    // fragment reads of the next tile.
+    // Software pipeline over k-tiles of 32 (two MFMA k-steps).  At the top of
+    // k-tile kt the loads of k-tile kt+3 go out, into the stage whose last readers
+    // passed the previous barrier; the barrier in the middle of the k-tile follows
+    // a wait for this wave's loads of k-tile kt+1 only (the newer two stay in
+    // flight).  MFMA fragments are double-buffered in registers, so the LDS reads
+    // of one k-step run under the MFMAs of the one before.  Past the end of K the
+    // last k-tile is loaded again (into stages nobody reads) rather than branching:
+    // the k-steps stay one basic block each, which the pinned order below needs.
+    constexpr int NLD = XU + WU;
+    const int swave = __builtin_amdgcn_readfirstlane(wave);   // wave-uniform: LDS bases stay scalar
     auto gload = [&](int kt, bf16* stage) {
 #pragma unroll
-        for (int i = 0; i < XU; ++i)
-            load16_to_lds(xptr[i] + kt * BK, stage + (wave * XU + i) * 8 * BK);
+        for (int i = 0; i < XU; ++i) load16_to_lds(xptr[i] + kt * BK, stage + (swave * XU + i) * 16 * BK);
 #pragma unroll
-        for (int i = 0; i < WU; ++i)
-            load16_to_lds(wptr[i] + kt * BK, stage + BM * BK + (wave * WU + i) * 8 * BK);
+        for (int i = 0; i < WU; ++i) load16_to_lds(wptr[i] + kt * BK, stage + BM * BK + (swave * WU + i) * 16 * BK);
     };
     auto frags = [&](const bf16* stage, int kk, bf16x8 (&xf)[TM], bf16x8 (&wf)[TN]) {
         const int ch = ((2 * kk + h) ^ sw) << 3;
@@ -161,51 +187,50 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmParams
             for (int j = 0; j < TN; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], xf[i], acc[i][j], 0, 0, 0);
     };
-
     // Pins the instruction order of one k-step: the LDS reads of the next k-step's
-    // fragments go out two per MFMA at the start of the group, so the last of them
-    // still has most of the group (not one MFMA) to land before it is needed.
+    // fragments go out two per MFMA at the start of the group (the last of them
+    // still has most of the group to land), then the global loads one per MFMA.
     constexpr int NRD = TM + TN, NMF = TM * TN;
-    static_assert(NRD % 2 == 0 && NMF >= NRD / 2, "k-step shape not covered by the pinned order");
-    auto pin_order = [&]() {
+    static_assert(NRD % 2 == 0 && NMF >= NRD / 2 + NLD, "k-step shape not covered by the pinned order");
+    auto pin_order = [&](auto n_loads_tag) {
+        constexpr int n_loads = decltype(n_loads_tag)::value;
 #pragma unroll
         for (int i = 0; i < NRD / 2; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // two LDS reads
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, NMF - NRD / 2, 0);
+#pragma unroll
+        for (int i = 0; i < n_loads; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // one global load
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, NMF - NRD / 2 - n_loads, 0);
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    gload(0, lds);
-    wait_all_memory();
-    __syncthreads();
+#pragma unroll
+    for (int t0 = 0; t0 < AHEAD; ++t0) gload(min(t0, nk - 1), lds + t0 * STAGE);
+    ring_barrier<(AHEAD - 1) * NLD>();
     bf16x8 xfA[TM], wfA[TN], xfB[TM], wfB[TN];
     frags(lds, 0, xfA, wfA);
+    __builtin_amdgcn_sched_barrier(0);
 
     for (int kt = 0; kt < nk; ++kt) {
-        const bf16* cur = lds + (kt & 1) * STAGE;
-        bf16* nxt = lds + ((kt + 1) & 1) * STAGE;
-        // k-step 0: start the next tile's loads, next fragments
-        if (kt + 1 < nk) gload(kt + 1, nxt);
+        const bf16* cur = lds + (kt % NSTAGE) * STAGE;
+        const bf16* nxt = lds + ((kt + 1) % NSTAGE) * STAGE;
+        bf16* fill = lds + ((kt + AHEAD) % NSTAGE) * STAGE;
+        // k-step 0: fragments of k-step 1, loads of k-tile kt + 3
         frags(cur, 1, xfB, wfB);
+        gload(min(kt + AHEAD, nk - 1), fill);
         mfmas(xfA, wfA);
-        pin_order();
-        // k-step 1
-        frags(cur, 2, xfA, wfA);
+        pin_order(std::integral_constant<int, NLD>{});
+        // k-step 1: k-tile kt + 1 has landed for everyone; its first fragments
+        ring_barrier<(AHEAD - 1) * NLD>();
+        frags(nxt, 0, xfA, wfA);
         mfmas(xfB, wfB);
-        pin_order();
-        // k-step 2
-        frags(cur, 3, xfB, wfB);
-        mfmas(xfA, wfA);
-        pin_order();
-        // k-step 3: everyone has read `cur` and filled `nxt`
-        wait_all_memory();
-        __syncthreads();
-        if (kt + 1 < nk) frags(nxt, 0, xfA, wfA);
-        mfmas(xfB, wfB);
-        __builtin_amdgcn_sched_barrier(0);
+        pin_order(std::integral_constant<int, 0>{});
     }
+    wait_all_memory();   // the repeated loads of the last k-tile must not land in the epilogue's slabs
     __syncthreads();
 
     // ---- epilogue: 32 output rows per pass through a wave-private fp32 slab ----
@@ -284,7 +309,7 @@ static int launch_cfg(compact_ctx* ctx, GemmParams& p, hipStream_t s) {
     constexpr int WOUT = (EPI == 1 ? BN / 2 : BN) / WN;
     if (!GROUPED) p.n_mtiles = (int)((p.M + BM - 1) / BM);
     p.n_ntiles = (p.N + OUTN - 1) / OUTN;
-    const size_t stage_bytes = (size_t)2 * (BM + BN) * 64 * sizeof(bf16);
+    const size_t stage_bytes = (size_t)GEMM_STAGES * (BM + BN) * GEMM_BK * sizeof(bf16);
     const size_t slab_bytes = (size_t)WM * WN * 32 * (WOUT + 4) * sizeof(float);
     const size_t smem = std::max(stage_bytes, slab_bytes);
     auto kern = gemm_bf16_kernel<BM, BN, WM, WN, EPI, GROUPED>;
@@ -306,7 +331,7 @@ int gemm_bf16_mtile() { return 256; }
 int launch_gemm_bf16(compact_ctx* ctx, const bf16* A, const bf16* B, const void* R, bool r_f32, bf16* C, int64_t M, int N,
                      int K, int epilogue, const GroupedArgs* grouped, hipStream_t s) {
     if (M == 0) return COMPACT_OK;
-    if (K % 64 != 0 || N % 8 != 0) return set_err(ctx, COMPACT_ESHAPE, "bf16 GEMM needs K % 64 == 0 and N % 8 == 0");
+    if (K % GEMM_BK != 0 || N % 8 != 0) return set_err(ctx, COMPACT_ESHAPE, "bf16 GEMM needs K % 32 == 0 and N % 8 == 0");
     GemmParams p{};
     p.X = A;
     p.W = B;
