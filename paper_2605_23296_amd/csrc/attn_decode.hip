@@ -38,6 +38,7 @@ __global__ __launch_bounds__(DEC_WAVES * 64) void attn_decode_bf16_kernel(const 
     constexpr int DT = HD / 16;  // 16-row tiles of O^T
     constexpr int PLD = HD + 2;  // partial record: HD values, max, sum
     extern __shared__ float so[];  // [DEC_WAVES][G][PLD]
+    __shared__ __attribute__((aligned(16))) bf16 qs[16 * HD];   // [G][HD] query rows of the group
 
     const int b = blockIdx.z, kvh = blockIdx.y, ch = blockIdx.x;
     const BlockMeta bm = meta[b];
@@ -58,7 +59,6 @@ __global__ __launch_bounds__(DEC_WAVES * 64) void attn_decode_bf16_kernel(const 
     // V^T tile d: lane (row dd = d*16 + r, c) holds tokens t0 + 8c .. +7
     bf16x8 kf[2][KS];
     bf16x8 vf[DT];
-    bf16x8 qf[KS];
     if (live) {
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {
@@ -71,14 +71,12 @@ __global__ __launch_bounds__(DEC_WAVES * 64) void attn_decode_bf16_kernel(const 
 #pragma unroll
         for (int d = 0; d < DT; ++d)
             vf[d] = *reinterpret_cast<const bf16x8*>(vslab + (size_t)(d * 16 + r) * bm.capacity + voff);
-        // query operand: lane (g = r, c) holds q[g][s*32 + c*8 .. +7]
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) qf[s][j] = (bf16)0.f;
-            if (r < G) qf[s] = *reinterpret_cast<const bf16x8*>(q + ((size_t)b * Hq + kvh * G + r) * HD + s * 32 + c * 8);
-        }
     }
+    // the group's query rows go through LDS: they are needed only once the K rows
+    // have arrived, and parking them in registers until then would cost occupancy
+    for (int i = t; i < G * (HD / 8); i += DEC_WAVES * 64)
+        *reinterpret_cast<bf16x8*>(qs + i * 8) = *reinterpret_cast<const bf16x8*>(q + ((size_t)b * Hq + kvh * G) * HD + i * 8);
+    __syncthreads();
 
     floatx4 oacc[DT];
 #pragma unroll
@@ -93,13 +91,17 @@ __global__ __launch_bounds__(DEC_WAVES * 64) void attn_decode_bf16_kernel(const 
                     if (t0 + 8 * c + j >= n_keys) vf[d][j] = (bf16)0.f;
         }
         // ---- S^T = K Q^T ------------------------------------------------------
-        floatx4 sacc[2];
+        // query operand: lane (g = r, c) holds q[g][s*32 + c*8 .. +7], read k-step by k-step
+        floatx4 sacc[2] = {floatx4{0.f, 0.f, 0.f, 0.f}, floatx4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-            sacc[tt] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int s = 0; s < KS; ++s) {
+            bf16x8 qf = *reinterpret_cast<const bf16x8*>(qs + (r < G ? r : 0) * HD + s * 32 + c * 8);
+            if (r >= G) {
 #pragma unroll
-            for (int s = 0; s < KS; ++s)
-                sacc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[tt][s], qf[s], sacc[tt], 0, 0, 0);
+                for (int j = 0; j < 8; ++j) qf[j] = (bf16)0.f;
+            }
+            sacc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][s], qf, sacc[0], 0, 0, 0);
+            sacc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[1][s], qf, sacc[1], 0, 0, 0);
         }
         // sacc[tt][e]: column g = r, token t0 + 8c + 4tt + e
         float sv[8];

@@ -35,8 +35,8 @@ struct SkinnyGroup {
     int total_rows;
 };
 
-template <int MT, bool GROUPED>
-__global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16* __restrict__ X, const bf16* __restrict__ W,
+template <int MT, bool GROUPED, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const bf16* __restrict__ X, const bf16* __restrict__ W,
                                                           float* __restrict__ P, int M, int N, int K, const SkinnyGroup grp) {
     constexpr int LDX = SKINNY_KSLICE + 8;
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -60,7 +60,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16* __restrict
     const int klen = min(SKINNY_KSLICE, K - k0);
     const int nsteps = klen / 32;
     const int r = lane & 15, c = lane >> 4;
-    const int n0 = (blockIdx.y * 4 + wave) * 16;
+    const int n0 = (blockIdx.y * WAVES + wave) * 16;
     const bool active = n0 < N;
 
     // the weight stream goes first: everything below overlaps with it
@@ -73,7 +73,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16* __restrict
     }
 
     const int cpr = klen / 8;  // 16-byte chunks per row
-    for (int q = t; q < MT * 16 * cpr; q += 256) {
+    for (int q = t; q < MT * 16 * cpr; q += WAVES * 64) {
         const int row = q / cpr, cc = q - row * cpr;
         bf16x8 v;
 #pragma unroll
@@ -239,38 +239,37 @@ int launch_gemm_skinny_swiglu(compact_ctx* ctx, const bf16* X, const bf16* W, bf
     }
 }
 
+template <int MT, int WAVES>
+static int launch_skinny_cfg(compact_ctx* ctx, const bf16* A, const bf16* B, float* partials, int M, int N, int K, int ks,
+                             hipStream_t s) {
+    const size_t smem = (size_t)MT * 16 * (SKINNY_KSLICE + 8) * sizeof(bf16);
+    static bool attr = false;
+    if (!attr && smem > 48 * 1024) {
+        HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel<MT, false, WAVES>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+        attr = true;
+    }
+    dim3 grid(ks, (N + 16 * WAVES - 1) / (16 * WAVES));
+    gemm_skinny_kernel<MT, false, WAVES><<<grid, WAVES * 64, smem, s>>>(A, B, partials, M, N, K, SkinnyGroup{});
+    LAUNCH_CHECK(ctx);
+    return COMPACT_OK;
+}
+
+// One workgroup = 4 wavefronts (64 weight rows) for up to 16 activation rows; with
+// more rows the staged activation slice grows, so 8 wavefronts (128 weight rows)
+// share it: half the activation traffic per weight byte, the same number of
+// wavefronts per compute unit.
 int launch_gemm_skinny(compact_ctx* ctx, const bf16* A, const bf16* B, float* partials, int M, int N, int K, int ks,
                        hipStream_t s) {
     if (M < 1 || M > 64) return set_err(ctx, COMPACT_ESHAPE, "weight-streaming GEMM takes 1..64 activation rows");
     if (N % 16 != 0 || K % 64 != 0) return set_err(ctx, COMPACT_ESHAPE, "weight-streaming GEMM needs N % 16 == 0 and K % 64 == 0");
     if (ks != skinny_ksplit(M, N, K)) return set_err(ctx, COMPACT_EINVAL, "unexpected K split");
-    dim3 grid(ks, (N + 63) / 64);
-    const int mt = (M + 15) / 16;
-    const size_t smem = (size_t)mt * 16 * (SKINNY_KSLICE + 8) * sizeof(bf16);
-    switch (mt) {
-        case 1: gemm_skinny_kernel<1, false><<<grid, 256, smem, s>>>(A, B, partials, M, N, K, SkinnyGroup{}); break;
-        case 2: gemm_skinny_kernel<2, false><<<grid, 256, smem, s>>>(A, B, partials, M, N, K, SkinnyGroup{}); break;
-        case 3: {
-            static bool set3 = false;
-            if (!set3) {
-                HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel<3, false>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-                set3 = true;
-            }
-            gemm_skinny_kernel<3, false><<<grid, 256, smem, s>>>(A, B, partials, M, N, K, SkinnyGroup{});
-            break;
-        }
-        default: {
-            static bool set4 = false;
-            if (!set4) {
-                HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel<4, false>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-                set4 = true;
-            }
-            gemm_skinny_kernel<4, false><<<grid, 256, smem, s>>>(A, B, partials, M, N, K, SkinnyGroup{});
-            break;
-        }
+    switch ((M + 15) / 16) {
+        case 1: return launch_skinny_cfg<1, 4>(ctx, A, B, partials, M, N, K, ks, s);
+        case 2: return launch_skinny_cfg<2, 8>(ctx, A, B, partials, M, N, K, ks, s);
+        case 3: return launch_skinny_cfg<3, 8>(ctx, A, B, partials, M, N, K, ks, s);
+        default: return launch_skinny_cfg<4, 8>(ctx, A, B, partials, M, N, K, ks, s);
     }
-    LAUNCH_CHECK(ctx);
-    return COMPACT_OK;
 }
 
 // Per-expert weight streaming for routed decode rows (at most 16 rows per expert):
@@ -283,7 +282,7 @@ int launch_gemm_skinny_grouped(compact_ctx* ctx, const bf16* X, const int32_t* a
     SkinnyGroup g{offsets, a_gather, w_expert_stride, total_rows};
     dim3 grid(ks, (N + 63) / 64, n_experts);
     const size_t smem = (size_t)16 * (SKINNY_KSLICE + 8) * sizeof(bf16);
-    gemm_skinny_kernel<1, true><<<grid, 256, smem, s>>>(X, W, partials, 0, N, K, g);
+    gemm_skinny_kernel<1, true, 4><<<grid, 256, smem, s>>>(X, W, partials, 0, N, K, g);
     LAUNCH_CHECK(ctx);
     return COMPACT_OK;
 }
