@@ -263,18 +263,21 @@ extern "C" int compact_workspace_bytes(const compact_ctx* ctx, int64_t max_token
 struct Plan {
     std::vector<BlockMeta> meta;
     std::vector<TileItem> rope_tiles, q_tiles;
+    std::vector<TileItem> kv_chunks;   // decode attention work list: (block, first cached row of a chunk)
     int max_len = 0;
     // device views
     const BlockMeta* d_meta = nullptr;
     const TileItem* d_rope_tiles = nullptr;
     const TileItem* d_q_tiles = nullptr;
+    const TileItem* d_kv_chunks = nullptr;
 };
 
 static int upload_plan(compact_ctx* ctx, Plan& p, hipStream_t s) {
     const size_t b0 = align_up(p.meta.size() * sizeof(BlockMeta), 256);
     const size_t b1 = align_up(p.rope_tiles.size() * sizeof(TileItem), 256);
     const size_t b2 = align_up(p.q_tiles.size() * sizeof(TileItem), 256);
-    const size_t total = b0 + b1 + b2;
+    const size_t b3 = align_up(p.kv_chunks.size() * sizeof(TileItem), 256);
+    const size_t total = b0 + b1 + b2 + b3;
     if (total > ctx->meta_bytes) {
         // growing the metadata buffer: wait for work that may still read the old one
         HIP_TRY(ctx, hipDeviceSynchronize());
@@ -297,6 +300,7 @@ static int upload_plan(compact_ctx* ctx, Plan& p, hipStream_t s) {
     memcpy(hs, p.meta.data(), p.meta.size() * sizeof(BlockMeta));
     if (!p.rope_tiles.empty()) memcpy(hs + b0, p.rope_tiles.data(), p.rope_tiles.size() * sizeof(TileItem));
     if (!p.q_tiles.empty()) memcpy(hs + b0 + b1, p.q_tiles.data(), p.q_tiles.size() * sizeof(TileItem));
+    if (!p.kv_chunks.empty()) memcpy(hs + b0 + b1 + b2, p.kv_chunks.data(), p.kv_chunks.size() * sizeof(TileItem));
     HIP_TRY(ctx, hipMemcpyAsync(ctx->d_meta, hs, total, hipMemcpyHostToDevice, s));
     HIP_TRY(ctx, hipEventRecord(ctx->stage_event, s));
     ctx->stage_pending = true;
@@ -304,6 +308,7 @@ static int upload_plan(compact_ctx* ctx, Plan& p, hipStream_t s) {
     p.d_meta = (const BlockMeta*)dm;
     p.d_rope_tiles = (const TileItem*)(dm + b0);
     p.d_q_tiles = (const TileItem*)(dm + b0 + b1);
+    p.d_kv_chunks = (const TileItem*)(dm + b0 + b1 + b2);
     return COMPACT_OK;
 }
 
@@ -358,6 +363,15 @@ static void build_prefill_plan(const compact_kv* kv, int n_blocks, const int32_t
     // causal work of a query tile grows with its row offset: heaviest first
     std::stable_sort(p.q_tiles.begin(), p.q_tiles.end(),
                      [](const TileItem& a, const TileItem& b) { return a.row0 > b.row0; });
+}
+
+// Work list of the split-KV decode attention: every DECODE_CHUNK-row chunk that some
+// step of the call touches, block by block (`extra` = rows the call appends to each
+// cache).  Chunks a given step does not reach yet leave at once.
+static void add_kv_chunks(Plan& p, int extra) {
+    p.kv_chunks.clear();
+    for (int b = 0; b < (int)p.meta.size(); ++b)
+        for (int r = 0; r < p.meta[b].len + extra; r += DECODE_CHUNK) p.kv_chunks.push_back({b, r});
 }
 
 static void build_decode_plan(const compact_kv* kv, int n_blocks, Plan& p) {
@@ -488,8 +502,8 @@ static int run_attn_decode(compact_ctx* ctx, const Plan& p, int n_blocks, int st
                            float* attn_partials, void* o, hipStream_t s) {
     if (ctx->cfg.dtype == COMPACT_BF16) {
         const int max_chunks = chunks_for(p.max_len + step + 1);
-        return launch_attn_decode_bf16(ctx, p.d_meta, n_blocks, step, max_chunks, (const bf16*)q, (const bf16*)kv->d_k,
-                                       (const bf16*)kv->d_v, attn_partials, (bf16*)o, s);
+        return launch_attn_decode_bf16(ctx, p.d_meta, p.d_kv_chunks, (int)p.kv_chunks.size(), n_blocks, step, max_chunks,
+                                       (const bf16*)q, (const bf16*)kv->d_k, (const bf16*)kv->d_v, attn_partials, (bf16*)o, s);
     }
     return launch_attn_decode_f32(ctx, p.d_meta, n_blocks, step, (const float*)q, (const float*)kv->d_k,
                                   (const float*)kv->d_v, (float*)o, s);
@@ -605,6 +619,7 @@ extern "C" int compact_decode_step(compact_ctx* ctx, const compact_weights* w, i
     hipStream_t s = (hipStream_t)hip_stream;
     Plan plan;
     build_decode_plan(kv, n_blocks, plan);
+    add_kv_chunks(plan, 1);
     Carver cv(d_workspace);
     DecodeBufs b;
     carve_decode(cv, ctx->cfg, n_blocks, chunks_for(plan.max_len + 1), b);
@@ -627,6 +642,7 @@ extern "C" int compact_layer_forward(compact_ctx* ctx, const compact_weights* w,
     hipStream_t s = (hipStream_t)hip_stream;
     Plan plan;
     build_prefill_plan(kv, n_blocks, h_cu_seqlens, plan);
+    if (n_steps > 0) add_kv_chunks(plan, n_steps);
     const int64_t T = h_cu_seqlens[n_blocks];
 
     // workspace: [prefill region][prefill y if the caller wants none][decode region]
@@ -784,6 +800,7 @@ extern "C" int compact_attn_decode(compact_ctx* ctx, int32_t n_blocks, const voi
     build_decode_plan(kv, n_blocks, plan);
     for (auto& m : plan.meta) m.len -= 1;  // the kernels attend rows 0..len inclusive
     plan.max_len -= 1;
+    add_kv_chunks(plan, 1);
     const size_t need = attn_decode_partial_floats(ctx->cfg, n_blocks, chunks_for(plan.max_len + 1)) * 4;
     if (ctx->cfg.dtype == COMPACT_BF16 && (!d_workspace || ws_bytes < need))
         return set_err(ctx, COMPACT_EWORKSPACE, "workspace too small for the split-KV partials");

@@ -3,7 +3,8 @@
 // exactly once per step, with 16-byte loads that land directly in the MFMA
 // operand layout (no LDS staging of K/V).
 //
-//  * grid = (chunk, kv head, block); a workgroup owns DECODE_CHUNK cached
+//  * grid = (chunk item, kv head), the items being the (block, chunk) pairs
+//    of the ragged batch listed by the host; a workgroup owns DECODE_CHUNK cached
 //    tokens of one (block, kv head) and all query heads of that KV head's
 //    group (the cache is read once for the whole group).  Chunks are fixed
 //    size, so the split of a block depends on its own length only.
@@ -28,7 +29,8 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 #define DEC_WAVES (DECODE_CHUNK / 32)   // one 32-token window per wavefront
 
 template <int HD>
-__global__ __launch_bounds__(DEC_WAVES * 64) void attn_decode_bf16_kernel(const BlockMeta* __restrict__ meta, int step,
+__global__ __launch_bounds__(DEC_WAVES * 64) void attn_decode_bf16_kernel(const BlockMeta* __restrict__ meta,
+                                                                         const TileItem* __restrict__ chunks, int step,
                                                                          int max_chunks, const bf16* __restrict__ q,
                                                                          const bf16* __restrict__ kbase,
                                                                          const bf16* __restrict__ vbase,
@@ -40,11 +42,11 @@ __global__ __launch_bounds__(DEC_WAVES * 64) void attn_decode_bf16_kernel(const 
     extern __shared__ float so[];  // [DEC_WAVES][G][PLD]
     __shared__ __attribute__((aligned(16))) bf16 qs[16 * HD];   // [G][HD] query rows of the group
 
-    const int b = blockIdx.z, kvh = blockIdx.y, ch = blockIdx.x;
+    const TileItem it = chunks[blockIdx.x];
+    const int b = it.block, kvh = blockIdx.y, c0 = it.row0, ch = c0 / DECODE_CHUNK;
     const BlockMeta bm = meta[b];
     const int n_keys = bm.len + step + 1;
-    const int c0 = ch * DECODE_CHUNK;
-    if (c0 >= n_keys) return;
+    if (c0 >= n_keys) return;   // a chunk this step does not reach yet
     const int G = Hq / Hkv;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int r = lane & 15, c = lane >> 4;
@@ -221,11 +223,12 @@ size_t attn_decode_partial_floats(const compact_layer_cfg& cfg, int n_blocks, in
     return (size_t)n_blocks * cfg.n_q_heads * max_chunks * (cfg.head_dim + 2);
 }
 
-int launch_attn_decode_bf16(compact_ctx* ctx, const BlockMeta* d_meta, int n_blocks, int step, int max_chunks,
-                            const bf16* q, const bf16* d_k, const bf16* d_v, float* partials, bf16* o, hipStream_t s) {
+int launch_attn_decode_bf16(compact_ctx* ctx, const BlockMeta* d_meta, const TileItem* d_chunks, int n_chunks, int n_blocks,
+                            int step, int max_chunks, const bf16* q, const bf16* d_k, const bf16* d_v, float* partials, bf16* o, hipStream_t s) {
     const compact_layer_cfg& c = ctx->cfg;
     const float scale_log2 = LOG2E / sqrtf((float)c.head_dim);
-    dim3 grid(max_chunks, c.n_kv_heads, n_blocks);
+    if (n_chunks == 0) return COMPACT_OK;
+    dim3 grid(n_chunks, c.n_kv_heads);
     dim3 cgrid(c.n_q_heads, n_blocks);
     const size_t smem = (size_t)DEC_WAVES * (c.n_q_heads / c.n_kv_heads) * (c.head_dim + 2) * sizeof(float);
     if (max_chunks > COMBINE_MAX_CHUNKS) return set_err(ctx, COMPACT_ECAPACITY, "KV cache longer than the decode combine supports");
@@ -239,7 +242,7 @@ int launch_attn_decode_bf16(compact_ctx* ctx, const BlockMeta* d_meta, int n_blo
     if (c.head_dim == 128) {
         {
             ProfileScope ps(ctx, COMPACT_K_ATTN_DECODE, s);
-            attn_decode_bf16_kernel<128><<<grid, DEC_WAVES * 64, smem, s>>>(d_meta, step, max_chunks, q, d_k, d_v, partials,
+            attn_decode_bf16_kernel<128><<<grid, DEC_WAVES * 64, smem, s>>>(d_meta, d_chunks, step, max_chunks, q, d_k, d_v, partials,
                                                                            c.n_q_heads, c.n_kv_heads, scale_log2);
         }
         LAUNCH_CHECK(ctx);
@@ -247,7 +250,7 @@ int launch_attn_decode_bf16(compact_ctx* ctx, const BlockMeta* d_meta, int n_blo
     } else {
         {
             ProfileScope ps(ctx, COMPACT_K_ATTN_DECODE, s);
-            attn_decode_bf16_kernel<64><<<grid, DEC_WAVES * 64, smem, s>>>(d_meta, step, max_chunks, q, d_k, d_v, partials,
+            attn_decode_bf16_kernel<64><<<grid, DEC_WAVES * 64, smem, s>>>(d_meta, d_chunks, step, max_chunks, q, d_k, d_v, partials,
                                                                           c.n_q_heads, c.n_kv_heads, scale_log2);
         }
         LAUNCH_CHECK(ctx);

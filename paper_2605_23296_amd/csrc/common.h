@@ -194,7 +194,9 @@ int launch_attn_prefill_bf16(compact_ctx* ctx, const BlockMeta* d_meta, const Ti
 
 // attn_decode.hip (bf16 MFMA, split-KV)
 size_t attn_decode_partial_floats(const compact_layer_cfg& cfg, int n_blocks, int max_chunks);
-int launch_attn_decode_bf16(compact_ctx* ctx, const BlockMeta* d_meta, int n_blocks, int step, int max_chunks,
+// d_chunks: the (block, first row) list of the DECODE_CHUNK-row pieces the call's steps touch
+int launch_attn_decode_bf16(compact_ctx* ctx, const BlockMeta* d_meta, const TileItem* d_chunks, int n_chunks, int n_blocks,
+                            int step, int max_chunks,
                             const bf16* q, const bf16* d_k, const bf16* d_v, float* partials, bf16* o,
                             hipStream_t s);
 
