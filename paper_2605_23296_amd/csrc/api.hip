@@ -560,8 +560,14 @@ static int decode_impl(compact_ctx* ctx, const compact_weights* w, int n_blocks,
             TRY(gemm_partials(ctx, ffn_in, w->w_gate_up, b.partials, N, 2 * c.ffn_dim, c.d_model, &ks, s));
             TRY(launch_swiglu_reduce(ctx, b.partials, ks, b.act, N, c.ffn_dim, s));
         }
-        TRY(gemm_partials(ctx, b.act, w->w_down, b.partials, N, c.d_model, c.ffn_dim, &ks, s));
-        TRY(launch_residual_reduce(ctx, b.partials, ks, b.h, y, N, c.d_model, s));
+        if (bf && resid_out_stream_supported(N, c.d_model, c.ffn_dim)) {
+            ProfileScope ps(ctx, COMPACT_K_GEMM_SKINNY, s);
+            TRY(launch_resid_out_stream(ctx, (const bf16*)b.act, (const bf16*)w->w_down, b.h, (bf16*)y, N, c.d_model,
+                                        c.ffn_dim, s));
+        } else {
+            TRY(gemm_partials(ctx, b.act, w->w_down, b.partials, N, c.d_model, c.ffn_dim, &ks, s));
+            TRY(launch_residual_reduce(ctx, b.partials, ks, b.h, y, N, c.d_model, s));
+        }
     } else {
         if (pending_norm) TRY(launch_rownorm_apply(ctx, (const bf16*)b.hg, rn, (bf16*)b.m, N, c.d_model, s));
         int32_t* idx = route && route->d_expert_idx ? route->d_expert_idx : b.idx;

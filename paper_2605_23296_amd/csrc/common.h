@@ -179,6 +179,10 @@ int launch_skinny_finish(compact_ctx* ctx, const float* partials, int ks, const 
 bool resid_norm_stream_supported(int M, int N, int K);
 int launch_resid_norm_stream(compact_ctx* ctx, const bf16* X, const bf16* W, const bf16* resid, const bf16* g, float* h_out,
                              bf16* hg_out, float* ssq_parts, int M, int N, int K, hipStream_t s);
+// y = bf16(resid_f32 + X W^T), K a multiple of 512
+bool resid_out_stream_supported(int M, int N, int K);
+int launch_resid_out_stream(compact_ctx* ctx, const bf16* X, const bf16* W, const float* resid, bf16* y, int M, int N, int K,
+                            hipStream_t s);
 // m = bf16(hg / rms): finishes the RMSNorm whose sums of squares are in `norm`
 int launch_rownorm_apply(compact_ctx* ctx, const bf16* hg, const RowNorm& norm, bf16* m, int rows, int d, hipStream_t s);
 

@@ -143,17 +143,6 @@ __global__ __launch_bounds__(512) void gemm_skinny_swiglu_kernel(const bf16* __r
 #pragma unroll
     for (int i = 0; i < SG_RING && i < SPW; ++i) ring[i] = *reinterpret_cast<const bf16x8*>(wrow + i * 128);
 
-    // 1/rms of the rows from the column-group sums of squares, added in a fixed
-    // order (lane-strided, then a butterfly): wavefront w finishes rows w and w + 8
-    for (int row = wave; row < MROWS; row += 8) {
-        float ss = 0.f;
-        if (norm.ssq_parts && row < M)
-            for (int pidx = lane; pidx < norm.nparts; pidx += 64) ss += norm.ssq_parts[(size_t)pidx * M + row];
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
-        if (lane == 0) rinv[row] = norm.ssq_parts ? 1.0f / sqrtf(ss * norm.inv_d + norm.eps) : 1.0f;
-    }
-
     // activations: all of K for the M rows
     constexpr int CPR = K / 8;
     for (int q = t; q < MROWS * CPR; q += 512) {
@@ -164,6 +153,18 @@ __global__ __launch_bounds__(512) void gemm_skinny_swiglu_kernel(const bf16* __r
         if (row < M) v = *reinterpret_cast<const bf16x8*>(X + (size_t)row * K + cc * 8);
         *reinterpret_cast<bf16x8*>(xs + row * LDX + cc * 8) = v;
     }
+    // Column-group sums of squares of the rows this wavefront finishes (rows w and
+    // w + 8): only loaded here (behind the weight ring and the activations),
+    // lane-strided; they are added up after the main loop, so nothing waits for them.
+    constexpr int NRW = MROWS / 8, PMAX = 8;   // rows per wavefront; parts per lane (nparts <= 512)
+    float pv[NRW][PMAX];
+#pragma unroll
+    for (int j = 0; j < NRW; ++j)
+#pragma unroll
+        for (int u = 0; u < PMAX; ++u) {
+            const int row = wave + 8 * j, pidx = lane + 64 * u;
+            pv[j][u] = (norm.ssq_parts && row < M && pidx < norm.nparts) ? norm.ssq_parts[(size_t)pidx * M + row] : 0.f;
+        }
     __syncthreads();
 
     floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -180,6 +181,16 @@ __global__ __launch_bounds__(512) void gemm_skinny_swiglu_kernel(const bf16* __r
         if (i + SG_RING < SPW) ring[i % SG_RING] = *reinterpret_cast<const bf16x8*>(wrow + (i + SG_RING) * 128);
     }
 
+    // 1/rms of the rows: a fixed summation order (per lane, then a butterfly)
+#pragma unroll
+    for (int j = 0; j < NRW; ++j) {
+        float ss = 0.f;
+#pragma unroll
+        for (int u = 0; u < PMAX; ++u) ss += pv[j][u];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+        if (lane == 0) rinv[wave + 8 * j] = norm.ssq_parts ? 1.0f / sqrtf(ss * norm.inv_d + norm.eps) : 1.0f;
+    }
     // add the four k-interleaves of each tile in kw order
     *reinterpret_cast<floatx4*>(red + (wave * 64 + lane) * 4) = acc;
     __syncthreads();

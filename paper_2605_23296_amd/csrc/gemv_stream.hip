@@ -97,6 +97,78 @@ int launch_resid_norm_stream(compact_ctx* ctx, const bf16* X, const bf16* W, con
     return COMPACT_OK;
 }
 
+// ---------------------------------------------------------------------------
+// Projection with the closing residual add: y[M, N] = bf16(resid_f32 + X W^T).
+// One tile per workgroup, any K that is a multiple of 512: weight and
+// activation fragments travel through a ring of GS_RING loads per wavefront.
+// ---------------------------------------------------------------------------
+#define GS_RING 7
+__global__ __launch_bounds__(GS_WAVES * 64) void resid_out_stream_kernel(const bf16* __restrict__ X, const bf16* __restrict__ W,
+                                                                          const float* __restrict__ resid, bf16* __restrict__ y,
+                                                                          int M, int N, int K) {
+    __shared__ floatx4 red[GS_WAVES * 64];
+    const int t = threadIdx.x, lane = t & 63, kw = t >> 6;
+    const int r = lane & 15, c = lane >> 4;
+    const int tile = blockIdx.x;
+    const int S = K / (GS_WAVES * 32);   // k-steps per wavefront
+    const bf16* w0 = W + (size_t)(tile * 16 + r) * K + kw * 32 + c * 8;
+    const bf16* x0 = X + (size_t)(r < M ? r : 0) * K + kw * 32 + c * 8;
+    const bool xv = r < M;
+    bf16x8 wf[GS_RING], xf[GS_RING];
+#pragma unroll
+    for (int i = 0; i < GS_RING; ++i) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) xf[i][j] = (bf16)0.f;
+        if (i < S) {
+            wf[i] = *reinterpret_cast<const bf16x8*>(w0 + (size_t)i * GS_WAVES * 32);
+            if (xv) xf[i] = *reinterpret_cast<const bf16x8*>(x0 + (size_t)i * GS_WAVES * 32);
+        }
+    }
+    floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int s0 = 0; s0 < S; s0 += GS_RING) {
+#pragma unroll
+        for (int i = 0; i < GS_RING; ++i) {
+            const int s = s0 + i;
+            if (s < S) {
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[i], xf[i], acc, 0, 0, 0);
+                if (s + GS_RING < S) {
+                    wf[i] = *reinterpret_cast<const bf16x8*>(w0 + (size_t)(s + GS_RING) * GS_WAVES * 32);
+                    if (xv) xf[i] = *reinterpret_cast<const bf16x8*>(x0 + (size_t)(s + GS_RING) * GS_WAVES * 32);
+                }
+            }
+        }
+    }
+    red[kw * 64 + lane] = acc;
+    __syncthreads();
+    if (kw != 0) return;
+    floatx4 v = red[lane];
+#pragma unroll
+    for (int w = 1; w < GS_WAVES; ++w) {
+        const floatx4 o = red[w * 64 + lane];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] += o[e];
+    }
+    // v[e]: activation row r, output column n = tile*16 + 4c + e
+    if (r < M) {
+        const size_t o = (size_t)r * N + tile * 16 + 4 * c;
+        const floatx4 h = *reinterpret_cast<const floatx4*>(resid + o);
+        bf16x4 out;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) out[e] = (bf16)(h[e] + v[e]);
+        *reinterpret_cast<bf16x4*>(y + o) = out;
+    }
+}
+
+bool resid_out_stream_supported(int M, int N, int K) { return M >= 1 && M <= 16 && N % 16 == 0 && K >= 512 && K % 512 == 0; }
+
+int launch_resid_out_stream(compact_ctx* ctx, const bf16* X, const bf16* W, const float* resid, bf16* y, int M, int N, int K,
+                            hipStream_t s) {
+    if (!resid_out_stream_supported(M, N, K)) return set_err(ctx, COMPACT_ESHAPE, "residual streaming kernel does not cover this shape");
+    resid_out_stream_kernel<<<N / 16, GS_WAVES * 64, 0, s>>>(X, W, resid, y, M, N, K);
+    LAUNCH_CHECK(ctx);
+    return COMPACT_OK;
+}
+
 // m[r][c] = bf16(hg[r][c] / rms_r), 1 / rms from the column sums of squares
 __global__ __launch_bounds__(256) void rownorm_apply_kernel(const bf16* __restrict__ hg, const RowNorm norm, bf16* __restrict__ m,
                                                             int rows, int d) {
