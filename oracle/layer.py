@@ -287,6 +287,52 @@ class Layer:
             routes.append([(st[b]["idx"], st[b]["gate"], st[b]["logits"]) for b in range(N)])
         return pre, y_dec, Ks, Vs, routes
 
+    # -- prefix-aware layout ------------------------------------------------
+    def decode_block_prefix(self, x, Kp, Vp, prefix_len, Kt, Vt):
+        """One new token of worker k in the prefix-aware target-at-end layout
+        (paper Sec. IV, Dispatch: worker k's prompt is blocks 1..k in order, so
+        every worker's prefix extends the previous one's and its cache is
+        shared).  The worker sees the first `prefix_len` rows of the shared
+        cache (Kp, Vp: the whole history, computed once) followed by its own
+        private tail (Kt, Vt: the tokens it has generated so far).  The new
+        token sits at position prefix_len + len(tail); its K/V row is appended
+        to the tail.  Returns dict with y [d], Kt, Vt grown by one row."""
+        x = _f64(x).reshape(1, self.d)
+        n_tail = Kt.shape[0]
+        q, k, v = self.qkv(x, np.array([prefix_len + n_tail]))
+        Kt = np.concatenate([Kt, k], axis=0)
+        Vt = np.concatenate([Vt, v], axis=0)
+        K = np.concatenate([Kp[:prefix_len], Kt], axis=0)
+        V = np.concatenate([Vp[:prefix_len], Vt], axis=0)
+        o = gqa_attention(q, K, V, visible=np.array([K.shape[0]]))
+        h = x + o.reshape(1, self.Dq) @ _f64(self.w["w_o"]).T
+        y, idx, gate, logits = self.ffn(h)
+        return dict(y=y[0], Kt=Kt, Vt=Vt,
+                    idx=None if idx is None else idx[0],
+                    gate=None if gate is None else gate[0],
+                    logits=None if logits is None else logits[0])
+
+    def forward_prefix(self, x_history, cu_seqlens, x_decode, rows=None):
+        """Prefix-aware pass: the history is prefilled once as ONE causal
+        sequence (every worker's prompt is a prefix of it, so its cache rows are
+        the workers' shared prefix), then worker b decodes S tokens against rows
+        0 .. cu[b+1]-1 of that cache plus its own tail.  x_decode [S, N, d].
+        Returns (prefill dict of the whole history, y_decode [S, N, d],
+        tail K list, tail V list)."""
+        pre = self.prefill_block(_f64(x_history), 0, rows)
+        Kp, Vp = pre["K"], pre["V"]
+        N = len(cu_seqlens) - 1
+        S = 0 if x_decode is None else x_decode.shape[0]
+        Kt = [np.zeros((0, self.Hkv, self.hd), dtype=F64) for _ in range(N)]
+        Vt = [np.zeros((0, self.Hkv, self.hd), dtype=F64) for _ in range(N)]
+        y_dec = np.zeros((S, N, self.d), dtype=F64)
+        for s in range(S):
+            for b in range(N):
+                st = self.decode_block_prefix(x_decode[s, b], Kp, Vp, int(cu_seqlens[b + 1]), Kt[b], Vt[b])
+                y_dec[s, b] = st["y"]
+                Kt[b], Vt[b] = st["Kt"], st["Vt"]
+        return pre, y_dec, Kt, Vt
+
     def forward_sampled(self, x_prefill, cu_seqlens, x_decode, rows, steps, pos_offset=None):
         """The same pass, evaluated only at sampled places (for workloads too
         large to check everywhere).  Because the decode-step inputs are given

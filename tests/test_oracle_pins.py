@@ -400,3 +400,75 @@ def test_linear_is_x_times_w_transposed(rng):
     w = rng.standard_normal((4, 5))
     want = np.array([[sum(x[i, k] * w[j, k] for k in range(5)) for j in range(4)] for i in range(3)])
     np.testing.assert_allclose(O.linear(x, w), want, atol=1e-14)
+
+
+# ---------------------------------------------------------------------------
+# prefix-aware layout (paper Sec. IV, Dispatch: worker k's prompt is blocks 1..k)
+# ---------------------------------------------------------------------------
+def _small_layer(rng, moe=False):
+    cfg = dict(d_model=64, n_q_heads=4, n_kv_heads=2, head_dim=16, ffn_dim=96, n_experts=8 if moe else 0,
+               top_k=2 if moe else 0, rms_eps=1e-5, rope_theta=10000.0)
+    d, Dq, Dkv, F = 64, 64, 32, 96
+    w = dict(g_attn=1 + 0.1 * rng.standard_normal(d), g_ffn=1 + 0.1 * rng.standard_normal(d),
+             w_qkv=0.2 * rng.standard_normal((Dq + 2 * Dkv, d)), w_o=0.2 * rng.standard_normal((d, Dq)))
+    if moe:
+        w.update(w_router=rng.standard_normal((8, d)), w_exp_gate_up=0.2 * rng.standard_normal((8, 2 * F, d)),
+                 w_exp_down=0.2 * rng.standard_normal((8, d, F)))
+    else:
+        w.update(w_gate_up=0.2 * rng.standard_normal((2 * F, d)), w_down=0.2 * rng.standard_normal((d, F)))
+    return O.Layer(cfg, w)
+
+
+@pytest.mark.parametrize("moe", [False, True])
+def test_prefix_aware_worker_equals_a_lone_run_on_its_truncated_history(rng, moe):
+    """Worker k of the prefix-aware layout sees blocks 1..k and nothing else: its
+    decode outputs must equal those of an ordinary single-block run whose block is
+    the history cut after block k (a different code path: one private cache)."""
+    lay = _small_layer(rng, moe)
+    lens = [5, 9, 3, 7]
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    x = rng.standard_normal((cu[-1], 64))
+    xd = rng.standard_normal((4, len(lens), 64))
+    pre, yd, Kt, Vt = lay.forward_prefix(x, cu, xd)
+    for b in range(len(lens)):
+        T_b = int(cu[b + 1])
+        pre1, yd1, Ks1, Vs1, _ = lay.forward(x[:T_b], [0, T_b], xd[:, b:b + 1])
+        np.testing.assert_allclose(yd[:, b], yd1[:, 0], rtol=1e-10, atol=1e-12)
+        np.testing.assert_allclose(Kt[b], Ks1[0][T_b:], rtol=1e-10, atol=1e-12)
+        np.testing.assert_allclose(Vt[b], Vs1[0][T_b:], rtol=1e-10, atol=1e-12)
+        # the shared cache rows of the worker's prefix are those of the lone run too
+        np.testing.assert_allclose(pre["K"][:T_b], pre1[0]["K"], rtol=1e-10, atol=1e-12)
+
+
+def test_prefix_aware_worker_ignores_the_history_after_its_block(rng):
+    lay = _small_layer(rng)
+    lens = [6, 4, 8]
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    x = rng.standard_normal((cu[-1], 64))
+    xd = rng.standard_normal((3, 3, 64))
+    _, yd, _, _ = lay.forward_prefix(x, cu, xd)
+    x2 = x.copy()
+    x2[cu[2]:] += 3.0                      # perturb block 3 only
+    _, yd2, _, _ = lay.forward_prefix(x2, cu, xd)
+    np.testing.assert_array_equal(yd[:, :2], yd2[:, :2])
+    assert np.abs(yd[:, 2] - yd2[:, 2]).max() > 1e-3
+
+
+def test_prefix_aware_identical_keys_give_the_mean_over_prefix_and_tail(rng):
+    """Zero query weights: every score is 0, so the attention output is the plain mean
+    of the values over the worker's prefix rows and its tail rows (the new token
+    included) -- checks which rows a worker sees."""
+    lay = _small_layer(rng)
+    lay.w["w_qkv"][:lay.Dq] = 0.0
+    lens = [4, 6]
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    x = rng.standard_normal((cu[-1], 64))
+    xd = rng.standard_normal((2, 2, 64))
+    pre, yd, Kt, Vt = lay.forward_prefix(x, cu, xd)
+    for b in range(2):
+        V = np.concatenate([pre["V"][:cu[b + 1]], Vt[b]], axis=0)          # [rows, Hkv, hd]
+        mean_v = V.mean(axis=0)                                             # after both steps
+        o = np.repeat(mean_v, lay.Hq // lay.Hkv, axis=0).reshape(-1)
+        h = xd[1, b] + o @ lay.w["w_o"].T
+        y, _, _, _ = lay.ffn(h[None])
+        np.testing.assert_allclose(yd[1, b], y[0], rtol=1e-10, atol=1e-12)
