@@ -161,6 +161,35 @@ int compact_layer_forward(compact_ctx* ctx, const compact_weights* w, int32_t n_
                           void* d_y_last, void* d_y_decode, void* d_workspace, size_t ws_bytes,
                           void* hip_stream);
 
+/* ---- prefix-aware target-at-end layout (paper Sec. IV, Dispatch: worker k's
+ * prompt is blocks 1..k in order; "Prefix-aware target-at-end layout": every
+ * worker's prefix strictly extends the previous one's, so one cache of the
+ * whole history serves all of them) -----------------------------------------
+ * The history is prefilled ONCE as a single block (compact_prefill with
+ * n_blocks = 1, rows 0..T-1 at positions 0..T-1): `shared` is that one-block
+ * compact_kv and stays read-only.  Worker b sees its first h_prefix_len[b] rows
+ * (the end of its block k: h_prefix_len must not decrease with b, each at most
+ * shared->h_len[0]) followed by its own private tail: `tails` is a compact_kv
+ * with one slab per worker holding the tokens that worker has generated
+ * (h_len[b] of them; h_pos_offset is ignored).
+ *
+ * compact_prefix_decode_step advances all N <= 64 workers by one token: d_x
+ * [N, d] holds worker b's new token at rotary position h_prefix_len[b] +
+ * tails->h_len[b]; its K/V row is appended to tail b, it attends the shared rows
+ * 0..h_prefix_len[b]-1 and tail rows 0..h_len[b] inclusive, tails->h_len[b] is
+ * incremented, d_y [N, d] receives the layer outputs.  The shared rows are read
+ * from memory once per step for all workers together (a 256-row chunk is
+ * multiplied with the query heads of every worker whose prefix covers it).
+ * bf16 storage only.  Errors as compact_decode_step; COMPACT_EINVAL for a
+ * decreasing or out-of-range h_prefix_len.  The workspace must hold
+ * compact_prefix_workspace_bytes(ctx, N, max h_prefix_len, max tail length). */
+int compact_prefix_workspace_bytes(const compact_ctx* ctx, int32_t n_workers, int32_t max_prefix_len,
+                                   int32_t max_tail_len, size_t* bytes);
+int compact_prefix_decode_step(compact_ctx* ctx, const compact_weights* w, int32_t n_workers,
+                               const void* d_x, const compact_kv* shared, const int32_t* h_prefix_len,
+                               compact_kv* tails, void* d_y, const compact_route_out* route,
+                               void* d_workspace, size_t ws_bytes, void* hip_stream);
+
 /* ---- per-kernel timing ----------------------------------------------------
  * When enabled, every launch of the selected kernel class is bracketed by HIP
  * events on the launch stream.  compact_profile_read synchronises those
@@ -201,6 +230,14 @@ int compact_attn_prefill(compact_ctx* ctx, int32_t n_blocks, const int32_t* h_cu
  * q [N, Dq] -> o [N, Dq].                                                    */
 int compact_attn_decode(compact_ctx* ctx, int32_t n_blocks, const void* d_q, const compact_kv* kv,
                         void* d_o, void* d_workspace, size_t ws_bytes, void* hip_stream);
+/* Prefix-aware decode attention alone: worker b's query q [N, Dq] against rows
+ * 0..h_prefix_len[b]-1 of the shared block and rows 0..tails->h_len[b]-1 of its
+ * tail (h_len >= 1: the current token's row is already there).  o [N, Dq].
+ * The workspace holds the per-item records.                                  */
+int compact_attn_decode_prefix(compact_ctx* ctx, int32_t n_workers, const void* d_q,
+                               const compact_kv* shared, const int32_t* h_prefix_len,
+                               const compact_kv* tails, void* d_o, void* d_workspace, size_t ws_bytes,
+                               void* hip_stream);
 /* Router: logits in fp32, top-k ids (descending, ties to the lower id) and
  * softmax gate over the selected logits, for rows of m [rows, d].           */
 int compact_moe_route(compact_ctx* ctx, const void* d_m, const void* d_w_router, int64_t rows,

@@ -24,6 +24,7 @@ EXPORTS = [
     "compact_profile_select", "compact_profile_read",
     "compact_rmsnorm", "compact_rope_kvwrite", "compact_gemm", "compact_attn_prefill",
     "compact_attn_decode", "compact_moe_route", "compact_moe_ffn",
+    "compact_prefix_workspace_bytes", "compact_prefix_decode_step", "compact_attn_decode_prefix",
 ]
 
 
@@ -88,6 +89,9 @@ def lib():
     L.compact_attn_decode.argtypes = [vp, i32, vp, P(KV), vp, vp, sz, vp]
     L.compact_moe_route.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, sz, vp]
     L.compact_moe_ffn.argtypes = [vp, P(Weights), vp, vp, vp, vp, i64, vp, vp, sz, vp]
+    L.compact_prefix_workspace_bytes.argtypes = [vp, i32, i32, i32, P(sz)]
+    L.compact_prefix_decode_step.argtypes = [vp, P(Weights), i32, vp, P(KV), P(i32), P(KV), vp, P(RouteOut), vp, sz, vp]
+    L.compact_attn_decode_prefix.argtypes = [vp, i32, vp, P(KV), P(i32), P(KV), vp, vp, sz, vp]
     for name in EXPORTS:
         fn = getattr(L, name)
         if name not in ("compact_destroy", "compact_last_error"):
@@ -224,6 +228,23 @@ class Layer:
         self.check(self.L.compact_layer_forward(
             self.ctx, C.byref(self.w), len(cu_seqlens) - 1, _i32arr(cu_seqlens), _ptr(x_prefill), S,
             _ptr(x_decode), C.byref(kv.c), _ptr(y_prefill), _ptr(y_last), _ptr(y_decode), wsp, wsn, _stream()))
+
+    # -- prefix-aware layout ------------------------------------------------------
+    def prefix_workspace_bytes(self, n_workers, max_prefix_len, max_tail_len):
+        n = C.c_size_t()
+        self.check(self.L.compact_prefix_workspace_bytes(self.ctx, n_workers, max_prefix_len, max_tail_len, C.byref(n)))
+        return n.value
+
+    def compact_prefix_decode_step(self, x, shared, prefix_len, tails, y, route=None):
+        wsp, wsn = self._ws()
+        r = None if route is None else C.byref(RouteOut(route[0].data_ptr(), route[1].data_ptr()))
+        self.check(self.L.compact_prefix_decode_step(self.ctx, C.byref(self.w), tails.N, _ptr(x), C.byref(shared.c),
+                                                     _i32arr(prefix_len), C.byref(tails.c), _ptr(y), r, wsp, wsn, _stream()))
+
+    def compact_attn_decode_prefix(self, q, shared, prefix_len, tails, o):
+        wsp, wsn = self._ws()
+        self.check(self.L.compact_attn_decode_prefix(self.ctx, tails.N, _ptr(q), C.byref(shared.c), _i32arr(prefix_len),
+                                                     C.byref(tails.c), _ptr(o), wsp, wsn, _stream()))
 
     # -- profiling --------------------------------------------------------------
     def compact_profile_select(self, klass):

@@ -270,6 +270,8 @@ struct Plan {
     const TileItem* d_rope_tiles = nullptr;
     const TileItem* d_q_tiles = nullptr;
     const TileItem* d_kv_chunks = nullptr;
+    std::vector<char> extra;           // further host-built tables, uploaded behind the lists
+    const char* d_extra = nullptr;
 };
 
 static int upload_plan(compact_ctx* ctx, Plan& p, hipStream_t s) {
@@ -277,7 +279,8 @@ static int upload_plan(compact_ctx* ctx, Plan& p, hipStream_t s) {
     const size_t b1 = align_up(p.rope_tiles.size() * sizeof(TileItem), 256);
     const size_t b2 = align_up(p.q_tiles.size() * sizeof(TileItem), 256);
     const size_t b3 = align_up(p.kv_chunks.size() * sizeof(TileItem), 256);
-    const size_t total = b0 + b1 + b2 + b3;
+    const size_t b4 = align_up(p.extra.size(), 256);
+    const size_t total = b0 + b1 + b2 + b3 + b4;
     if (total > ctx->meta_bytes) {
         // growing the metadata buffer: wait for work that may still read the old one
         HIP_TRY(ctx, hipDeviceSynchronize());
@@ -301,6 +304,7 @@ static int upload_plan(compact_ctx* ctx, Plan& p, hipStream_t s) {
     if (!p.rope_tiles.empty()) memcpy(hs + b0, p.rope_tiles.data(), p.rope_tiles.size() * sizeof(TileItem));
     if (!p.q_tiles.empty()) memcpy(hs + b0 + b1, p.q_tiles.data(), p.q_tiles.size() * sizeof(TileItem));
     if (!p.kv_chunks.empty()) memcpy(hs + b0 + b1 + b2, p.kv_chunks.data(), p.kv_chunks.size() * sizeof(TileItem));
+    if (!p.extra.empty()) memcpy(hs + b0 + b1 + b2 + b3, p.extra.data(), p.extra.size());
     HIP_TRY(ctx, hipMemcpyAsync(ctx->d_meta, hs, total, hipMemcpyHostToDevice, s));
     HIP_TRY(ctx, hipEventRecord(ctx->stage_event, s));
     ctx->stage_pending = true;
@@ -309,6 +313,7 @@ static int upload_plan(compact_ctx* ctx, Plan& p, hipStream_t s) {
     p.d_rope_tiles = (const TileItem*)(dm + b0);
     p.d_q_tiles = (const TileItem*)(dm + b0 + b1);
     p.d_kv_chunks = (const TileItem*)(dm + b0 + b1 + b2);
+    p.d_extra = dm + b0 + b1 + b2 + b3;
     return COMPACT_OK;
 }
 
@@ -509,11 +514,23 @@ static int run_attn_decode(compact_ctx* ctx, const Plan& p, int n_blocks, int st
                                   (const float*)kv->d_v, (float*)o, s);
 }
 
+// Prefix-aware layout: what the decode step needs besides the per-worker tails.
+struct PrefixArgs {
+    BlockMeta shared;             // the one shared block (the whole history)
+    const void *d_k, *d_v;        // its slabs
+    std::vector<PrefixItem> items;
+    std::vector<int32_t> wl_off, wl;
+    int64_t total_recs = 0;
+    int max_list = 0;
+    size_t off_items = 0, off_wl_off = 0, off_wl = 0;   // byte offsets inside Plan::extra
+    float* records = nullptr;
+};
+
 // one decode step for all blocks; plan.meta.len = cached tokens before step 0.
 // n_pre (nullable) = RMSNorm(x; g_attn) already computed for this step's rows.
 static int decode_impl(compact_ctx* ctx, const compact_weights* w, int n_blocks, int step, const void* x,
                        const void* n_pre, compact_kv* kv, void* y, const compact_route_out* route, const DecodeBufs& b,
-                       const Plan& plan, hipStream_t s) {
+                       const Plan& plan, hipStream_t s, const PrefixArgs* pfx = nullptr) {
     const compact_layer_cfg& c = ctx->cfg;
     const int N = n_blocks;
     const int Dq = c.n_q_heads * c.head_dim, Dtot = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
@@ -525,7 +542,15 @@ static int decode_impl(compact_ctx* ctx, const compact_weights* w, int n_blocks,
     }
     TRY(gemm_partials(ctx, n, w->w_qkv, b.partials, N, Dtot, c.d_model, &ks, s));
     TRY(launch_decode_qkv_epilogue(ctx, plan.d_meta, N, step, b.partials, ks, b.q, kv->d_k, kv->d_v, s));
-    TRY(run_attn_decode(ctx, plan, N, step, b.q, kv, b.attn_partials, b.o, s));
+    if (pfx) {
+        TRY(launch_attn_decode_prefix_bf16(ctx, plan.d_meta, pfx->shared, (const PrefixItem*)(plan.d_extra + pfx->off_items),
+                                           (int)pfx->items.size(), (const int32_t*)(plan.d_extra + pfx->off_wl_off),
+                                           (const int32_t*)(plan.d_extra + pfx->off_wl), pfx->max_list, N, step,
+                                           (const bf16*)b.q, (const bf16*)pfx->d_k, (const bf16*)pfx->d_v, (const bf16*)kv->d_k,
+                                           (const bf16*)kv->d_v, pfx->records, pfx->total_recs, (bf16*)b.o, s));
+    } else {
+        TRY(run_attn_decode(ctx, plan, N, step, b.q, kv, b.attn_partials, b.o, s));
+    }
     // O projection + residual, and the RMSNorm that feeds the FFN.  bf16 storage with
     // few rows: one whole-K kernel leaves h, the un-normalised FFN input h * g and the
     // row sums of squares; whoever consumes the input applies 1/rms.
@@ -682,6 +707,151 @@ extern "C" int compact_layer_forward(compact_ctx* ctx, const compact_weights* w,
     }
     for (int b = 0; b < n_blocks; ++b) kv->h_len[b] = h_cu_seqlens[b + 1] - h_cu_seqlens[b] + n_steps;
     return COMPACT_OK;
+}
+
+// ---------------------------------------------------------------------------
+// prefix-aware layout: shared prefix + private tails
+// ---------------------------------------------------------------------------
+static int64_t prefix_max_recs(const compact_layer_cfg& c, int n_workers, int max_prefix_len, int max_tail_len) {
+    const int G = c.n_q_heads / c.n_kv_heads;
+    return ((int64_t)chunks_for(max_prefix_len) * n_workers + (int64_t)n_workers * chunks_for(max_tail_len + 1)) * G;
+}
+
+extern "C" int compact_prefix_workspace_bytes(const compact_ctx* ctx, int32_t n_workers, int32_t max_prefix_len,
+                                              int32_t max_tail_len, size_t* bytes) {
+    if (!ctx || !bytes) return COMPACT_EINVAL;
+    compact_ctx* c = const_cast<compact_ctx*>(ctx);
+    if (n_workers < 1 || max_prefix_len < 0 || max_tail_len < 1)
+        return set_err(c, COMPACT_EINVAL, "n_workers >= 1, max_prefix_len >= 0, max_tail_len >= 1 required");
+    Carver cd(nullptr);
+    DecodeBufs db;
+    carve_decode(cd, ctx->cfg, n_workers, 1, db);
+    const size_t recs = (size_t)prefix_max_recs(ctx->cfg, n_workers, max_prefix_len, max_tail_len) * ctx->cfg.n_kv_heads *
+                        (ctx->cfg.head_dim + 2) * 4;
+    *bytes = align_up(cd.off, 256) + align_up(recs, 256) + 256;
+    return COMPACT_OK;
+}
+
+// Validates the prefix-aware arguments and builds the tail metadata, the work items and the
+// per-worker item lists.  `steps` = tokens this call appends to every tail.
+static int build_prefix_plan(compact_ctx* ctx, int n_workers, const compact_kv* shared, const int32_t* h_prefix_len,
+                             const compact_kv* tails, int steps, Plan& plan, PrefixArgs& pa) {
+    const compact_layer_cfg& c = ctx->cfg;
+    if (c.dtype != COMPACT_BF16) return set_err(ctx, COMPACT_EUNSUPPORTED, "the prefix-aware decode path exists for bf16 storage only");
+    if (n_workers < 1 || n_workers > 64) return set_err(ctx, COMPACT_EINVAL, "n_workers must be in 1..64");
+    if (!h_prefix_len) return set_err(ctx, COMPACT_EINVAL, "null h_prefix_len");
+    TRY(check_kv(ctx, shared, 1));
+    TRY(check_kv(ctx, tails, n_workers));
+    const int shared_len = shared->h_len[0];
+    if (shared_len < 0 || shared_len > shared->h_capacity[0]) return set_err(ctx, COMPACT_ECAPACITY, "shared h_len must be in 0..capacity");
+    for (int b = 0; b < n_workers; ++b) {
+        if (h_prefix_len[b] < 0 || h_prefix_len[b] > shared_len)
+            return set_err(ctx, COMPACT_EINVAL, "h_prefix_len[b] must be in 0..shared h_len");
+        if (b > 0 && h_prefix_len[b] < h_prefix_len[b - 1])
+            return set_err(ctx, COMPACT_EINVAL, "h_prefix_len must not decrease (every worker's prefix extends the previous one's)");
+        if (tails->h_len[b] < 0 || (int64_t)tails->h_len[b] + steps > tails->h_capacity[b])
+            return set_err(ctx, COMPACT_ECAPACITY, "worker " + std::to_string(b) + ": tail len + steps exceeds its slab");
+    }
+    plan.meta.resize(n_workers);
+    for (int b = 0; b < n_workers; ++b) {
+        BlockMeta& m = plan.meta[b];
+        m.row0 = b;
+        m.len = tails->h_len[b];
+        m.capacity = tails->h_capacity[b];
+        m.pos_offset = h_prefix_len[b];   // the new token's rotary position is prefix_len + tail len
+        m.slab = tails->h_slab_offset[b];
+        plan.max_len = std::max(plan.max_len, m.len);
+    }
+    pa.shared.row0 = 0;
+    pa.shared.len = shared_len;
+    pa.shared.capacity = shared->h_capacity[0];
+    pa.shared.pos_offset = 0;
+    pa.shared.slab = shared->h_slab_offset[0];
+    pa.d_k = shared->d_k;
+    pa.d_v = shared->d_v;
+    const int G = c.n_q_heads / c.n_kv_heads;
+    const int max_prefix = h_prefix_len[n_workers - 1];
+    std::vector<std::vector<int32_t>> lists(n_workers);
+    int32_t rec = 0;
+    int w0 = 0;
+    for (int r0 = 0; r0 < max_prefix; r0 += DECODE_CHUNK) {
+        while (h_prefix_len[w0] <= r0) ++w0;   // first worker whose prefix reaches into the chunk
+        PrefixItem it{r0, std::min(DECODE_CHUNK, max_prefix - r0), w0, n_workers - w0, 0, rec};
+        for (int b = w0; b < n_workers; ++b) lists[b].push_back((int32_t)pa.items.size());
+        pa.items.push_back(it);
+        rec += it.nw * G;
+    }
+    for (int b = 0; b < n_workers; ++b)
+        for (int r0 = 0; r0 < tails->h_len[b] + steps; r0 += DECODE_CHUNK) {
+            PrefixItem it{r0, DECODE_CHUNK, b, 1, 1, rec};
+            lists[b].push_back((int32_t)pa.items.size());
+            pa.items.push_back(it);
+            rec += G;
+        }
+    pa.total_recs = rec;
+    pa.wl_off.assign(1, 0);
+    for (int b = 0; b < n_workers; ++b) {
+        pa.max_list = std::max(pa.max_list, (int)lists[b].size());
+        pa.wl.insert(pa.wl.end(), lists[b].begin(), lists[b].end());
+        pa.wl_off.push_back((int32_t)pa.wl.size());
+    }
+    // pack the tables behind the plan's lists
+    pa.off_items = 0;
+    pa.off_wl_off = align_up(pa.items.size() * sizeof(PrefixItem), 16);
+    pa.off_wl = pa.off_wl_off + align_up(pa.wl_off.size() * 4, 16);
+    plan.extra.assign(pa.off_wl + pa.wl.size() * 4 + 16, 0);
+    memcpy(plan.extra.data() + pa.off_items, pa.items.data(), pa.items.size() * sizeof(PrefixItem));
+    memcpy(plan.extra.data() + pa.off_wl_off, pa.wl_off.data(), pa.wl_off.size() * 4);
+    if (!pa.wl.empty()) memcpy(plan.extra.data() + pa.off_wl, pa.wl.data(), pa.wl.size() * 4);
+    return COMPACT_OK;
+}
+
+extern "C" int compact_prefix_decode_step(compact_ctx* ctx, const compact_weights* w, int32_t n_workers, const void* d_x,
+                                          const compact_kv* shared, const int32_t* h_prefix_len, compact_kv* tails,
+                                          void* d_y, const compact_route_out* route, void* d_workspace, size_t ws_bytes,
+                                          void* hip_stream) {
+    if (!ctx) return COMPACT_EINVAL;
+    TRY(check_weights(ctx, w));
+    if (!d_x || !d_y) return set_err(ctx, COMPACT_EINVAL, "null input or output");
+    if (!d_workspace) return set_err(ctx, COMPACT_EWORKSPACE, "null workspace");
+    if (!shared || !tails) return set_err(ctx, COMPACT_EINVAL, "null shared or tails");
+    hipStream_t s = (hipStream_t)hip_stream;
+    Plan plan;
+    PrefixArgs pa;
+    TRY(build_prefix_plan(ctx, n_workers, shared, h_prefix_len, tails, 1, plan, pa));
+    Carver cv(d_workspace);
+    DecodeBufs b;
+    carve_decode(cv, ctx->cfg, n_workers, 1, b);
+    pa.records = (float*)cv.take((size_t)pa.total_recs * ctx->cfg.n_kv_heads * (ctx->cfg.head_dim + 2) * 4);
+    if (cv.off > ws_bytes) return set_err(ctx, COMPACT_EWORKSPACE, "workspace too small for this prefix-aware decode step");
+    TRY(upload_plan(ctx, plan, s));
+    TRY(decode_impl(ctx, w, n_workers, 0, d_x, nullptr, tails, d_y, route, b, plan, s, &pa));
+    for (int b2 = 0; b2 < n_workers; ++b2) tails->h_len[b2] += 1;
+    return COMPACT_OK;
+}
+
+extern "C" int compact_attn_decode_prefix(compact_ctx* ctx, int32_t n_workers, const void* d_q, const compact_kv* shared,
+                                          const int32_t* h_prefix_len, const compact_kv* tails, void* d_o,
+                                          void* d_workspace, size_t ws_bytes, void* hip_stream) {
+    if (!ctx) return COMPACT_EINVAL;
+    if (!d_q || !d_o) return set_err(ctx, COMPACT_EINVAL, "null q or o");
+    if (!shared || !tails) return set_err(ctx, COMPACT_EINVAL, "null shared or tails");
+    hipStream_t s = (hipStream_t)hip_stream;
+    Plan plan;
+    PrefixArgs pa;
+    // the hook attends tail rows 0 .. h_len-1: plan it as the step that appended the last of them
+    for (int b = 0; b < n_workers && tails->h_len; ++b)
+        if (tails->h_len[b] < 1) return set_err(ctx, COMPACT_EINVAL, "every tail must hold at least the current token");
+    TRY(build_prefix_plan(ctx, n_workers, shared, h_prefix_len, tails, 0, plan, pa));
+    for (auto& m : plan.meta) m.len -= 1;
+    const size_t need = (size_t)pa.total_recs * ctx->cfg.n_kv_heads * (ctx->cfg.head_dim + 2) * 4;
+    if (!d_workspace || ws_bytes < need) return set_err(ctx, COMPACT_EWORKSPACE, "workspace too small for the prefix-aware records");
+    TRY(upload_plan(ctx, plan, s));
+    return launch_attn_decode_prefix_bf16(ctx, plan.d_meta, pa.shared, (const PrefixItem*)(plan.d_extra + pa.off_items),
+                                          (int)pa.items.size(), (const int32_t*)(plan.d_extra + pa.off_wl_off),
+                                          (const int32_t*)(plan.d_extra + pa.off_wl), pa.max_list, n_workers, 0, (const bf16*)d_q,
+                                          (const bf16*)shared->d_k, (const bf16*)shared->d_v, (const bf16*)tails->d_k,
+                                          (const bf16*)tails->d_v, (float*)d_workspace, pa.total_recs, (bf16*)d_o, s);
 }
 
 // ---------------------------------------------------------------------------

@@ -45,6 +45,14 @@ struct TileItem {  // (block, first block-local row) of a row tile
     int32_t row0;
 };
 
+// Work item of the prefix-aware decode attention: rows row0 .. row0 + n_rows - 1 of
+// the shared slab (tail = 0) for workers w0 .. w0 + nw - 1, or a chunk of worker w0's
+// private tail slab (tail = 1, nw = 1; its live rows follow from the tail length).
+// rec0 = index of the item's first (worker, head-in-group) record.
+struct PrefixItem {
+    int32_t row0, n_rows, w0, nw, tail, rec0;
+};
+
 struct ProfileSlot {
     hipEvent_t start, stop;
 };
@@ -203,6 +211,13 @@ int launch_attn_decode_bf16(compact_ctx* ctx, const BlockMeta* d_meta, const Til
                             int step, int max_chunks,
                             const bf16* q, const bf16* d_k, const bf16* d_v, float* partials, bf16* o,
                             hipStream_t s);
+
+// attn_decode_prefix.hip (bf16): cascade over the shared prefix + private tails
+int launch_attn_decode_prefix_bf16(compact_ctx* ctx, const BlockMeta* d_tail_meta, const BlockMeta& shared,
+                                   const PrefixItem* d_items, int n_items, const int32_t* d_wl_off, const int32_t* d_wl,
+                                   int max_list, int n_workers, int step, const bf16* q, const bf16* kshared,
+                                   const bf16* vshared, const bf16* ktail, const bf16* vtail, float* records,
+                                   int64_t total_recs, bf16* o, hipStream_t s);
 
 // moe.hip
 struct MoePlan {              // device buffers carved from the workspace
