@@ -138,3 +138,42 @@ def test_kernel_hooks_reject_bad_arguments_without_a_device():
     assert L.compact_attn_decode(ctx, 1, p, C.byref(kv), p, None, 0, None) == 3   # empty cache
     blay = _fake_layer("dense_8x4096")
     assert blay.L.compact_gemm(blay.ctx, p, p, None, p, 128, 64, 100, 0, None, 0, None) == 2
+
+
+def test_prefix_aware_calls_reject_bad_arguments_without_a_device():
+    lay = _fake_layer("dense_8x4096")
+    L, ctx, w = lay.L, lay.ctx, C.byref(lay.w)
+    x = C.c_void_p(0x30000)
+    ws = C.c_void_p(0x40000)
+    shared, ks = _kv([1024], [1000])
+    tails, kt = _kv([64, 64, 64], [0, 3, 64])
+
+    def step(prefix, tails=tails, shared=shared, n=3, ws=ws, x=x):
+        pl = (C.c_int32 * len(prefix))(*prefix) if prefix is not None else None
+        return L.compact_prefix_decode_step(ctx, w, n, x, C.byref(shared) if shared is not None else None, pl,
+                                            C.byref(tails) if tails is not None else None, x, None, ws, 1 << 30, None)
+
+    assert step([100, 200, 300]) == 3                     # worker 2's tail is full
+    assert b"tail" in L.compact_last_error(ctx)
+    tails2, kt2 = _kv([64, 64, 64], [0, 3, 5])
+    assert step([100, 50, 300], tails=tails2) == 1        # prefixes must not decrease
+    assert step([100, 200, 1001], tails=tails2) == 1      # prefix beyond the shared rows
+    assert step(None, tails=tails2) == 1
+    assert step([100, 200, 300], tails=tails2, shared=None) == 1
+    assert step([100, 200, 300], tails=None) == 1
+    assert step([100, 200, 300], tails=tails2, ws=None) == 4
+    assert step([100, 200, 300], tails=tails2, x=None) == 1
+    assert step([100, 200, 300], tails=tails2, n=0) == 1
+    assert kt2["len"][1] == 3                             # untouched on failure
+    n = C.c_size_t()
+    assert L.compact_prefix_workspace_bytes(ctx, 8, 32768, 256, C.byref(n)) == 0 and n.value > 0
+    small = n.value
+    assert L.compact_prefix_workspace_bytes(ctx, 8, 65536, 256, C.byref(n)) == 0 and n.value > small
+    assert L.compact_prefix_workspace_bytes(ctx, 0, 32768, 256, C.byref(n)) == 1
+    # fp32 storage has no prefix-aware path
+    flay = _fake_layer()
+    s32, _k1 = _kv([128], [100])
+    t32, _k2 = _kv([16, 16], [0, 0])
+    pl = (C.c_int32 * 2)(50, 100)
+    assert flay.L.compact_prefix_decode_step(flay.ctx, C.byref(flay.w), 2, x, C.byref(s32), pl, C.byref(t32), x, None, ws,
+                                             1 << 30, None) == 5
