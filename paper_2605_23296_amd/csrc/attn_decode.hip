@@ -8,18 +8,20 @@
 //    tokens of one (block, kv head) and all query heads of that KV head's
 //    group (the cache is read once for the whole group).  Chunks are fixed
 //    size, so the split of a block depends on its own length only.
-//  * per 32-token window a wavefront computes S^T = K Q^T with
+//  * scores: per 32-token window a wavefront computes S^T = K Q^T with
 //    v_mfma_f32_16x16x32_bf16 (K rows as MFMA rows, the group's query heads,
-//    padded to 16, as MFMA columns) and O^T += V^T P^T with the V slab's
-//    transposed layout [hd][token] supplying the MFMA rows.  The MFMA rows of
-//    the two S^T tiles are assigned to tokens so that the accumulator layout
-//    of S^T is exactly the operand layout of P^T: no shuffle, no LDS.
-//  * softmax statistics are per lane-column; the max/sum across the four lane
-//    groups uses wavefront shuffles.  A workgroup is 8 wavefronts, one
-//    32-token window each (many short wavefronts keep the memory system
-//    busier than few long ones); they are merged through LDS in window order,
-//    and chunks are merged by a second small kernel with a log-sum-exp combine
-//    in fixed chunk order.
+//    padded to 16, as MFMA columns).  The MFMA rows of the two S^T tiles are
+//    assigned to tokens so that a lane ends up with 8 consecutive tokens of
+//    one column.  A workgroup is 8 wavefronts, one window each (many short
+//    wavefronts keep the memory system busier than few long ones).
+//  * the windows exchange their column maxima through LDS, so that all of them
+//    exponentiate against the chunk's maximum; the probabilities P^T go to LDS
+//    as bf16 ([column][token], 8 KB).
+//  * output: wavefront w owns rows 16w .. 16w+15 of O^T = V^T P^T over ALL tokens
+//    of the chunk: its V^T operand rows are 512-byte contiguous runs of the
+//    transposed V slab [hd][token], and nothing has to be merged across
+//    wavefronts.  Chunks are merged by a second small kernel with a log-sum-exp
+//    combine in fixed chunk order.
 #include "common.h"
 
 #define LOG2E 1.4426950408889634f
@@ -28,39 +30,45 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 
 #define DEC_WAVES (DECODE_CHUNK / 32)   // one 32-token window per wavefront
 
+#define DEC_PLD (DECODE_CHUNK + 8)   // bf16 per column of the probability tile (padded against bank conflicts)
+
 template <int HD>
-__global__ __launch_bounds__(DEC_WAVES * 64) void attn_decode_bf16_kernel(const BlockMeta* __restrict__ meta,
-                                                                         const TileItem* __restrict__ chunks, int step,
-                                                                         int max_chunks, const bf16* __restrict__ q,
-                                                                         const bf16* __restrict__ kbase,
-                                                                         const bf16* __restrict__ vbase,
-                                                                         float* __restrict__ partials, int Hq, int Hkv,
-                                                                         float scale_log2) {
-    constexpr int KS = HD / 32;  // k-steps of the QK product
-    constexpr int DT = HD / 16;  // 16-row tiles of O^T
-    constexpr int PLD = HD + 2;  // partial record: HD values, max, sum
-    extern __shared__ float so[];  // [DEC_WAVES][G][PLD]
-    __shared__ __attribute__((aligned(16))) bf16 qs[16 * HD];   // [G][HD] query rows of the group
+__global__ __launch_bounds__(DEC_WAVES * 64, 4) void attn_decode_bf16_kernel(const BlockMeta* __restrict__ meta,
+                                                                            const TileItem* __restrict__ chunks, int step,
+                                                                            int max_chunks, const bf16* __restrict__ q,
+                                                                            const bf16* __restrict__ kbase,
+                                                                            const bf16* __restrict__ vbase,
+                                                                            float* __restrict__ partials, int Hq, int Hkv,
+                                                                            float scale_log2) {
+    constexpr int KS = HD / 32;            // k-steps of the QK product
+    constexpr int DT = HD / 16;            // 16-row tiles of O^T, one per wavefront (the first DT wavefronts)
+    constexpr int PLD = HD + 2;            // partial record: HD values, max, sum
+    constexpr int VS = DECODE_CHUNK / 32;  // k-steps of the PV product
+    __shared__ __attribute__((aligned(16))) bf16 qs[16 * HD];        // [G][HD] query rows of the group
+    __shared__ __attribute__((aligned(16))) bf16 ps[16 * DEC_PLD];   // P^T: [column][token of the chunk]
+    __shared__ float s_max[DEC_WAVES][16], s_sum[DEC_WAVES][16];     // per-window maximum and sum of every column
 
     const TileItem it = chunks[blockIdx.x];
     const int b = it.block, kvh = blockIdx.y, c0 = it.row0, ch = c0 / DECODE_CHUNK;
     const BlockMeta bm = meta[b];
     const int n_keys = bm.len + step + 1;
     if (c0 >= n_keys) return;   // a chunk this step does not reach yet
+    const int n_rows = min(n_keys - c0, DECODE_CHUNK);
     const int G = Hq / Hkv;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int r = lane & 15, c = lane >> 4;
-    const int t0 = c0 + wave * 32;
-    const bool live = t0 < n_keys;
+    const int w_lo = wave * 32;
+    const int t0 = c0 + w_lo;
+    const bool live = w_lo < n_rows;
 
     const bf16* kslab = kbase + bm.slab + (size_t)kvh * bm.capacity * HD;
     const bf16* vslab = vbase + bm.slab + (size_t)kvh * HD * bm.capacity;
 
-    // ---- all loads of the window are issued before any arithmetic -------------
-    // S^T tile tt, MFMA row m  <->  token t0 + 8*(m/4) + 4*tt + (m%4)
-    // V^T tile d: lane (row dd = d*16 + r, c) holds tokens t0 + 8c .. +7
+    // ---- all loads are issued before any arithmetic ----------------------------
+    // scores: S^T tile tt, MFMA row m  <->  token t0 + 8*(m/4) + 4*tt + (m%4)
+    // output: lane (r, c) of k-step j holds V^T[16*wave + r][c0 + 32j + 8c .. +7]
     bf16x8 kf[2][KS];
-    bf16x8 vf[DT];
+    bf16x8 vf[VS];
     if (live) {
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {
@@ -69,10 +77,15 @@ __global__ __launch_bounds__(DEC_WAVES * 64) void attn_decode_bf16_kernel(const 
 #pragma unroll
             for (int s = 0; s < KS; ++s) kf[tt][s] = *reinterpret_cast<const bf16x8*>(kp + s * 32);
         }
-        const int voff = min(t0 + 8 * c, bm.capacity - 8);
+    }
+    if (wave < DT) {
+        const bf16* vp = vslab + (size_t)(wave * 16 + r) * bm.capacity;
 #pragma unroll
-        for (int d = 0; d < DT; ++d)
-            vf[d] = *reinterpret_cast<const bf16x8*>(vslab + (size_t)(d * 16 + r) * bm.capacity + voff);
+        for (int j = 0; j < VS; ++j) {
+            // tokens past the cache end are never used: keep the load inside the slab row
+            const int voff = min(c0 + 32 * j + 8 * c, bm.capacity - 8);
+            vf[j] = *reinterpret_cast<const bf16x8*>(vp + voff);
+        }
     }
     // the group's query rows go through LDS: they are needed only once the K rows
     // have arrived, and parking them in registers until then would cost occupancy
@@ -80,19 +93,10 @@ __global__ __launch_bounds__(DEC_WAVES * 64) void attn_decode_bf16_kernel(const 
         *reinterpret_cast<bf16x8*>(qs + i * 8) = *reinterpret_cast<const bf16x8*>(q + ((size_t)b * Hq + kvh * G) * HD + i * 8);
     __syncthreads();
 
-    floatx4 oacc[DT];
-#pragma unroll
-    for (int d = 0; d < DT; ++d) oacc[d] = floatx4{0.f, 0.f, 0.f, 0.f};
-    float m_run = -INFINITY, l_run = 0.f;
+    // ---- S^T = K Q^T over the wavefront's window; the window's column maxima ------
+    float sv[8];
+    float mx = -INFINITY;
     if (live) {
-        if (t0 + 32 > n_keys) {  // ragged tail: rows past the cache end must not reach the MFMA
-#pragma unroll
-            for (int d = 0; d < DT; ++d)
-#pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    if (t0 + 8 * c + j >= n_keys) vf[d][j] = (bf16)0.f;
-        }
-        // ---- S^T = K Q^T ------------------------------------------------------
         // query operand: lane (g = r, c) holds q[g][s*32 + c*8 .. +7], read k-step by k-step
         floatx4 sacc[2] = {floatx4{0.f, 0.f, 0.f, 0.f}, floatx4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
@@ -106,68 +110,66 @@ __global__ __launch_bounds__(DEC_WAVES * 64) void attn_decode_bf16_kernel(const 
             sacc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[1][s], qf, sacc[1], 0, 0, 0);
         }
         // sacc[tt][e]: column g = r, token t0 + 8c + 4tt + e
-        float sv[8];
-        float mx = -INFINITY;
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const int tok = t0 + 8 * c + 4 * tt + e;
-                const float sc = tok < n_keys ? sacc[tt][e] * scale_log2 : -INFINITY;
+                const int row = w_lo + 8 * c + 4 * tt + e;
+                const float sc = row < n_rows ? sacc[tt][e] * scale_log2 : -INFINITY;
                 sv[tt * 4 + e] = sc;
                 mx = fmaxf(mx, sc);
             }
         mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        m_run = mx;  // finite: the window holds at least one valid token
-        bf16x8 pf;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const float p = fast_exp2(sv[j] - m_run);
-            l_run += p;
-            pf[j] = (bf16)p;
-        }
-        // ---- O^T = V^T P^T ----------------------------------------------------
-#pragma unroll
-        for (int d = 0; d < DT; ++d) oacc[d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[d], pf, oacc[d], 0, 0, 0);
-        // sum of p over the four lane groups of the column
-        l_run += __shfl_xor(l_run, 16, 64);
-        l_run += __shfl_xor(l_run, 32, 64);
     }
-
-    // ---- merge the wavefronts in window order ----------------------------------------
-    // oacc[d][e]: column g = r, output element dd = d*16 + 4c + e
-    if (r < G) {
-        float* rec = so + ((size_t)wave * G + r) * PLD;
+    if (c == 0) s_max[wave][r] = mx;
+    if (wave < DT && n_rows < DECODE_CHUNK) {  // ragged tail: bits past the cache end must not reach the MFMA
 #pragma unroll
-        for (int d = 0; d < DT; ++d)
+        for (int j = 0; j < VS; ++j)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) rec[d * 16 + 4 * c + e] = oacc[d][e];
-        if (c == 0) {
-            rec[HD] = m_run;
-            rec[HD + 1] = l_run;
-        }
+            for (int i = 0; i < 8; ++i)
+                if (32 * j + 8 * c + i >= n_rows) vf[j][i] = (bf16)0.f;
     }
     __syncthreads();
-    for (int idx = t; idx < G * HD; idx += DEC_WAVES * 64) {
-        const int g = idx / HD, dd = idx - g * HD;
-        float mm = -INFINITY;
+
+    // ---- one maximum per column for the whole chunk: P = exp2(S - max) ------------
+    float m_all = s_max[0][r];   // finite: the chunk holds at least one valid token
 #pragma unroll
-        for (int w = 0; w < DEC_WAVES; ++w) mm = fmaxf(mm, so[((size_t)w * G + g) * PLD + HD]);
-        float o = 0.f, l = 0.f;
+    for (int w = 1; w < DEC_WAVES; ++w) m_all = fmaxf(m_all, s_max[w][r]);
+    bf16x8 pf;
+    float l_run = 0.f;
 #pragma unroll
-        for (int w = 0; w < DEC_WAVES; ++w) {
-            const float* rec = so + ((size_t)w * G + g) * PLD;
-            const float lw = rec[HD + 1];
-            const float f = lw > 0.f ? fast_exp2(rec[HD] - mm) : 0.f;
-            o += f * rec[dd];
-            l += f * lw;
+    for (int j = 0; j < 8; ++j) {
+        const float p = live ? fast_exp2(sv[j] - m_all) : 0.f;
+        l_run += p;
+        pf[j] = (bf16)p;
+    }
+    l_run += __shfl_xor(l_run, 16, 64);
+    l_run += __shfl_xor(l_run, 32, 64);
+    if (c == 0) s_sum[wave][r] = l_run;
+    *reinterpret_cast<bf16x8*>(ps + r * DEC_PLD + w_lo + 8 * c) = pf;
+    __syncthreads();
+
+    // ---- O^T rows 16*wave .. +15 = V^T P^T over all tokens of the chunk --------------
+    if (wave < DT) {
+        floatx4 oacc = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < VS; ++j) {
+            const bf16x8 pb = *reinterpret_cast<const bf16x8*>(ps + r * DEC_PLD + 32 * j + 8 * c);
+            oacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[j], pb, oacc, 0, 0, 0);
         }
-        float* out = partials + (((size_t)b * Hq + kvh * G + g) * max_chunks + ch) * PLD;
-        out[dd] = o;
-        if (dd == 0) {
-            out[HD] = mm;
-            out[HD + 1] = l;
+        // oacc[e]: column g = r, output element 16*wave + 4c + e
+        if (r < G) {
+            float* out = partials + (((size_t)b * Hq + kvh * G + r) * max_chunks + ch) * PLD;
+            *reinterpret_cast<float2*>(out + wave * 16 + 4 * c) = float2{oacc[0], oacc[1]};
+            *reinterpret_cast<float2*>(out + wave * 16 + 4 * c + 2) = float2{oacc[2], oacc[3]};
+            if (wave == 0 && c == 0) {
+                float l = s_sum[0][r];
+#pragma unroll
+                for (int w = 1; w < DEC_WAVES; ++w) l += s_sum[w][r];
+                out[HD] = m_all;
+                out[HD + 1] = l;
+            }
         }
     }
 }
@@ -230,19 +232,11 @@ int launch_attn_decode_bf16(compact_ctx* ctx, const BlockMeta* d_meta, const Til
     if (n_chunks == 0) return COMPACT_OK;
     dim3 grid(n_chunks, c.n_kv_heads);
     dim3 cgrid(c.n_q_heads, n_blocks);
-    const size_t smem = (size_t)DEC_WAVES * (c.n_q_heads / c.n_kv_heads) * (c.head_dim + 2) * sizeof(float);
     if (max_chunks > COMBINE_MAX_CHUNKS) return set_err(ctx, COMPACT_ECAPACITY, "KV cache longer than the decode combine supports");
-    static bool attr_set = false;
-    if (!attr_set) {   // a group of 16 heads of 128 needs a little over 64 KB of LDS
-        const int big = DEC_WAVES * 16 * (128 + 2) * (int)sizeof(float);
-        HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(attn_decode_bf16_kernel<128>), hipFuncAttributeMaxDynamicSharedMemorySize, big));
-        HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(attn_decode_bf16_kernel<64>), hipFuncAttributeMaxDynamicSharedMemorySize, big));
-        attr_set = true;
-    }
     if (c.head_dim == 128) {
         {
             ProfileScope ps(ctx, COMPACT_K_ATTN_DECODE, s);
-            attn_decode_bf16_kernel<128><<<grid, DEC_WAVES * 64, smem, s>>>(d_meta, d_chunks, step, max_chunks, q, d_k, d_v, partials,
+            attn_decode_bf16_kernel<128><<<grid, DEC_WAVES * 64, 0, s>>>(d_meta, d_chunks, step, max_chunks, q, d_k, d_v, partials,
                                                                            c.n_q_heads, c.n_kv_heads, scale_log2);
         }
         LAUNCH_CHECK(ctx);
@@ -250,7 +244,7 @@ int launch_attn_decode_bf16(compact_ctx* ctx, const BlockMeta* d_meta, const Til
     } else {
         {
             ProfileScope ps(ctx, COMPACT_K_ATTN_DECODE, s);
-            attn_decode_bf16_kernel<64><<<grid, DEC_WAVES * 64, smem, s>>>(d_meta, d_chunks, step, max_chunks, q, d_k, d_v, partials,
+            attn_decode_bf16_kernel<64><<<grid, DEC_WAVES * 64, 0, s>>>(d_meta, d_chunks, step, max_chunks, q, d_k, d_v, partials,
                                                                           c.n_q_heads, c.n_kv_heads, scale_log2);
         }
         LAUNCH_CHECK(ctx);

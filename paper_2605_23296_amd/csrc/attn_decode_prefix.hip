@@ -16,25 +16,30 @@
 
 #define LOG2E 1.4426950408889634f
 #define PFX_WAVES (DECODE_CHUNK / 32)
+#define PFX_QCOLS 32   // query columns staged at a time (two MFMA column groups)
 
 __device__ __forceinline__ float pfx_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+#define PFX_PLD (DECODE_CHUNK + 8)   // bf16 per column of the shared probability tile (padded against bank conflicts)
+
 template <int HD>
-__global__ __launch_bounds__(PFX_WAVES * 64) void attn_decode_prefix_kernel(const BlockMeta* __restrict__ tail_meta,
-                                                                           const BlockMeta shared, const PrefixItem* __restrict__ items,
-                                                                           int step, const bf16* __restrict__ q,
-                                                                           const bf16* __restrict__ kshared,
-                                                                           const bf16* __restrict__ vshared,
-                                                                           const bf16* __restrict__ ktail,
-                                                                           const bf16* __restrict__ vtail,
-                                                                           float* __restrict__ records, int64_t total_recs, int Hq,
-                                                                           int Hkv, float scale_log2) {
-    constexpr int KS = HD / 32;  // k-steps of the QK product
-    constexpr int DT = HD / 16;  // 16-row tiles of O^T
-    constexpr int PLD = HD + 2;  // record: HD values, max, sum
-    extern __shared__ float so[];                                // [PFX_WAVES][16][PLD]
-    __shared__ __attribute__((aligned(16))) bf16 qs[16 * HD];    // the 16 query rows of the current column group
-    __shared__ int s_valid[16];                                  // rows of the item each column may see
+__global__ __launch_bounds__(PFX_WAVES * 64, 4) void attn_decode_prefix_kernel(const BlockMeta* __restrict__ tail_meta,
+                                                                              const BlockMeta shared, const PrefixItem* __restrict__ items,
+                                                                              int step, const bf16* __restrict__ q,
+                                                                              const bf16* __restrict__ kshared,
+                                                                              const bf16* __restrict__ vshared,
+                                                                              const bf16* __restrict__ ktail,
+                                                                              const bf16* __restrict__ vtail,
+                                                                              float* __restrict__ records, int64_t total_recs, int Hq,
+                                                                              int Hkv, float scale_log2) {
+    constexpr int KS = HD / 32;            // k-steps of the QK product
+    constexpr int DT = HD / 16;            // 16-row tiles of O^T, one per wavefront (the first DT wavefronts)
+    constexpr int PLD = HD + 2;            // record: HD values, max, sum
+    constexpr int VS = DECODE_CHUNK / 32;  // k-steps of the PV product
+    __shared__ __attribute__((aligned(16))) bf16 qs[PFX_QCOLS * HD];    // query rows of the staged columns
+    __shared__ __attribute__((aligned(16))) bf16 ps[16 * PFX_PLD];      // P^T of the current column group: [column][item row]
+    __shared__ float s_max[PFX_WAVES][16], s_sum[PFX_WAVES][16];        // per-window maximum and sum of every column
+    __shared__ int s_valid[PFX_QCOLS];                                  // rows of the item each column may see
 
     const PrefixItem it = items[blockIdx.x];
     const int kvh = blockIdx.y;
@@ -57,15 +62,16 @@ __global__ __launch_bounds__(PFX_WAVES * 64) void attn_decode_prefix_kernel(cons
         kslab = kshared + shared.slab + (size_t)kvh * cap * HD;
         vslab = vshared + shared.slab + (size_t)kvh * HD * cap;
     }
-    const int w_lo = wave * 32;                 // first item row of this wavefront's window
+    const int w_lo = wave * 32;                 // first item row of this wavefront's score window
     const bool live = w_lo < n_rows;
     const int t0 = it.row0 + w_lo;              // slab row of the window
     const int last_row = it.row0 + n_rows - 1;
 
-    // ---- the window's K rows and V^T rows: loaded once, used by every column group ----
-    // S^T tile tt, MFMA row m  <->  row t0 + 8*(m/4) + 4*tt + (m%4);  V^T tile d: lane (row d*16 + r, c) holds rows t0 + 8c .. +7
+    // ---- loaded once, used by every column group ------------------------------------
+    // scores: this wavefront's 32-row window of K.  S^T tile tt, MFMA row m <-> row t0 + 8*(m/4) + 4*tt + (m%4)
+    // output: rows wave*16 .. +15 of V^T over all rows of the item; lane (r, c) of k-step j holds item rows 32j + 8c .. +7
     bf16x8 kf[2][KS];
-    bf16x8 vf[DT];
+    bf16x8 vf[VS];
     if (live) {
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {
@@ -74,61 +80,64 @@ __global__ __launch_bounds__(PFX_WAVES * 64) void attn_decode_prefix_kernel(cons
 #pragma unroll
             for (int s = 0; s < KS; ++s) kf[tt][s] = *reinterpret_cast<const bf16x8*>(kp + s * 32);
         }
-        const int voff = min(t0 + 8 * c, cap - 8);
-#pragma unroll
-        for (int d = 0; d < DT; ++d)
-            vf[d] = *reinterpret_cast<const bf16x8*>(vslab + (size_t)(d * 16 + r) * cap + voff);
     }
-    bool v_fixed = false;
+    if (wave < DT) {
+        const bf16* vp = vslab + (size_t)(wave * 16 + r) * cap;
+#pragma unroll
+        for (int j = 0; j < VS; ++j) {
+            const int ro = 32 * j + 8 * c;                       // item row of the lane's first element
+            const int voff = min(it.row0 + ro, cap - 8);        // rows past the item are never used: keep the load in bounds
+            vf[j] = *reinterpret_cast<const bf16x8*>(vp + voff);
+        }
+        // rows past the item's end must not reach the MFMA (their probabilities are zero, their bits are anything)
+        if (n_rows < DECODE_CHUNK) {
+#pragma unroll
+            for (int j = 0; j < VS; ++j)
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if (32 * j + 8 * c + i >= n_rows) vf[j][i] = (bf16)0.f;
+        }
+    }
 
     const int ncols = it.nw * G;
     for (int col0 = 0; col0 < ncols; col0 += 16) {
-        // ---- stage the group's query rows and their row limits -----------------------
-        __syncthreads();   // the previous group's merge has read so[] and qs[]
-        for (int i = t; i < 16 * (HD / 8); i += PFX_WAVES * 64) {
-            const int col = col0 + i / (HD / 8), ch8 = i % (HD / 8);
-            bf16x8 v;
+        // ---- every PFX_QCOLS columns: stage their query rows and row limits ---------
+        __syncthreads();   // the previous group has read ps[], s_max[], s_sum[], qs[] and s_valid[]
+        if (col0 % PFX_QCOLS == 0) {
+            for (int i = t; i < PFX_QCOLS * (HD / 8); i += PFX_WAVES * 64) {
+                const int col = col0 + i / (HD / 8), ch8 = i % (HD / 8);
+                bf16x8 v;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) v[j] = (bf16)0.f;
-            if (col < ncols) {
-                const int w = it.w0 + col / G, head = kvh * G + col % G;
-                v = *reinterpret_cast<const bf16x8*>(q + ((size_t)w * Hq + head) * HD + ch8 * 8);
+                for (int j = 0; j < 8; ++j) v[j] = (bf16)0.f;
+                if (col < ncols) {
+                    const int w = it.w0 + col / G, head = kvh * G + col % G;
+                    v = *reinterpret_cast<const bf16x8*>(q + ((size_t)w * Hq + head) * HD + ch8 * 8);
+                }
+                *reinterpret_cast<bf16x8*>(qs + (size_t)(i / (HD / 8)) * HD + ch8 * 8) = v;
             }
-            *reinterpret_cast<bf16x8*>(qs + (size_t)(i / (HD / 8)) * HD + ch8 * 8) = v;
+            if (t < PFX_QCOLS) {
+                const int col = col0 + t;
+                int lim = 0;
+                if (col < ncols) lim = it.tail ? n_rows : min(n_rows, tail_meta[it.w0 + col / G].pos_offset - it.row0);
+                s_valid[t] = lim;
+            }
+            __syncthreads();
         }
-        if (t < 16) {
-            const int col = col0 + t;
-            int lim = 0;
-            if (col < ncols) lim = it.tail ? n_rows : min(n_rows, tail_meta[it.w0 + col / G].pos_offset - it.row0);
-            s_valid[t] = lim;
-        }
-        __syncthreads();
+        const int qc = col0 % PFX_QCOLS;   // first staged column of this group
 
-        floatx4 oacc[DT];
-#pragma unroll
-        for (int d = 0; d < DT; ++d) oacc[d] = floatx4{0.f, 0.f, 0.f, 0.f};
-        float m_run = -INFINITY, l_run = 0.f;
+        // ---- S^T = K Q^T over the wavefront's window; the window's column maxima ----
+        float sv[8];
+        float mx = -INFINITY;
         if (live) {
-            if (!v_fixed && w_lo + 32 > n_rows) {   // rows past the item's end must not reach the MFMA
-#pragma unroll
-                for (int d = 0; d < DT; ++d)
-#pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        if (w_lo + 8 * c + j >= n_rows) vf[d][j] = (bf16)0.f;
-            }
-            v_fixed = true;
-            const int lim = s_valid[r];   // rows of the item column r may see
-            // ---- S^T = K Q^T ------------------------------------------------------
+            const int lim = s_valid[qc + r];   // rows of the item column r may see
             floatx4 sacc[2] = {floatx4{0.f, 0.f, 0.f, 0.f}, floatx4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
-                const bf16x8 qf = *reinterpret_cast<const bf16x8*>(qs + r * HD + s * 32 + c * 8);
+                const bf16x8 qf = *reinterpret_cast<const bf16x8*>(qs + (qc + r) * HD + s * 32 + c * 8);
                 sacc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][s], qf, sacc[0], 0, 0, 0);
                 sacc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[1][s], qf, sacc[1], 0, 0, 0);
             }
             // sacc[tt][e]: column r, item row w_lo + 8c + 4tt + e
-            float sv[8];
-            float mx = -INFINITY;
 #pragma unroll
             for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
@@ -140,114 +149,137 @@ __global__ __launch_bounds__(PFX_WAVES * 64) void attn_decode_prefix_kernel(cons
                 }
             mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            m_run = mx;                                   // -inf when the column sees none of the window
-            const float m_use = mx == -INFINITY ? 0.f : mx;
-            bf16x8 pf;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const float p = pfx_exp2(sv[j] - m_use);
-                l_run += p;
-                pf[j] = (bf16)p;
-            }
-            // ---- O^T = V^T P^T ----------------------------------------------------
-#pragma unroll
-            for (int d = 0; d < DT; ++d) oacc[d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[d], pf, oacc[d], 0, 0, 0);
-            l_run += __shfl_xor(l_run, 16, 64);
-            l_run += __shfl_xor(l_run, 32, 64);
         }
-
-        // ---- merge the wavefronts in window order ------------------------------------
-        // oacc[d][e]: column r, output element d*16 + 4c + e
-        {
-            float* rec = so + ((size_t)wave * 16 + r) * PLD;
-#pragma unroll
-            for (int d = 0; d < DT; ++d)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) rec[d * 16 + 4 * c + e] = oacc[d][e];
-            if (c == 0) {
-                rec[HD] = m_run;
-                rec[HD + 1] = l_run;
-            }
-        }
+        if (c == 0) s_max[wave][r] = mx;
         __syncthreads();
-        const int gcols = min(16, ncols - col0);
-        for (int idx = t; idx < gcols * HD; idx += PFX_WAVES * 64) {
-            const int g = idx / HD, dd = idx - g * HD;
-            float mm = -INFINITY;
+
+        // ---- one maximum per column for the whole item: P = exp2(S - max) -----------
+        float m_all = s_max[0][r];
 #pragma unroll
-            for (int w = 0; w < PFX_WAVES; ++w) mm = fmaxf(mm, so[((size_t)w * 16 + g) * PLD + HD]);
-            float ov = 0.f, l = 0.f;
+        for (int w = 1; w < PFX_WAVES; ++w) m_all = fmaxf(m_all, s_max[w][r]);
+        const float m_use = m_all == -INFINITY ? 0.f : m_all;   // a column that sees none of the item
+        bf16x8 pf;
+        float l_run = 0.f;
 #pragma unroll
-            for (int w = 0; w < PFX_WAVES; ++w) {
-                const float* rec = so + ((size_t)w * 16 + g) * PLD;
-                const float lw = rec[HD + 1];
-                const float f = lw > 0.f ? pfx_exp2(rec[HD] - mm) : 0.f;
-                ov += f * rec[dd];
-                l += f * lw;
+        for (int j = 0; j < 8; ++j) {
+            const float p = live ? pfx_exp2(sv[j] - m_use) : 0.f;
+            l_run += p;
+            pf[j] = (bf16)p;
+        }
+        l_run += __shfl_xor(l_run, 16, 64);
+        l_run += __shfl_xor(l_run, 32, 64);
+        if (c == 0) s_sum[wave][r] = l_run;
+        *reinterpret_cast<bf16x8*>(ps + r * PFX_PLD + w_lo + 8 * c) = pf;
+        __syncthreads();
+
+        // ---- O^T rows wave*16 .. +15 = V^T P^T over all rows of the item --------------
+        if (wave < DT) {
+            floatx4 oacc = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < VS; ++j) {
+                const bf16x8 pb = *reinterpret_cast<const bf16x8*>(ps + r * PFX_PLD + 32 * j + 8 * c);
+                oacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[j], pb, oacc, 0, 0, 0);
             }
-            float* out = records + ((size_t)kvh * total_recs + it.rec0 + col0 + g) * PLD;
-            out[dd] = ov;
-            if (dd == 0) {
-                out[HD] = mm;
-                out[HD + 1] = l;
+            // oacc[e]: column r, output element wave*16 + 4c + e
+            if (col0 + r < ncols) {
+                float* out = records + ((size_t)kvh * total_recs + it.rec0 + col0 + r) * PLD;
+                *reinterpret_cast<float2*>(out + wave * 16 + 4 * c) = float2{oacc[0], oacc[1]};
+                *reinterpret_cast<float2*>(out + wave * 16 + 4 * c + 2) = float2{oacc[2], oacc[3]};
+                if (wave == 0 && c == 0) {
+                    float l = s_sum[0][r];
+#pragma unroll
+                    for (int w = 1; w < PFX_WAVES; ++w) l += s_sum[w][r];
+                    out[HD] = m_all;
+                    out[HD + 1] = l;
+                }
             }
         }
     }
 }
 
-// Merges the records of one (worker, head): the items on the worker's list, in list
-// order.  Tail chunks the step has not reached yet are skipped (nobody wrote them).
+// Merges the records of one (worker, head): the items on the worker's list.  Tail
+// chunks the step has not reached yet carry weight zero and are never read (nobody
+// wrote them).  256 threads: HD / 2 threads span a record, 512 / HD records are read
+// side by side; all sums run in a fixed order.
 #define PFX_MAX_ITEMS 1024
+#define PFX_CT 256
 template <int HD>
-__global__ __launch_bounds__(HD) void attn_decode_prefix_combine_kernel(const BlockMeta* __restrict__ tail_meta,
-                                                                        const PrefixItem* __restrict__ items,
-                                                                        const int32_t* __restrict__ wl_off,
-                                                                        const int32_t* __restrict__ wl, int step,
-                                                                        const float* __restrict__ records, int64_t total_recs,
-                                                                        bf16* __restrict__ o, int Hq, int Hkv) {
+__global__ __launch_bounds__(PFX_CT) void attn_decode_prefix_combine_kernel(const BlockMeta* __restrict__ tail_meta,
+                                                                            const PrefixItem* __restrict__ items,
+                                                                            const int32_t* __restrict__ wl_off,
+                                                                            const int32_t* __restrict__ wl, int step,
+                                                                            const float* __restrict__ records, int64_t total_recs,
+                                                                            bf16* __restrict__ o, int Hq, int Hkv) {
     constexpr int PLD = HD + 2;
+    constexpr int TPR = HD / 2;          // threads per record (two floats each)
+    constexpr int NS = PFX_CT / TPR;     // records read side by side
     __shared__ float wgt[PFX_MAX_ITEMS];
-    __shared__ int32_t roff[PFX_MAX_ITEMS];   // record index of every live item of this (worker, head)
-    __shared__ float red_m[HD / 64], red_l[HD / 64];
-    __shared__ int s_n;
-    const int b = blockIdx.y, head = blockIdx.x, dd = threadIdx.x;
+    __shared__ int32_t roff[PFX_MAX_ITEMS];
+    __shared__ float red[PFX_CT / 64];
+    __shared__ float2 part[NS][TPR];
+    const int b = blockIdx.y, head = blockIdx.x, t = threadIdx.x;
     const int G = Hq / Hkv, kvh = head / G, g = head % G;
     const int tail_rows = tail_meta[b].len + step + 1;
-    if (dd == 0) {   // the list is short; one thread keeps its order
-        int n = 0;
-        for (int i = wl_off[b]; i < wl_off[b + 1]; ++i) {
-            const PrefixItem it = items[wl[i]];
-            if (it.tail && it.row0 >= tail_rows) continue;
-            roff[n++] = it.rec0 + (b - it.w0) * G + g;
-        }
-        s_n = n;
-    }
-    __syncthreads();
-    const int n = s_n;
+    const int l0 = wl_off[b], n = wl_off[b + 1] - l0;
     const float* base = records + (size_t)kvh * total_recs * PLD;
+    // record index of every item on the list, -1 for a tail chunk not reached yet; running maximum
     float mm = -INFINITY;
-    for (int i = dd; i < n; i += HD) mm = fmaxf(mm, base[(size_t)roff[i] * PLD + HD]);
+    for (int i = t; i < n; i += PFX_CT) {
+        const PrefixItem it = items[wl[l0 + i]];
+        const bool dead = it.tail && it.row0 >= tail_rows;
+        const int ro = dead ? -1 : it.rec0 + (b - it.w0) * G + g;
+        roff[i] = ro;
+        if (!dead) mm = fmaxf(mm, base[(size_t)ro * PLD + HD]);
+    }
 #pragma unroll
     for (int ofs = 32; ofs > 0; ofs >>= 1) mm = fmaxf(mm, __shfl_xor(mm, ofs, 64));
-    if ((dd & 63) == 0) red_m[dd >> 6] = mm;
+    if ((t & 63) == 0) red[t >> 6] = mm;
     __syncthreads();
-    mm = red_m[0];
+    mm = red[0];
 #pragma unroll
-    for (int i = 1; i < HD / 64; ++i) mm = fmaxf(mm, red_m[i]);
-    for (int i = dd; i < n; i += HD) {
-        const float* rec = base + (size_t)roff[i] * PLD;
-        wgt[i] = rec[HD + 1] > 0.f ? pfx_exp2(rec[HD] - mm) : 0.f;
+    for (int i = 1; i < PFX_CT / 64; ++i) mm = fmaxf(mm, red[i]);
+    __syncthreads();   // red[] is reused below
+    float l = 0.f;
+    for (int i = t; i < n; i += PFX_CT) {
+        float wi = 0.f;
+        if (roff[i] >= 0) {
+            const float* rec = base + (size_t)roff[i] * PLD;
+            const float li = rec[HD + 1];
+            wi = li > 0.f ? pfx_exp2(rec[HD] - mm) : 0.f;
+            l += wi * li;
+        }
+        wgt[i] = wi;
     }
-    __syncthreads();
-    if (dd == 0) {
-        float l = 0.f;
-        for (int i = 0; i < n; ++i) l += wgt[i] * base[(size_t)roff[i] * PLD + HD + 1];
-        red_l[0] = l;
+#pragma unroll
+    for (int ofs = 32; ofs > 0; ofs >>= 1) l += __shfl_xor(l, ofs, 64);
+    if ((t & 63) == 0) red[t >> 6] = l;
+    __syncthreads();   // wgt[] complete as well
+    l = red[0];
+#pragma unroll
+    for (int i = 1; i < PFX_CT / 64; ++i) l += red[i];
+    const int sl = t / TPR, e = t % TPR;
+    float2 acc = float2{0.f, 0.f};
+    for (int i = sl; i < n; i += NS) {
+        const float wi = wgt[i];
+        if (wi != 0.f) {
+            const float2 v = *reinterpret_cast<const float2*>(base + (size_t)roff[i] * PLD + 2 * e);
+            acc.x += wi * v.x;
+            acc.y += wi * v.y;
+        }
     }
-    float acc = 0.f;
-    for (int i = 0; i < n; ++i) acc += wgt[i] * base[(size_t)roff[i] * PLD + dd];
+    part[sl][e] = acc;
     __syncthreads();
-    o[((size_t)b * Hq + head) * HD + dd] = (bf16)(acc / red_l[0]);
+    if (sl == 0) {
+#pragma unroll
+        for (int j = 1; j < NS; ++j) {
+            acc.x += part[j][e].x;
+            acc.y += part[j][e].y;
+        }
+        bf16x2 out;
+        out[0] = (bf16)(acc.x / l);
+        out[1] = (bf16)(acc.y / l);
+        *reinterpret_cast<bf16x2*>(o + ((size_t)b * Hq + head) * HD + 2 * e) = out;
+    }
 }
 
 int launch_attn_decode_prefix_bf16(compact_ctx* ctx, const BlockMeta* d_tail_meta, const BlockMeta& shared,
@@ -261,33 +293,25 @@ int launch_attn_decode_prefix_bf16(compact_ctx* ctx, const BlockMeta* d_tail_met
     const float scale_log2 = LOG2E / sqrtf((float)c.head_dim);
     dim3 grid(n_items, c.n_kv_heads);
     dim3 cgrid(c.n_q_heads, n_workers);
-    const size_t smem = (size_t)PFX_WAVES * 16 * (c.head_dim + 2) * sizeof(float);
-    static bool attr_set = false;
-    if (!attr_set) {
-        const int big = PFX_WAVES * 16 * (128 + 2) * (int)sizeof(float);
-        HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(attn_decode_prefix_kernel<128>), hipFuncAttributeMaxDynamicSharedMemorySize, big));
-        HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(attn_decode_prefix_kernel<64>), hipFuncAttributeMaxDynamicSharedMemorySize, big));
-        attr_set = true;
-    }
     if (c.head_dim == 128) {
         {
             ProfileScope ps(ctx, COMPACT_K_ATTN_DECODE, s);
-            attn_decode_prefix_kernel<128><<<grid, PFX_WAVES * 64, smem, s>>>(d_tail_meta, shared, d_items, step, q, kshared, vshared,
+            attn_decode_prefix_kernel<128><<<grid, PFX_WAVES * 64, 0, s>>>(d_tail_meta, shared, d_items, step, q, kshared, vshared,
                                                                              ktail, vtail, records, total_recs, c.n_q_heads,
                                                                              c.n_kv_heads, scale_log2);
         }
         LAUNCH_CHECK(ctx);
-        attn_decode_prefix_combine_kernel<128><<<cgrid, 128, 0, s>>>(d_tail_meta, d_items, d_wl_off, d_wl, step, records,
+        attn_decode_prefix_combine_kernel<128><<<cgrid, PFX_CT, 0, s>>>(d_tail_meta, d_items, d_wl_off, d_wl, step, records,
                                                                      total_recs, o, c.n_q_heads, c.n_kv_heads);
     } else {
         {
             ProfileScope ps(ctx, COMPACT_K_ATTN_DECODE, s);
-            attn_decode_prefix_kernel<64><<<grid, PFX_WAVES * 64, smem, s>>>(d_tail_meta, shared, d_items, step, q, kshared, vshared,
+            attn_decode_prefix_kernel<64><<<grid, PFX_WAVES * 64, 0, s>>>(d_tail_meta, shared, d_items, step, q, kshared, vshared,
                                                                             ktail, vtail, records, total_recs, c.n_q_heads,
                                                                             c.n_kv_heads, scale_log2);
         }
         LAUNCH_CHECK(ctx);
-        attn_decode_prefix_combine_kernel<64><<<cgrid, 64, 0, s>>>(d_tail_meta, d_items, d_wl_off, d_wl, step, records, total_recs, o,
+        attn_decode_prefix_combine_kernel<64><<<cgrid, PFX_CT, 0, s>>>(d_tail_meta, d_items, d_wl_off, d_wl, step, records, total_recs, o,
                                                                    c.n_q_heads, c.n_kv_heads);
     }
     LAUNCH_CHECK(ctx);
