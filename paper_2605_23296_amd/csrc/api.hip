@@ -527,21 +527,34 @@ struct PrefixArgs {
 };
 
 // one decode step for all blocks; plan.meta.len = cached tokens before step 0.
-// n_pre (nullable) = RMSNorm(x; g_attn) already computed for this step's rows.
 static int decode_impl(compact_ctx* ctx, const compact_weights* w, int n_blocks, int step, const void* x,
-                       const void* n_pre, compact_kv* kv, void* y, const compact_route_out* route, const DecodeBufs& b,
+                       compact_kv* kv, void* y, const compact_route_out* route, const DecodeBufs& b,
                        const Plan& plan, hipStream_t s, const PrefixArgs* pfx = nullptr) {
     const compact_layer_cfg& c = ctx->cfg;
     const int N = n_blocks;
     const int Dq = c.n_q_heads * c.head_dim, Dtot = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
     int ks = 1;
-    const void* n = n_pre;
-    if (!n) {
+    // RMSNorm + QKV projection.  bf16 storage and whole 512-wide K slices: the
+    // projection stages bf16(x * g) itself and leaves the row sums of squares, the
+    // epilogue multiplies by 1 / rms before the rotation.
+    if (c.dtype == COMPACT_BF16 && skinny_norm_in_supported(N, Dtot, c.d_model)) {
+        ks = skinny_ksplit(N, Dtot, c.d_model);
+        {
+            ProfileScope ps(ctx, COMPACT_K_GEMM_SKINNY, s);
+            TRY(launch_gemm_skinny(ctx, (const bf16*)x, (const bf16*)w->w_qkv, b.partials, N, Dtot, c.d_model, ks, s,
+                                   (const bf16*)w->g_attn, b.ssq_parts));
+        }
+        RowNorm rq;
+        rq.ssq_parts = b.ssq_parts;
+        rq.nparts = ks;
+        rq.inv_d = 1.0f / (float)c.d_model;
+        rq.eps = c.rms_eps;
+        TRY(launch_decode_qkv_epilogue(ctx, plan.d_meta, N, step, b.partials, ks, b.q, kv->d_k, kv->d_v, s, &rq));
+    } else {
         TRY(launch_rmsnorm(ctx, x, false, w->g_attn, b.n, N, s));
-        n = b.n;
+        TRY(gemm_partials(ctx, b.n, w->w_qkv, b.partials, N, Dtot, c.d_model, &ks, s));
+        TRY(launch_decode_qkv_epilogue(ctx, plan.d_meta, N, step, b.partials, ks, b.q, kv->d_k, kv->d_v, s));
     }
-    TRY(gemm_partials(ctx, n, w->w_qkv, b.partials, N, Dtot, c.d_model, &ks, s));
-    TRY(launch_decode_qkv_epilogue(ctx, plan.d_meta, N, step, b.partials, ks, b.q, kv->d_k, kv->d_v, s));
     if (pfx) {
         TRY(launch_attn_decode_prefix_bf16(ctx, plan.d_meta, pfx->shared, (const PrefixItem*)(plan.d_extra + pfx->off_items),
                                            (int)pfx->items.size(), (const int32_t*)(plan.d_extra + pfx->off_wl_off),
@@ -656,7 +669,7 @@ extern "C" int compact_decode_step(compact_ctx* ctx, const compact_weights* w, i
     carve_decode(cv, ctx->cfg, n_blocks, chunks_for(plan.max_len + 1), b);
     if (cv.off > ws_bytes) return set_err(ctx, COMPACT_EWORKSPACE, "workspace too small for this decode step");
     TRY(upload_plan(ctx, plan, s));
-    TRY(decode_impl(ctx, w, n_blocks, 0, d_x, nullptr, kv, d_y, route, b, plan, s));
+    TRY(decode_impl(ctx, w, n_blocks, 0, d_x, kv, d_y, route, b, plan, s));
     for (int b2 = 0; b2 < n_blocks; ++b2) kv->h_len[b2] += 1;
     return COMPACT_OK;
 }
@@ -693,17 +706,11 @@ extern "C" int compact_layer_forward(compact_ctx* ctx, const compact_weights* w,
 
     TRY(prefill_impl(ctx, w, n_blocks, h_cu_seqlens, d_x_prefill, kv, y_pre, d_y_last, nullptr, d_workspace, off, plan, s));
     const size_t row_bytes = (size_t)n_blocks * c.d_model * dtype_size(c.dtype);
-    // the step inputs are all known up front: their first RMSNorm is one launch over
-    // all S*N rows, into the prefill scratch that is dead by now (when it is large enough)
-    const char* n_all = nullptr;
-    if (n_steps > 0 && (int64_t)n_steps * n_blocks <= T) {
-        TRY(launch_rmsnorm(ctx, d_x_decode, false, w->g_attn, pb.n, (int64_t)n_steps * n_blocks, s));
-        n_all = (const char*)pb.n;
-    }
+    // every step is self-contained (as in autoregressive use, where a step's input exists
+    // only once the previous step has finished): nothing is hoisted across steps
     for (int st = 0; st < n_steps; ++st) {
-        TRY(decode_impl(ctx, w, n_blocks, st, (const char*)d_x_decode + st * row_bytes,
-                        n_all ? n_all + st * row_bytes : nullptr, kv, (char*)d_y_decode + st * row_bytes, nullptr, db,
-                        plan, s));
+        TRY(decode_impl(ctx, w, n_blocks, st, (const char*)d_x_decode + st * row_bytes, kv,
+                        (char*)d_y_decode + st * row_bytes, nullptr, db, plan, s));
     }
     for (int b = 0; b < n_blocks; ++b) kv->h_len[b] = h_cu_seqlens[b + 1] - h_cu_seqlens[b] + n_steps;
     return COMPACT_OK;
@@ -825,7 +832,7 @@ extern "C" int compact_prefix_decode_step(compact_ctx* ctx, const compact_weight
     pa.records = (float*)cv.take((size_t)pa.total_recs * ctx->cfg.n_kv_heads * (ctx->cfg.head_dim + 2) * 4);
     if (cv.off > ws_bytes) return set_err(ctx, COMPACT_EWORKSPACE, "workspace too small for this prefix-aware decode step");
     TRY(upload_plan(ctx, plan, s));
-    TRY(decode_impl(ctx, w, n_workers, 0, d_x, nullptr, tails, d_y, route, b, plan, s, &pa));
+    TRY(decode_impl(ctx, w, n_workers, 0, d_x, tails, d_y, route, b, plan, s, &pa));
     for (int b2 = 0; b2 < n_workers; ++b2) tails->h_len[b2] += 1;
     return COMPACT_OK;
 }

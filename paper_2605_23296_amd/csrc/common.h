@@ -126,9 +126,11 @@ int launch_rmsnorm(compact_ctx* ctx, const void* x, bool x_is_f32, const void* g
 int launch_rope_kvwrite(compact_ctx* ctx, const BlockMeta* d_meta, const TileItem* d_tiles, int n_tiles,
                         void* qkv, void* d_k, void* d_v, hipStream_t s);
 // decode: reduce ks split partials of the QKV projection, rotate, append K/V, emit q
+// norm (nullable): the partials were formed from un-normalised rows; every row is
+// multiplied by its 1 / rms first
 int launch_decode_qkv_epilogue(compact_ctx* ctx, const BlockMeta* d_meta, int n_blocks, int step,
                                const float* partials, int ks, void* q_out, void* d_k, void* d_v,
-                               hipStream_t s);
+                               hipStream_t s, const RowNorm* norm = nullptr);
 // decode: h = resid + sum partials; writes h and m = RMSNorm(h; g)
 int launch_residual_norm(compact_ctx* ctx, const float* partials, int ks, const void* resid,
                          const void* g, void* h_out, void* m_out, int rows, hipStream_t s);
@@ -165,8 +167,11 @@ int gemm_bf16_mtile();
 
 // gemm_skinny.hip : partials[ks][M][N] (fp32) = A[M,K] B[N,K]^T split over K
 int skinny_ksplit(int M, int N, int K);
+// norm_g (nullable): A holds un-normalised rows x; the operand becomes bf16(x * norm_g) and
+// norm_ssq_parts[ks][M] receives the per-slice sums of x^2 (the consumer applies 1 / rms)
 int launch_gemm_skinny(compact_ctx* ctx, const bf16* A, const bf16* B, float* partials, int M, int N, int K,
-                       int ks, hipStream_t s);
+                       int ks, hipStream_t s, const bf16* norm_g = nullptr, float* norm_ssq_parts = nullptr);
+bool skinny_norm_in_supported(int M, int N, int K);
 // the same per expert, for routed decode rows: expert e multiplies the rows offsets[e] ..
 // offsets[e+1]-1 of the expert-sorted order (at most 16; X is read through a_gather when
 // given); partials[ks][total_rows][N] keep the sorted order

@@ -35,9 +35,19 @@ struct SkinnyGroup {
     int total_rows;
 };
 
+// Front half of an RMSNorm folded into the activation staging (null g: off): the
+// staged operand is bf16(x * g) and the workgroups of the first column tile leave
+// ssq_parts[slice][row] = sum of x^2 over the slice; the consumer of the partials
+// multiplies by 1 / rms.  Needs whole 512-wide slices (one wavefront stages one row).
+struct SkinnyNormIn {
+    const bf16* g = nullptr;
+    float* ssq_parts = nullptr;
+};
+
 template <int MT, bool GROUPED, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const bf16* __restrict__ X, const bf16* __restrict__ W,
-                                                          float* __restrict__ P, int M, int N, int K, const SkinnyGroup grp) {
+                                                          float* __restrict__ P, int M, int N, int K, const SkinnyGroup grp,
+                                                          const SkinnyNormIn nin) {
     constexpr int LDX = SKINNY_KSLICE + 8;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16* xs = reinterpret_cast<bf16*>(smem);  // [MT*16][LDX]
@@ -82,6 +92,19 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const bf16* __r
             size_t src = row_base + row;
             if (GROUPED && grp.a_gather) src = grp.a_gather[src];
             v = *reinterpret_cast<const bf16x8*>(X + src * K + k0 + cc * 8);
+        }
+        if (!GROUPED && nin.g) {   // cpr == 64: this wavefront holds the whole slice of one row
+            const bf16x8 gv = *reinterpret_cast<const bf16x8*>(nin.g + k0 + cc * 8);
+            float ss = 0.f;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float f = (float)v[j];
+                ss += f * f;
+                v[j] = (bf16)(f * (float)gv[j]);
+            }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+            if (lane == 0 && blockIdx.y == 0 && row < M) nin.ssq_parts[(size_t)slice * M + row] = ss;
         }
         *reinterpret_cast<bf16x8*>(xs + row * LDX + cc * 8) = v;
     }
@@ -252,7 +275,7 @@ int launch_gemm_skinny_swiglu(compact_ctx* ctx, const bf16* X, const bf16* W, bf
 
 template <int MT, int WAVES>
 static int launch_skinny_cfg(compact_ctx* ctx, const bf16* A, const bf16* B, float* partials, int M, int N, int K, int ks,
-                             hipStream_t s) {
+                             const SkinnyNormIn& nin, hipStream_t s) {
     const size_t smem = (size_t)MT * 16 * (SKINNY_KSLICE + 8) * sizeof(bf16);
     static bool attr = false;
     if (!attr && smem > 48 * 1024) {
@@ -261,7 +284,7 @@ static int launch_skinny_cfg(compact_ctx* ctx, const bf16* A, const bf16* B, flo
         attr = true;
     }
     dim3 grid(ks, (N + 16 * WAVES - 1) / (16 * WAVES));
-    gemm_skinny_kernel<MT, false, WAVES><<<grid, WAVES * 64, smem, s>>>(A, B, partials, M, N, K, SkinnyGroup{});
+    gemm_skinny_kernel<MT, false, WAVES><<<grid, WAVES * 64, smem, s>>>(A, B, partials, M, N, K, SkinnyGroup{}, nin);
     LAUNCH_CHECK(ctx);
     return COMPACT_OK;
 }
@@ -270,16 +293,25 @@ static int launch_skinny_cfg(compact_ctx* ctx, const bf16* A, const bf16* B, flo
 // more rows the staged activation slice grows, so 8 wavefronts (128 weight rows)
 // share it: half the activation traffic per weight byte, the same number of
 // wavefronts per compute unit.
+bool skinny_norm_in_supported(int M, int N, int K) { return M >= 1 && M <= 64 && N % 16 == 0 && K % SKINNY_KSLICE == 0; }
+
 int launch_gemm_skinny(compact_ctx* ctx, const bf16* A, const bf16* B, float* partials, int M, int N, int K, int ks,
-                       hipStream_t s) {
+                       hipStream_t s, const bf16* norm_g, float* norm_ssq_parts) {
     if (M < 1 || M > 64) return set_err(ctx, COMPACT_ESHAPE, "weight-streaming GEMM takes 1..64 activation rows");
     if (N % 16 != 0 || K % 64 != 0) return set_err(ctx, COMPACT_ESHAPE, "weight-streaming GEMM needs N % 16 == 0 and K % 64 == 0");
     if (ks != skinny_ksplit(M, N, K)) return set_err(ctx, COMPACT_EINVAL, "unexpected K split");
+    SkinnyNormIn nin;
+    if (norm_g) {
+        if (!skinny_norm_in_supported(M, N, K) || !norm_ssq_parts)
+            return set_err(ctx, COMPACT_ESHAPE, "folding the RMSNorm into the weight-streaming GEMM needs K % 512 == 0");
+        nin.g = norm_g;
+        nin.ssq_parts = norm_ssq_parts;
+    }
     switch ((M + 15) / 16) {
-        case 1: return launch_skinny_cfg<1, 4>(ctx, A, B, partials, M, N, K, ks, s);
-        case 2: return launch_skinny_cfg<2, 8>(ctx, A, B, partials, M, N, K, ks, s);
-        case 3: return launch_skinny_cfg<3, 8>(ctx, A, B, partials, M, N, K, ks, s);
-        default: return launch_skinny_cfg<4, 8>(ctx, A, B, partials, M, N, K, ks, s);
+        case 1: return launch_skinny_cfg<1, 4>(ctx, A, B, partials, M, N, K, ks, nin, s);
+        case 2: return launch_skinny_cfg<2, 8>(ctx, A, B, partials, M, N, K, ks, nin, s);
+        case 3: return launch_skinny_cfg<3, 8>(ctx, A, B, partials, M, N, K, ks, nin, s);
+        default: return launch_skinny_cfg<4, 8>(ctx, A, B, partials, M, N, K, ks, nin, s);
     }
 }
 
@@ -293,7 +325,7 @@ int launch_gemm_skinny_grouped(compact_ctx* ctx, const bf16* X, const int32_t* a
     SkinnyGroup g{offsets, a_gather, w_expert_stride, total_rows};
     dim3 grid(ks, (N + 63) / 64, n_experts);
     const size_t smem = (size_t)16 * (SKINNY_KSLICE + 8) * sizeof(bf16);
-    gemm_skinny_kernel<1, true, 4><<<grid, 256, smem, s>>>(X, W, partials, 0, N, K, g);
+    gemm_skinny_kernel<1, true, 4><<<grid, 256, smem, s>>>(X, W, partials, 0, N, K, g, SkinnyNormIn{});
     LAUNCH_CHECK(ctx);
     return COMPACT_OK;
 }

@@ -180,7 +180,7 @@ __global__ __launch_bounds__(64) void decode_qkv_epilogue_kernel(const BlockMeta
                                                                 const float* __restrict__ partials, int ks,
                                                                 T* __restrict__ q_out, T* __restrict__ kbase,
                                                                 T* __restrict__ vbase, int Hq, int Hkv, int hd,
-                                                                double log2_theta) {
+                                                                double log2_theta, const RowNorm norm) {
     const int head = blockIdx.x, b = blockIdx.y;
     const int i = threadIdx.x;
     const int half = hd / 2;
@@ -209,6 +209,13 @@ __global__ __launch_bounds__(64) void decode_qkv_epilogue_kernel(const BlockMeta
         lo += row[s * ps + i];
         hi += row[s * ps + half + i];
     }
+    if (norm.ssq_parts) {
+        float ss = 0.f;
+        for (int pi = 0; pi < norm.nparts; ++pi) ss += norm.ssq_parts[(size_t)pi * n_rows + b];
+        const float rinv = 1.0f / sqrtf(ss * norm.inv_d + norm.eps);
+        lo *= rinv;
+        hi *= rinv;
+    }
     if (head < Hq + Hkv) {
         const double inv_freq = exp2(-2.0 * (double)i / (double)hd * log2_theta);
         double sn, cn;
@@ -228,18 +235,19 @@ __global__ __launch_bounds__(64) void decode_qkv_epilogue_kernel(const BlockMeta
 }
 
 int launch_decode_qkv_epilogue(compact_ctx* ctx, const BlockMeta* d_meta, int n_blocks, int step, const float* partials,
-                               int ks, void* q_out, void* d_k, void* d_v, hipStream_t s) {
+                               int ks, void* q_out, void* d_k, void* d_v, hipStream_t s, const RowNorm* norm) {
     const compact_layer_cfg& c = ctx->cfg;
+    const RowNorm rn = norm ? *norm : RowNorm{};
     const double l2t = log2((double)c.rope_theta);
     dim3 grid(c.n_q_heads + 2 * c.n_kv_heads, n_blocks);
     if (c.dtype == COMPACT_BF16)
         decode_qkv_epilogue_kernel<bf16, 8><<<grid, 64, 0, s>>>(d_meta, n_blocks, step, partials, ks, (bf16*)q_out,
                                                                (bf16*)d_k, (bf16*)d_v, c.n_q_heads, c.n_kv_heads,
-                                                               c.head_dim, l2t);
+                                                               c.head_dim, l2t, rn);
     else
         decode_qkv_epilogue_kernel<float, 1><<<grid, 64, 0, s>>>(d_meta, n_blocks, step, partials, ks, (float*)q_out,
                                                                 (float*)d_k, (float*)d_v, c.n_q_heads, c.n_kv_heads,
-                                                                c.head_dim, l2t);
+                                                                c.head_dim, l2t, rn);
     LAUNCH_CHECK(ctx);
     return COMPACT_OK;
 }
