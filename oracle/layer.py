@@ -31,7 +31,10 @@ identical-experts == dense equivalence; and a whole-layer cross-check against
 library fp64 routines (torch CPU rms_norm / scaled_dot_product_attention /
 silu).  Conventions that no mathematics fixes -- the rotate-half pairing of
 rotary dimensions and the contiguous grouping of query heads onto KV heads --
-are pinned only to the library routines' conventions.
+are pinned only to the library routines' conventions.  The prefix-aware
+layout is pinned by lone runs on truncated histories; the depth of layers
+(Stack) by library layers applied in turn, an inserted identity layer, and
+decode == longer prefill through the whole depth.
 """
 import math
 
@@ -362,3 +365,40 @@ class Layer:
             y_dec[s] = y
             routes[s] = (idx, gate, logits)
         return pre, y_dec, Ks, Vs, routes
+
+
+class Stack:
+    """A depth of L layers run over the batch of blocks (the full model the
+    paper's workers run, Sec. IV-A, minus embedding and output head): the
+    output rows of layer l are the input rows of layer l + 1, in prefill (all
+    rows of every block) and in each decode step (one row per block); every
+    layer keeps its own K/V cache per block.  Nothing else connects the layers.
+    """
+
+    def __init__(self, cfg, weights):
+        """weights: one weight dict per layer."""
+        self.layers = [Layer(cfg, w) for w in weights]
+
+    def forward(self, x_prefill, cu_seqlens, x_decode, pos_offset=None):
+        """Returns (y_prefill [T, d] of the last layer, y_decode [S, N, d] of the
+        last layer, per-layer K lists, per-layer V lists)."""
+        x = _f64(x_prefill)
+        N = len(cu_seqlens) - 1
+        Ks, Vs = [], []
+        for lay in self.layers:
+            pre = lay.prefill(x, cu_seqlens, pos_offset)
+            Ks.append([p["K"] for p in pre])
+            Vs.append([p["V"] for p in pre])
+            x = np.concatenate([p["y"] for p in pre], axis=0)
+        y_pre = x
+        S = 0 if x_decode is None else x_decode.shape[0]
+        y_dec = np.zeros((S, N, self.layers[0].d), dtype=F64)
+        for s in range(S):
+            xs = _f64(x_decode[s])
+            for li, lay in enumerate(self.layers):
+                st = lay.decode_step(xs, Ks[li], Vs[li], pos_offset)
+                for b in range(N):
+                    Ks[li][b], Vs[li][b] = st[b]["K"], st[b]["V"]
+                xs = np.stack([st[b]["y"] for b in range(N)])
+            y_dec[s] = xs
+        return y_pre, y_dec, Ks, Vs

@@ -472,3 +472,112 @@ def test_prefix_aware_identical_keys_give_the_mean_over_prefix_and_tail(rng):
         h = xd[1, b] + o @ lay.w["w_o"].T
         y, _, _, _ = lay.ffn(h[None])
         np.testing.assert_allclose(yd[1, b], y[0], rtol=1e-10, atol=1e-12)
+
+
+# ---------------------------------------------------------------------------
+# a depth of layers (the full stack the workers run, paper Sec. IV-A models)
+# ---------------------------------------------------------------------------
+def _torch_layer(tx, tw, theta, Hq, Hkv, hd, F, d):
+    """One dense layer over ONE block from torch fp64 library routines (independent of the oracle's code)."""
+    TF = torch.nn.functional
+    L = tx.shape[0]
+    n = TF.rms_norm(tx, (d,), tw["g_attn"], 1e-5)
+    q, k, v = TF.linear(n, tw["w_qkv"]).split([Hq * hd, Hkv * hd, Hkv * hd], dim=-1)
+
+    def rot(t, H):
+        t = t.reshape(L, H, hd)
+        z = torch.complex(t[..., :hd // 2], t[..., hd // 2:])
+        ang = torch.arange(L, dtype=torch.float64)[:, None] * theta ** (-torch.arange(hd // 2, dtype=torch.float64) / (hd // 2))
+        z = z * torch.polar(torch.ones_like(ang), ang)[:, None, :]
+        return torch.cat([z.real, z.imag], -1)
+
+    q, k, v = rot(q, Hq), rot(k, Hkv), v.reshape(L, Hkv, hd)
+    o = TF.scaled_dot_product_attention(q.permute(1, 0, 2)[None], k.permute(1, 0, 2)[None], v.permute(1, 0, 2)[None],
+                                        is_causal=True, enable_gqa=True)[0].permute(1, 0, 2).reshape(L, Hq * hd)
+    h = tx + TF.linear(o, tw["w_o"])
+    gu = TF.linear(TF.rms_norm(h, (d,), tw["g_ffn"], 1e-5), tw["w_gate_up"])
+    return h + TF.linear(TF.silu(gu[:, :F]) * gu[:, F:], tw["w_down"]), k, v
+
+
+def test_stack_prefill_equals_library_layers_applied_in_turn(rng):
+    """Three different layers: the stack's last-layer output and the K rows cached by
+    the LAST layer equal torch fp64 layers applied one after the other to each block
+    (a wrong hand-over between layers, or one layer's cache filed under another, fails)."""
+    cfg = small_cfg()
+    ws = [small_weights(cfg, rng) for _ in range(3)]
+    lens = [7, 4]
+    cu = [0, 7, 11]
+    x = rng.standard_normal((11, 32))
+    y_pre, _, Ks, Vs = O.Stack(cfg, ws).forward(x, cu, None)
+    for b in range(2):
+        t = torch.from_numpy(x[cu[b]:cu[b + 1]])
+        for li, w in enumerate(ws):
+            tw = {k: torch.from_numpy(np.asarray(v)) for k, v in w.items()}
+            t, k, v = _torch_layer(t, tw, cfg["rope_theta"], 4, 2, 8, 48, 32)
+            np.testing.assert_allclose(Ks[li][b], k.numpy(), atol=1e-10)
+            np.testing.assert_allclose(Vs[li][b], v.numpy(), atol=1e-10)
+        np.testing.assert_allclose(y_pre[cu[b]:cu[b + 1]], t.numpy(), atol=1e-10)
+
+
+def test_stack_of_one_layer_is_the_layer(rng):
+    cfg = small_cfg()
+    w = small_weights(cfg, rng)
+    cu = [0, 5, 8]
+    x = rng.standard_normal((8, 32))
+    xd = rng.standard_normal((3, 2, 32))
+    pre, yd, Ks, Vs, _ = O.Layer(cfg, w).forward(x, cu, xd)
+    y_pre, yd2, Ks2, Vs2 = O.Stack(cfg, [w]).forward(x, cu, xd)
+    np.testing.assert_array_equal(np.concatenate([p["y"] for p in pre]), y_pre)
+    np.testing.assert_array_equal(yd, yd2)
+    np.testing.assert_array_equal(Ks[1], Ks2[0][1])
+
+
+def test_stack_skips_an_identity_layer(rng):
+    """A layer whose output and down projections are zero adds nothing to the residual
+    stream: inserting it anywhere leaves every other layer's outputs and caches alone,
+    in prefill and in decode."""
+    cfg = small_cfg()
+    wa, wb = small_weights(cfg, rng), small_weights(cfg, rng)
+    wi = small_weights(cfg, rng)
+    wi["w_o"] = np.zeros_like(wi["w_o"])
+    wi["w_down"] = np.zeros_like(wi["w_down"])
+    cu = [0, 6, 9]
+    x = rng.standard_normal((9, 32))
+    xd = rng.standard_normal((2, 2, 32))
+    y2, yd2, K2, V2 = O.Stack(cfg, [wa, wb]).forward(x, cu, xd)
+    y3, yd3, K3, V3 = O.Stack(cfg, [wa, wi, wb]).forward(x, cu, xd)
+    np.testing.assert_allclose(y3, y2, atol=1e-12)
+    np.testing.assert_allclose(yd3, yd2, atol=1e-12)
+    for b in range(2):
+        np.testing.assert_allclose(K3[2][b], K2[1][b], atol=1e-12)
+        np.testing.assert_allclose(V3[0][b], V2[0][b], atol=1e-12)
+        assert K3[1][b].shape[0] == K2[1][b].shape[0]   # the identity layer caches every row too
+
+
+def test_stack_decode_equals_a_longer_prefill(rng):
+    """Feeding a block's next token as a decode step through the whole depth gives the
+    last row of a prefill over the block with that token appended (every layer's cache
+    must take the row its own predecessor produced)."""
+    cfg = small_cfg()
+    ws = [small_weights(cfg, rng) for _ in range(3)]
+    x = rng.standard_normal((8, 32))
+    st = O.Stack(cfg, ws)
+    y_full, _, K_full, _ = st.forward(x, [0, 8], None)
+    _, yd, K_inc, _ = st.forward(x[:6], [0, 6], x[6:8].reshape(2, 1, 32))
+    np.testing.assert_allclose(yd[:, 0], y_full[6:8], atol=1e-11)
+    for li in range(3):
+        np.testing.assert_allclose(K_inc[li][0], K_full[li][0], atol=1e-11)
+
+
+def test_stack_batched_equals_one_block_at_a_time(rng):
+    cfg = small_cfg()
+    ws = [small_weights(cfg, rng) for _ in range(2)]
+    cu = [0, 4, 9, 12]
+    x = rng.standard_normal((12, 32))
+    xd = rng.standard_normal((2, 3, 32))
+    st = O.Stack(cfg, ws)
+    y, yd, _, _ = st.forward(x, cu, xd)
+    for b in range(3):
+        y1, yd1, _, _ = st.forward(x[cu[b]:cu[b + 1]], [0, cu[b + 1] - cu[b]], xd[:, b:b + 1])
+        np.testing.assert_array_equal(y[cu[b]:cu[b + 1]], y1)
+        np.testing.assert_array_equal(yd[:, b], yd1[:, 0])
