@@ -190,6 +190,27 @@ int compact_prefix_decode_step(compact_ctx* ctx, const compact_weights* w, int32
                                compact_kv* tails, void* d_y, const compact_route_out* route,
                                void* d_workspace, size_t ws_bytes, void* hip_stream);
 
+/* A depth of layers (the models of paper Sec. IV-A are 32- to 80-layer stacks
+ * of the layer above; embedding and output head excluded): layer l's output
+ * rows are layer l+1's input rows, in the prefill of all blocks and in each of
+ * the n_steps batched decode steps; d_x_decode [S, N, d] are the step inputs of
+ * layer 0.  w [n_layers] and kv [n_layers] are host arrays of per-layer
+ * weights and per-layer caches; all caches must share one geometry
+ * (h_slab_offset, h_capacity, h_pos_offset equal across layers; d_k / d_v
+ * differ).  d_y_last [N, d] (nullable) receives the last layer's last prefill
+ * row of each block, d_y_decode [S, N, d] the last layer's step outputs.
+ * With n_blocks = 1 and one block spanning the whole history this is the
+ * sequential baseline the paper compares against (Sec. V, Tables VII-IX).
+ * Every kv[l].h_len ends at L_b + n_steps.  Errors as compact_layer_forward;
+ * COMPACT_EINVAL for n_layers < 1 or caches of differing geometry.  The
+ * workspace must hold compact_stack_workspace_bytes(...).                     */
+int compact_stack_workspace_bytes(const compact_ctx* ctx, int64_t max_tokens, int32_t max_blocks,
+                                  int32_t max_kv_len, size_t* bytes);
+int compact_stack_forward(compact_ctx* ctx, int32_t n_layers, const compact_weights* w, int32_t n_blocks,
+                          const int32_t* h_cu_seqlens, const void* d_x_prefill, int32_t n_steps,
+                          const void* d_x_decode, compact_kv* kv, void* d_y_last, void* d_y_decode,
+                          void* d_workspace, size_t ws_bytes, void* hip_stream);
+
 /* ---- per-kernel timing ----------------------------------------------------
  * When enabled, every launch of the selected kernel class is bracketed by HIP
  * events on the launch stream.  compact_profile_read synchronises those

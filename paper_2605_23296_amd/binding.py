@@ -25,6 +25,7 @@ EXPORTS = [
     "compact_rmsnorm", "compact_rope_kvwrite", "compact_gemm", "compact_attn_prefill",
     "compact_attn_decode", "compact_moe_route", "compact_moe_ffn",
     "compact_prefix_workspace_bytes", "compact_prefix_decode_step", "compact_attn_decode_prefix",
+    "compact_stack_workspace_bytes", "compact_stack_forward",
 ]
 
 
@@ -92,6 +93,8 @@ def lib():
     L.compact_prefix_workspace_bytes.argtypes = [vp, i32, i32, i32, P(sz)]
     L.compact_prefix_decode_step.argtypes = [vp, P(Weights), i32, vp, P(KV), P(i32), P(KV), vp, P(RouteOut), vp, sz, vp]
     L.compact_attn_decode_prefix.argtypes = [vp, i32, vp, P(KV), P(i32), P(KV), vp, vp, sz, vp]
+    L.compact_stack_workspace_bytes.argtypes = [vp, i64, i32, i32, P(sz)]
+    L.compact_stack_forward.argtypes = [vp, i32, P(Weights), i32, P(i32), vp, i32, vp, P(KV), vp, vp, vp, sz, vp]
     for name in EXPORTS:
         fn = getattr(L, name)
         if name not in ("compact_destroy", "compact_last_error"):
@@ -228,6 +231,30 @@ class Layer:
         self.check(self.L.compact_layer_forward(
             self.ctx, C.byref(self.w), len(cu_seqlens) - 1, _i32arr(cu_seqlens), _ptr(x_prefill), S,
             _ptr(x_decode), C.byref(kv.c), _ptr(y_prefill), _ptr(y_last), _ptr(y_decode), wsp, wsn, _stream()))
+
+    # -- a depth of layers --------------------------------------------------------
+    def stack_workspace_bytes(self, max_tokens, max_blocks, max_kv_len):
+        n = C.c_size_t()
+        self.check(self.L.compact_stack_workspace_bytes(self.ctx, max_tokens, max_blocks, max_kv_len, C.byref(n)))
+        return n.value
+
+    def compact_stack_forward(self, layer_weights, cu_seqlens, x_prefill, x_decode, kvs, y_last, y_decode):
+        """layer_weights: one dict of device tensors per layer; kvs: one KVCache per layer (same geometry)."""
+        wsp, wsn = self._ws()
+        nl = len(layer_weights)
+        warr = (Weights * nl)()
+        for l, wd in enumerate(layer_weights):
+            for name, _ in Weights._fields_:
+                t = wd.get(name)
+                setattr(warr[l], name, t.data_ptr() if t is not None else None)
+        karr = (KV * nl)()
+        for l, kv in enumerate(kvs):
+            for name, _ in KV._fields_:
+                setattr(karr[l], name, getattr(kv.c, name))
+        S = 0 if x_decode is None else x_decode.shape[0]
+        self.check(self.L.compact_stack_forward(
+            self.ctx, nl, warr, len(cu_seqlens) - 1, _i32arr(cu_seqlens), _ptr(x_prefill), S, _ptr(x_decode), karr,
+            _ptr(y_last), _ptr(y_decode), wsp, wsn, _stream()))
 
     # -- prefix-aware layout ------------------------------------------------------
     def prefix_workspace_bytes(self, n_workers, max_prefix_len, max_tail_len):

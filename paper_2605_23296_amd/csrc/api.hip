@@ -453,7 +453,7 @@ static int prefill_impl(compact_ctx* ctx, const compact_weights* w, int n_blocks
     if (cv.off > ws_bytes) return set_err(ctx, COMPACT_EWORKSPACE, "workspace too small for this prefill");
     const int Dq = c.n_q_heads * c.head_dim, Dtot = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
 
-    TRY(upload_plan(ctx, plan, s));
+    if (!plan.d_meta) TRY(upload_plan(ctx, plan, s));   // a depth of layers shares one plan
     TRY(launch_rmsnorm(ctx, x, false, w->g_attn, b.n, T, s));
     TRY(gemm_full(ctx, b.n, w->w_qkv, nullptr, false, b.qkv, T, Dtot, c.d_model, 0, s));
     TRY(launch_rope_kvwrite(ctx, plan.d_meta, plan.d_rope_tiles, (int)plan.rope_tiles.size(), b.qkv, kv->d_k, kv->d_v, s));
@@ -713,6 +713,89 @@ extern "C" int compact_layer_forward(compact_ctx* ctx, const compact_weights* w,
                         (char*)d_y_decode + st * row_bytes, nullptr, db, plan, s));
     }
     for (int b = 0; b < n_blocks; ++b) kv->h_len[b] = h_cu_seqlens[b + 1] - h_cu_seqlens[b] + n_steps;
+    return COMPACT_OK;
+}
+
+// ---------------------------------------------------------------------------
+// a depth of layers
+// ---------------------------------------------------------------------------
+extern "C" int compact_stack_workspace_bytes(const compact_ctx* ctx, int64_t max_tokens, int32_t max_blocks,
+                                             int32_t max_kv_len, size_t* bytes) {
+    size_t one = 0;
+    const int rc = compact_workspace_bytes(ctx, max_tokens, max_blocks, max_kv_len, &one);
+    if (rc != COMPACT_OK) return rc;
+    const size_t es = dtype_size(ctx->cfg.dtype);
+    // two [T, d] and two [N, d] hand-over buffers behind one layer's workspace
+    *bytes = one + 2 * align_up((size_t)max_tokens * ctx->cfg.d_model * es, 256) +
+             2 * align_up((size_t)max_blocks * ctx->cfg.d_model * es, 256) + 256;
+    return COMPACT_OK;
+}
+
+extern "C" int compact_stack_forward(compact_ctx* ctx, int32_t n_layers, const compact_weights* w, int32_t n_blocks,
+                                     const int32_t* h_cu_seqlens, const void* d_x_prefill, int32_t n_steps,
+                                     const void* d_x_decode, compact_kv* kv, void* d_y_last, void* d_y_decode,
+                                     void* d_workspace, size_t ws_bytes, void* hip_stream) {
+    if (!ctx) return COMPACT_EINVAL;
+    if (n_layers < 1) return set_err(ctx, COMPACT_EINVAL, "n_layers must be >= 1");
+    if (n_steps < 0) return set_err(ctx, COMPACT_EINVAL, "n_steps must be >= 0");
+    if (!w || !kv) return set_err(ctx, COMPACT_EINVAL, "null per-layer weights or caches");
+    for (int l = 0; l < n_layers; ++l) {
+        TRY(validate_prefill(ctx, &w[l], n_blocks, h_cu_seqlens, d_x_prefill, &kv[l], d_workspace, n_steps));
+        for (int b = 0; l > 0 && b < n_blocks; ++b) {
+            const bool same = kv[l].h_capacity[b] == kv[0].h_capacity[b] && kv[l].h_slab_offset[b] == kv[0].h_slab_offset[b] &&
+                              (kv[l].h_pos_offset ? kv[l].h_pos_offset[b] : 0) == (kv[0].h_pos_offset ? kv[0].h_pos_offset[b] : 0);
+            if (!same) return set_err(ctx, COMPACT_EINVAL, "the caches of all layers must share one geometry");
+        }
+    }
+    if (n_steps > 0 && (!d_x_decode || !d_y_decode)) return set_err(ctx, COMPACT_EINVAL, "null decode input or output");
+    const compact_layer_cfg& c = ctx->cfg;
+    hipStream_t s = (hipStream_t)hip_stream;
+    Plan plan;
+    build_prefill_plan(&kv[0], n_blocks, h_cu_seqlens, plan);
+    if (n_steps > 0) add_kv_chunks(plan, n_steps);
+    const int64_t T = h_cu_seqlens[n_blocks];
+    const size_t es = dtype_size(c.dtype);
+
+    // workspace: [one layer's prefill region][decode region][two [T, d]][two [N, d]]
+    Carver cp(d_workspace);
+    PrefillBufs pb;
+    carve_prefill(cp, c, T, pb);
+    const size_t off = align_up(cp.off, 256);
+    Carver cd(d_workspace ? (char*)d_workspace + off : nullptr);
+    DecodeBufs db;
+    carve_decode(cd, c, n_blocks, chunks_for(plan.max_len + n_steps), db);
+    size_t end = off + align_up(cd.off, 256);
+    char* base = (char*)d_workspace;
+    void* big[2];
+    void* small[2];
+    for (int i = 0; i < 2; ++i) {
+        big[i] = base + end;
+        end += align_up((size_t)T * c.d_model * es, 256);
+    }
+    for (int i = 0; i < 2; ++i) {
+        small[i] = base + end;
+        end += align_up((size_t)n_blocks * c.d_model * es, 256);
+    }
+    if (end > ws_bytes) return set_err(ctx, COMPACT_EWORKSPACE, "workspace too small for this stack");
+
+    const void* x = d_x_prefill;
+    for (int l = 0; l < n_layers; ++l) {
+        void* y = big[l & 1];
+        TRY(prefill_impl(ctx, &w[l], n_blocks, h_cu_seqlens, x, &kv[l], y, l == n_layers - 1 ? d_y_last : nullptr, nullptr,
+                         d_workspace, off, plan, s));
+        x = y;
+    }
+    const size_t row_bytes = (size_t)n_blocks * c.d_model * es;
+    for (int st = 0; st < n_steps; ++st) {
+        const void* xs = (const char*)d_x_decode + st * row_bytes;
+        for (int l = 0; l < n_layers; ++l) {
+            void* ys = l == n_layers - 1 ? (void*)((char*)d_y_decode + st * row_bytes) : small[l & 1];
+            TRY(decode_impl(ctx, &w[l], n_blocks, st, xs, &kv[l], ys, nullptr, db, plan, s));
+            xs = ys;
+        }
+    }
+    for (int l = 0; l < n_layers; ++l)
+        for (int b = 0; b < n_blocks; ++b) kv[l].h_len[b] = h_cu_seqlens[b + 1] - h_cu_seqlens[b] + n_steps;
     return COMPACT_OK;
 }
 

@@ -74,6 +74,8 @@ WORKLOADS = {
         [128] * 4, 4, 16),
     # 32 k history in 8 blocks of 4 k: the headline prefill + B=8 decode case
     "dense_8x4096": Workload("dense_8x4096", LayerConfig(**DENSE_8B), [4096] * 8, 8, 256),
+    # the paper's own operating point (Sec. V: threshold 96 k tokens, 4 k blocks => 24 workers)
+    "dense_24x4096": Workload("dense_24x4096", LayerConfig(**DENSE_8B), [4096] * 24, 24, 256),
     # 128 k history in 64 blocks of 2 k: decode attention over 64 caches
     "dense_64x2048": Workload("dense_64x2048", LayerConfig(**DENSE_8B), [2048] * 64, 64, 128),
     # 32 ragged blocks, lengths uniform on [512, 8192] inclusive
@@ -183,6 +185,18 @@ def make_inputs(wl, device="cpu", gen_device=None, block_lens=None, decode_steps
     xd = _normal((S, len(lens), layer.d_model), 1.0, gen, device, dt)
     return Inputs(layer, lens, cu_seqlens(lens), x, w, xd,
                   meta=dict(workload=wl.name, seed=wl.seed, gen_device=str(gen_device)))
+
+
+def make_stack_weights(wl, n_layers, device="cpu", gen_device=None, gain_jitter=False):
+    """Weights of a depth of n_layers layers of the workload's shape: layer l is drawn
+    by make_weights' recipe from a generator of its own, seeded wl.seed + 1000 * (l + 1)."""
+    gen_device = gen_device or "cpu"
+    out = []
+    for l in range(n_layers):
+        gen = torch.Generator(device=gen_device)
+        gen.manual_seed(wl.seed + 1000 * (l + 1))
+        out.append(make_weights(wl.layer, gen, device, gain_jitter))
+    return out
 
 
 def to_numpy_f64(t):

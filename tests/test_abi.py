@@ -177,3 +177,47 @@ def test_prefix_aware_calls_reject_bad_arguments_without_a_device():
     pl = (C.c_int32 * 2)(50, 100)
     assert flay.L.compact_prefix_decode_step(flay.ctx, C.byref(flay.w), 2, x, C.byref(s32), pl, C.byref(t32), x, None, ws,
                                              1 << 30, None) == 5
+
+
+def test_stack_call_rejects_bad_arguments_without_a_device():
+    lay = _fake_layer()
+    L, ctx = lay.L, lay.ctx
+    x = C.c_void_p(0x30000)
+    ws = C.c_void_p(0x40000)
+    cu = (C.c_int32 * 3)(0, 100, 200)
+    warr = (B.Weights * 2)()
+    for l in range(2):
+        for name, _ in B.Weights._fields_:
+            setattr(warr[l], name, getattr(lay.w, name))
+
+    def kvarr(caps_per_layer, offs_per_layer=None):
+        arr, keep = (B.KV * len(caps_per_layer))(), []
+        for l, caps in enumerate(caps_per_layer):
+            kv, k = _kv(caps, [0] * len(caps), None if offs_per_layer is None else offs_per_layer[l])
+            keep.append(k)
+            for name, _ in B.KV._fields_:
+                setattr(arr[l], name, getattr(kv, name))
+        return arr, keep
+
+    def stack(nl=2, w=warr, kv=None, steps=4, xd=x, yd=x, ws=ws, wsn=1 << 30):
+        return L.compact_stack_forward(ctx, nl, w, 2, cu, x, steps, xd, kv, None, yd, ws, wsn, None)
+
+    good, keep = kvarr([[128, 128], [128, 128]])
+    assert stack(nl=0, kv=good) == 1
+    assert stack(w=None, kv=good) == 1
+    assert stack(kv=None) == 1
+    assert stack(kv=good, steps=-1) == 1
+    assert stack(kv=good, xd=None) == 1
+    assert stack(kv=good, ws=None) == 4
+    assert stack(kv=good, steps=29) == 3                       # 100 + 29 rows do not fit 128
+    other_caps, k2 = kvarr([[128, 128], [128, 136]])
+    assert stack(kv=other_caps) == 1                           # layer 1's slabs differ from layer 0's
+    assert b"geometry" in L.compact_last_error(ctx)
+    other_offs, k3 = kvarr([[128, 128], [128, 128]], [[0, 1 << 20], [0, 1 << 21]])
+    assert stack(kv=other_offs) == 1
+    assert keep[1]["len"][0] == 0                              # untouched on failure
+    n, m = C.c_size_t(), C.c_size_t()
+    assert L.compact_stack_workspace_bytes(ctx, 512, 4, 160, C.byref(n)) == 0
+    assert L.compact_workspace_bytes(ctx, 512, 4, 160, C.byref(m)) == 0
+    assert n.value >= m.value + 2 * 512 * 256 * 4 + 2 * 4 * 256 * 4
+    assert L.compact_stack_workspace_bytes(ctx, 512, 0, 160, C.byref(n)) == 1

@@ -1,0 +1,125 @@
+"""A depth of layers on the GPU (compact_stack_forward; the models of paper
+Sec. IV-A are stacks of the one layer): checked against the fp64 checker on
+stacks it finishes in seconds, and -- at the named workload's full size --
+against the composition of the single-layer calls, which must be bitwise equal."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import layer as O
+from paper_2605_23296_amd import binding as B
+from paper_2605_23296_amd.workloads import WORKLOADS, LayerConfig, Workload, make_inputs, make_stack_weights, to_numpy_f64
+from tests.util import rel_err, vec_rel_err
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def run_stack(inp, weights, n_steps):
+    layer, cu = inp.layer, inp.cu_seqlens
+    N, T, nl = len(inp.block_lens), cu[-1], len(weights)
+    wdev = [{k: v.to(DEV).contiguous() for k, v in w.items()} for w in weights]
+    lay = B.Layer(layer, wdev[0])
+    dt = lay.torch_dtype
+    kvs = [B.KVCache(layer, [L + n_steps + 3 for L in inp.block_lens], DEV, dt) for _ in range(nl)]
+    for kv in kvs:
+        kv.k.fill_(float("nan"))
+        kv.v.fill_(float("nan"))
+    lay.ws = torch.empty(lay.stack_workspace_bytes(T, N, max(inp.block_lens) + n_steps), dtype=torch.uint8, device=DEV)
+    y_last = torch.empty(N, layer.d_model, dtype=dt, device=DEV)
+    y_dec = torch.empty(n_steps, N, layer.d_model, dtype=dt, device=DEV)
+    xd = inp.x_decode[:n_steps].to(DEV).contiguous()
+    lay.compact_stack_forward(wdev, cu, inp.x_prefill.to(DEV), xd if n_steps else None, kvs, y_last, y_dec if n_steps else None)
+    torch.cuda.synchronize()
+    for kv in kvs:
+        assert kv.lens() == [L + n_steps for L in inp.block_lens]
+    return dict(y_last=y_last, y_dec=y_dec, kvs=kvs, wdev=wdev, lay=lay)
+
+
+def check_against_oracle(inp, weights, n_steps, tol, elem_tol):
+    g = run_stack(inp, weights, n_steps)
+    ref = O.Stack(inp.layer.as_dict(), [{k: to_numpy_f64(v) for k, v in w.items()} for w in weights])
+    y_pre, y_dec, Ks, Vs = ref.forward(to_numpy_f64(inp.x_prefill), inp.cu_seqlens, to_numpy_f64(inp.x_decode[:n_steps]))
+    cu = inp.cu_seqlens
+    errs, elem = {}, {}
+
+    def cmp(tag, got, r):
+        errs[tag] = vec_rel_err(got, r)
+        elem[tag] = rel_err(got, r)
+
+    cmp("y_last", to_numpy_f64(g["y_last"]), np.stack([y_pre[cu[b + 1] - 1] for b in range(len(cu) - 1)]))
+    cmp("y_dec", to_numpy_f64(g["y_dec"]), y_dec)
+    for li in range(len(weights)):
+        for b in range(len(cu) - 1):
+            cmp("K%d_%d" % (li, b), to_numpy_f64(g["kvs"][li].block_k(b)), Ks[li][b])
+            cmp("V%d_%d" % (li, b), to_numpy_f64(g["kvs"][li].block_v(b)), Vs[li][b])
+    worst, worst_e = max(errs, key=errs.get), max(elem, key=elem.get)
+    print("worst vector error", worst, "%.3e" % errs[worst], "| worst element error", worst_e, "%.3e" % elem[worst_e])
+    assert errs[worst] < tol, {k: "%.2e" % v for k, v in errs.items()}
+    assert elem[worst_e] < elem_tol, {k: "%.2e" % v for k, v in elem.items()}
+
+
+def test_tiny_fp32_stack_of_three_layers_in_full():
+    wl = WORKLOADS["tiny_fp32"]
+    inp = make_inputs(wl, block_lens=[128, 65, 1, 97], decode_steps=5)
+    check_against_oracle(inp, make_stack_weights(wl, 3, gain_jitter=True), 5, 1e-5, 1e-5)
+
+
+def test_bf16_stack_of_four_layers_ragged_blocks():
+    layer = LayerConfig(d_model=512, n_q_heads=4, n_kv_heads=2, head_dim=128, ffn_dim=1024, rope_theta=500000.0)
+    wl = Workload("small_dense", layer, [300, 77, 513], 3, 4)
+    inp = make_inputs(wl)
+    check_against_oracle(inp, make_stack_weights(wl, 4, gain_jitter=True), 4, 2e-2, 5e-2)
+
+
+def test_bf16_moe_stack_keeps_the_caches_right():
+    """Routed layers: a near-tie may move single output rows, the caches of layer 0
+    depend on no routing and the decode outputs agree in the median."""
+    layer = LayerConfig(d_model=256, n_q_heads=8, n_kv_heads=2, head_dim=64, ffn_dim=320, n_experts=16, top_k=4,
+                        rope_theta=500000.0)
+    wl = Workload("small_moe", layer, [130, 40], 2, 3)
+    inp = make_inputs(wl)
+    ws = make_stack_weights(wl, 2)
+    g = run_stack(inp, ws, 3)
+    ref = O.Stack(layer.as_dict(), [{k: to_numpy_f64(v) for k, v in w.items()} for w in ws])
+    _, y_dec, Ks, Vs = ref.forward(to_numpy_f64(inp.x_prefill), inp.cu_seqlens, to_numpy_f64(inp.x_decode))
+    for b in range(2):
+        assert vec_rel_err(to_numpy_f64(g["kvs"][0].block_k(b)), Ks[0][b]) < 2e-2
+        assert vec_rel_err(to_numpy_f64(g["kvs"][0].block_v(b)), Vs[0][b]) < 2e-2
+    err = np.sort(np.array([vec_rel_err(to_numpy_f64(g["y_dec"][s, b]), y_dec[s, b]) for s in range(3) for b in range(2)]))
+    assert err[len(err) // 2] < 2e-2
+
+
+def test_dense_8x4096_stack_equals_the_single_layer_calls_bitwise():
+    """Full size: three layers of the named workload through compact_stack_forward must
+    give the bits of compact_prefill / compact_decode_step applied layer by layer (those
+    are checked against the fp64 checker at this size in test_gpu_full_size.py)."""
+    wl = WORKLOADS["dense_8x4096"]
+    S, nl = 3, 3
+    inp = make_inputs(wl, device=DEV, gen_device=DEV, decode_steps=S)
+    ws = make_stack_weights(wl, nl, device=DEV, gen_device=DEV)
+    g = run_stack(inp, ws, S)
+    layer, cu = inp.layer, inp.cu_seqlens
+    N, T = len(inp.block_lens), cu[-1]
+    dt = torch.bfloat16
+    lays = [B.Layer(layer, w) for w in g["wdev"]]
+    kvs = [B.KVCache(layer, [L + S + 3 for L in inp.block_lens], DEV, dt) for _ in range(nl)]
+    x = inp.x_prefill
+    for l in range(nl):
+        lays[l].ensure_workspace(T, N, max(inp.block_lens) + S, DEV)
+        y = torch.empty(T, layer.d_model, dtype=dt, device=DEV)
+        lays[l].compact_prefill(cu, x, kvs[l], y)
+        x = y
+    assert torch.equal(g["y_last"], x[[c - 1 for c in cu[1:]]])
+    for s in range(S):
+        xs = inp.x_decode[s].contiguous()
+        for l in range(nl):
+            ys = torch.empty(N, layer.d_model, dtype=dt, device=DEV)
+            lays[l].compact_decode_step(xs, kvs[l], ys)
+            xs = ys
+        assert torch.equal(g["y_dec"][s], xs), s
+    torch.cuda.synchronize()
+    for l in range(nl):
+        for b in (0, N - 1):
+            assert torch.equal(g["kvs"][l].block_k(b), kvs[l].block_k(b))
+            assert torch.equal(g["kvs"][l].block_v(b), kvs[l].block_v(b))
