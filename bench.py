@@ -24,7 +24,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 from paper_2605_23296_amd import binding as B                       # noqa: E402
-from paper_2605_23296_amd.workloads import WORKLOADS, make_inputs  # noqa: E402
+from paper_2605_23296_amd.workloads import WORKLOADS, make_inputs, make_stack_weights  # noqa: E402
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
@@ -195,6 +195,51 @@ def prefix_aware_pass(args, wl, inp, lay, bufs):
     }
 
 
+def stack_pass(args, wl, inp, lay, bufs):
+    """L layers deep: the parallel pass (N blocks, S batched steps) and the sequential
+    baseline at matched decode volume (one block = the whole history, N * S steps)."""
+    layer, dev, dt = inp.layer, bufs["x"].device, lay.torch_dtype
+    lens, S, N, T = inp.block_lens, inp.x_decode.shape[0], len(inp.block_lens), inp.cu_seqlens[-1]
+    L = args.stack
+    weights = make_stack_weights(wl, L, device=dev, gen_device=dev)
+    need = max(lay.stack_workspace_bytes(T, N, max(lens) + S), lay.stack_workspace_bytes(T, 1, T + N * S))
+    lay.ws = torch.empty(need, dtype=torch.uint8, device=dev)
+
+    kvs = [B.KVCache(layer, [n + S for n in lens], dev, dt) for _ in range(L)]
+    par = lambda steps: lay.compact_stack_forward(weights, inp.cu_seqlens, bufs["x"], bufs["xd"][:steps] if steps else None,
+                                                  kvs, bufs["y_last"], bufs["y_dec"] if steps else None)
+    par(min(S, 8))
+    t_par = timed(lambda: par(S), max(1, args.steps))
+    t_par_pre = timed(lambda: par(0), 1)
+    del kvs
+
+    Ls = args.seq_layers if args.seq_layers > 0 else L
+    kv1 = [B.KVCache(layer, [T + N * S], dev, dt) for _ in range(Ls)]
+    xd1 = bufs["xd"].reshape(S * N, 1, layer.d_model)
+    yd1 = torch.empty_like(xd1)
+    seq = lambda steps: lay.compact_stack_forward(weights[:Ls], [0, T], bufs["x"], xd1[:steps] if steps else None, kv1,
+                                                  bufs["y_last"][:1], yd1 if steps else None)
+    seq(8)
+    t_seq = timed(lambda: seq(S * N), 1) * L / Ls
+    t_seq_pre = timed(lambda: seq(0), 1) * L / Ls
+    return {
+        "metric": "compaction_decode_tokens_per_s", "value": N * S / t_par, "unit": "tokens/s", "n_gpus": 1,
+        "steps": max(1, args.steps), "warmup": 1, "ms_per_step": t_par * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": layer.dtype, "data": "synthetic",
+        "config": {"workload": "%s, %d layers deep (random weights per layer): %d blocks x %d tokens prefill + %d decode "
+                               "steps/block" % (wl.name, L, N, lens[0], S), "total_prefill_tokens": T, "decode_tokens": N * S,
+                   "n_layers": L},
+        "ms_prefill": t_par_pre * 1e3, "ms_decode": (t_par - t_par_pre) * 1e3,
+        "us_per_decode_step_per_layer": (t_par - t_par_pre) * 1e6 / max(S, 1) / L,
+        "ms_per_decode_token": t_par * 1e3 / (N * S),
+        "sequential_single_block": {
+            "what": "the whole %d-token history as one block, the same %d decode tokens one after another" % (T, N * S),
+            "layers_measured": Ls, "scaled_to_layers": L, "ms_per_step": t_seq * 1e3, "ms_prefill": t_seq_pre * 1e3,
+            "ms_decode": (t_seq - t_seq_pre) * 1e3, "ms_per_decode_token": t_seq * 1e3 / (N * S),
+            "parallel_speedup": t_seq / t_par},
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -206,6 +251,13 @@ def main():
     ap.add_argument("--prefix-aware", action="store_true",
                     help="time the prefix-aware target-at-end layout instead (paper Sec. IV, Dispatch): the history is "
                          "prefilled once as one block, every worker then decodes against its prefix of that shared cache")
+    ap.add_argument("--stack", type=int, default=0, metavar="L",
+                    help="time a depth of L layers instead (compact_stack_forward; per-layer weights and caches), and "
+                         "beside it the paper's sequential baseline: the whole history as ONE block, the same number of "
+                         "decode tokens one after another (Sec. V, Tables VII-IX)")
+    ap.add_argument("--seq-layers", type=int, default=0,
+                    help="layers of the sequential baseline under --stack (default: all L; every layer costs the same, "
+                         "so fewer layers are scaled up and labelled so)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="first run one plain device copy of this many MiB (a kernel of known HBM traffic, "
                          "used to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -240,6 +292,10 @@ def main():
 
     if args.prefix_aware:
         print(json.dumps(prefix_aware_pass(args, wl, inp, lay, bufs)))
+        return
+    if args.stack > 0:
+        del kv
+        print(json.dumps(stack_pass(args, wl, inp, lay, bufs)))
         return
 
     for _ in range(args.warmup):
