@@ -250,6 +250,27 @@ class Layer:
                     gate=None if gate is None else gate[0],
                     logits=None if logits is None else logits[0])
 
+    def extend_block(self, x, K, V, pos0=0, rows=None):
+        """The next chunk of a block whose cache already holds len = K.shape[0]
+        rows (a prefill cut into chunks, Sec. IV-B: the server prefills long
+        prompts chunk by chunk; also a worker's own block behind a cached prefix).
+
+        x [C, d] sits at positions pos0 + len .. pos0 + len + C - 1; its K/V rows
+        are appended and chunk row i attends cache rows 0 .. len + i.  Returns a
+        dict like prefill_block, K and V grown by C rows.
+        """
+        x = _f64(x)
+        C = x.shape[0]
+        n_cached = K.shape[0]
+        q, k, v = self.qkv(x, pos0 + n_cached + np.arange(C))
+        K = np.concatenate([K, k], axis=0)
+        V = np.concatenate([V, v], axis=0)
+        rows = np.arange(C) if rows is None else np.asarray(rows, dtype=np.int64)
+        o = gqa_attention(q[rows], K, V, visible=n_cached + rows + 1)
+        h = x[rows] + o.reshape(len(rows), self.Dq) @ _f64(self.w["w_o"]).T
+        y, idx, gate, logits = self.ffn(h)
+        return dict(y=y, K=K, V=V, rows=rows, idx=idx, gate=gate, logits=logits)
+
     # -- the batch of blocks ------------------------------------------------
     def prefill(self, x, cu_seqlens, pos_offset=None, rows=None):
         """Block b = rows cu[b]..cu[b+1]-1 of the packed x [T, d]; blocks are

@@ -581,3 +581,54 @@ def test_stack_batched_equals_one_block_at_a_time(rng):
         y1, yd1, _, _ = st.forward(x[cu[b]:cu[b + 1]], [0, cu[b + 1] - cu[b]], xd[:, b:b + 1])
         np.testing.assert_array_equal(y[cu[b]:cu[b + 1]], y1)
         np.testing.assert_array_equal(yd[:, b], yd1[:, 0])
+
+
+# ---------------------------------------------------------------------------
+# a prefill cut into chunks (paper Sec. IV-B: chunked prefill on the server)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("moe", [False, True])
+@pytest.mark.parametrize("cuts", [[4], [1, 5], [3, 3, 4], [10]])
+def test_chunked_prefill_equals_the_prefill_in_one_piece(rng, moe, cuts):
+    """Cutting a block's prefill into chunks that are appended one after another gives
+    the outputs and the cache of the prefill in one piece (the full score matrix)."""
+    lay = _small_layer(rng, moe)
+    L = 11
+    x = rng.standard_normal((L, 64))
+    whole = lay.prefill_block(x, pos0=3)
+    K = np.zeros((0, lay.Hkv, lay.hd))
+    V = np.zeros((0, lay.Hkv, lay.hd))
+    ys, a = [], 0
+    for c in cuts + [L - sum(cuts)]:
+        if c == 0:
+            continue
+        st = lay.extend_block(x[a:a + c], K, V, pos0=3)
+        K, V = st["K"], st["V"]
+        ys.append(st["y"])
+        a += c
+    np.testing.assert_allclose(np.concatenate(ys), whole["y"], rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(K, whole["K"], rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(V, whole["V"], rtol=1e-12, atol=1e-14)
+
+
+def test_a_chunk_of_one_token_is_a_decode_step(rng):
+    lay = _small_layer(rng)
+    x = rng.standard_normal((7, 64))
+    pre = lay.prefill_block(x[:6], pos0=2)
+    a = lay.extend_block(x[6:7], pre["K"], pre["V"], pos0=2)
+    b = lay.decode_block(x[6], pre["K"], pre["V"], pos0=2)
+    np.testing.assert_array_equal(a["y"][0], b["y"])
+    np.testing.assert_array_equal(a["K"], b["K"])
+
+
+def test_chunk_rows_subset_and_causality_inside_a_chunk(rng):
+    lay = _small_layer(rng)
+    x = rng.standard_normal((9, 64))
+    pre = lay.prefill_block(x[:4])
+    full = lay.extend_block(x[4:], pre["K"], pre["V"])
+    sub = lay.extend_block(x[4:], pre["K"], pre["V"], rows=[0, 3])
+    np.testing.assert_array_equal(sub["y"], full["y"][[0, 3]])
+    x2 = x.copy()
+    x2[7] += 1.0                                  # chunk row 3
+    pert = lay.extend_block(x2[4:], pre["K"], pre["V"])
+    np.testing.assert_array_equal(pert["y"][:3], full["y"][:3])
+    assert np.abs(pert["y"][3:] - full["y"][3:]).max() > 1e-4
