@@ -139,6 +139,19 @@ int compact_prefill(compact_ctx* ctx, const compact_weights* w, int32_t n_blocks
                     const compact_route_out* route, void* d_workspace, size_t ws_bytes,
                     void* hip_stream);
 
+/* The next chunk of every block (a prefill cut into chunks as the paper's server
+ * does, Sec. IV-B "chunked prefill"; also a worker's own block behind an
+ * already cached prefix, Sec. IV Dispatch): as compact_prefill, but block b's
+ * rows are appended behind the h_len[b] rows its cache already holds.  Row i
+ * of the chunk sits at rotary position pos_offset[b] + h_len[b] + i, is
+ * written to cache row h_len[b] + i and attends cache rows 0 .. h_len[b] + i.
+ * h_len[b] grows by the chunk length; with h_len[b] = 0 this is
+ * compact_prefill.  COMPACT_ECAPACITY when h_len[b] + L_b exceeds the slab.  */
+int compact_prefill_extend(compact_ctx* ctx, const compact_weights* w, int32_t n_blocks,
+                           const int32_t* h_cu_seqlens, const void* d_x, compact_kv* kv, void* d_y,
+                           const compact_route_out* route, void* d_workspace, size_t ws_bytes,
+                           void* hip_stream);
+
 /* One batched decode step (the concurrent workers each emitting one summary
  * token): d_x [N, d] holds one new token per block, at rotary position
  * pos_offset[b] + len[b].  Its K/V row is appended at row len[b], it attends

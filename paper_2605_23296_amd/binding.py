@@ -25,7 +25,7 @@ EXPORTS = [
     "compact_rmsnorm", "compact_rope_kvwrite", "compact_gemm", "compact_attn_prefill",
     "compact_attn_decode", "compact_moe_route", "compact_moe_ffn",
     "compact_prefix_workspace_bytes", "compact_prefix_decode_step", "compact_attn_decode_prefix",
-    "compact_stack_workspace_bytes", "compact_stack_forward",
+    "compact_stack_workspace_bytes", "compact_stack_forward", "compact_prefill_extend",
 ]
 
 
@@ -80,6 +80,7 @@ def lib():
     L.compact_workspace_bytes.argtypes = [vp, i64, i32, i32, P(sz)]
     L.compact_prefill.argtypes = [vp, P(Weights), i32, P(i32), vp, P(KV), vp, P(RouteOut), vp, sz, vp]
     L.compact_decode_step.argtypes = [vp, P(Weights), i32, vp, P(KV), vp, P(RouteOut), vp, sz, vp]
+    L.compact_prefill_extend.argtypes = [vp, P(Weights), i32, P(i32), vp, P(KV), vp, P(RouteOut), vp, sz, vp]
     L.compact_layer_forward.argtypes = [vp, P(Weights), i32, P(i32), vp, i32, vp, P(KV), vp, vp, vp, vp, sz, vp]
     L.compact_profile_select.argtypes = [vp, i32]
     L.compact_profile_read.argtypes = [vp, P(i64), P(C.c_double)]
@@ -218,6 +219,12 @@ class Layer:
         r = None if route is None else C.byref(RouteOut(route[0].data_ptr(), route[1].data_ptr()))
         self.check(self.L.compact_prefill(self.ctx, C.byref(self.w), len(cu_seqlens) - 1, _i32arr(cu_seqlens),
                                           _ptr(x), C.byref(kv.c), _ptr(y), r, wsp, wsn, _stream()))
+
+    def compact_prefill_extend(self, cu_seqlens, x, kv, y, route=None):
+        wsp, wsn = self._ws()
+        r = None if route is None else C.byref(RouteOut(route[0].data_ptr(), route[1].data_ptr()))
+        self.check(self.L.compact_prefill_extend(self.ctx, C.byref(self.w), len(cu_seqlens) - 1, _i32arr(cu_seqlens),
+                                                 _ptr(x), C.byref(kv.c), _ptr(y), r, wsp, wsn, _stream()))
 
     def compact_decode_step(self, x, kv, y, route=None):
         wsp, wsn = self._ws()

@@ -352,12 +352,14 @@ static int check_blocks(compact_ctx* ctx, int n_blocks, const int32_t* cu) {
     return COMPACT_OK;
 }
 
-static void build_prefill_plan(const compact_kv* kv, int n_blocks, const int32_t* cu, Plan& p) {
+// extend: the rows of the call are appended behind the h_len[b] rows the cache holds
+static void build_prefill_plan(const compact_kv* kv, int n_blocks, const int32_t* cu, Plan& p, bool extend = false) {
     p.meta.resize(n_blocks);
     for (int b = 0; b < n_blocks; ++b) {
         BlockMeta& m = p.meta[b];
         m.row0 = cu[b];
         m.len = cu[b + 1] - cu[b];
+        m.prior = extend ? kv->h_len[b] : 0;
         m.capacity = kv->h_capacity[b];
         m.pos_offset = kv->h_pos_offset ? kv->h_pos_offset[b] : 0;
         m.slab = kv->h_slab_offset[b];
@@ -365,9 +367,11 @@ static void build_prefill_plan(const compact_kv* kv, int n_blocks, const int32_t
         for (int r = 0; r < m.len; r += ROPE_TILE) p.rope_tiles.push_back({b, r});
         for (int r = 0; r < m.len; r += PREFILL_QTILE) p.q_tiles.push_back({b, r});
     }
-    // causal work of a query tile grows with its row offset: heaviest first
-    std::stable_sort(p.q_tiles.begin(), p.q_tiles.end(),
-                     [](const TileItem& a, const TileItem& b) { return a.row0 > b.row0; });
+    // causal work of a query tile grows with its cache row: heaviest first
+    const std::vector<BlockMeta>& mt = p.meta;
+    std::stable_sort(p.q_tiles.begin(), p.q_tiles.end(), [&mt](const TileItem& a, const TileItem& b) {
+        return mt[a.block].prior + a.row0 > mt[b.block].prior + b.row0;
+    });
 }
 
 // Work list of the split-KV decode attention: every DECODE_CHUNK-row chunk that some
@@ -500,6 +504,25 @@ extern "C" int compact_prefill(compact_ctx* ctx, const compact_weights* w, int32
     return COMPACT_OK;
 }
 
+extern "C" int compact_prefill_extend(compact_ctx* ctx, const compact_weights* w, int32_t n_blocks,
+                                      const int32_t* h_cu_seqlens, const void* d_x, compact_kv* kv, void* d_y,
+                                      const compact_route_out* route, void* d_workspace, size_t ws_bytes, void* hip_stream) {
+    if (!ctx) return COMPACT_EINVAL;
+    TRY(validate_prefill(ctx, w, n_blocks, h_cu_seqlens, d_x, kv, d_workspace, 0));
+    if (!d_y) return set_err(ctx, COMPACT_EINVAL, "null output");
+    for (int b = 0; b < n_blocks; ++b) {
+        if (kv->h_len[b] < 0) return set_err(ctx, COMPACT_EINVAL, "negative h_len");
+        if ((int64_t)kv->h_len[b] + (h_cu_seqlens[b + 1] - h_cu_seqlens[b]) > kv->h_capacity[b])
+            return set_err(ctx, COMPACT_ECAPACITY, "block " + std::to_string(b) + ": cached rows + chunk exceed its KV slab");
+    }
+    Plan plan;
+    build_prefill_plan(kv, n_blocks, h_cu_seqlens, plan, true);
+    TRY(prefill_impl(ctx, w, n_blocks, h_cu_seqlens, d_x, kv, d_y, nullptr, route, d_workspace, ws_bytes, plan,
+                     (hipStream_t)hip_stream));
+    for (int b = 0; b < n_blocks; ++b) kv->h_len[b] += h_cu_seqlens[b + 1] - h_cu_seqlens[b];
+    return COMPACT_OK;
+}
+
 // ---------------------------------------------------------------------------
 // decode
 // ---------------------------------------------------------------------------
@@ -516,7 +539,7 @@ static int run_attn_decode(compact_ctx* ctx, const Plan& p, int n_blocks, int st
 
 // Prefix-aware layout: what the decode step needs besides the per-worker tails.
 struct PrefixArgs {
-    BlockMeta shared;             // the one shared block (the whole history)
+    BlockMeta shared{};           // the one shared block (the whole history)
     const void *d_k, *d_v;        // its slabs
     std::vector<PrefixItem> items;
     std::vector<int32_t> wl_off, wl;

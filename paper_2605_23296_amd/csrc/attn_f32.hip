@@ -44,7 +44,7 @@ __global__ __launch_bounds__(256) void attn_prefill_f32_kernel(const BlockMeta* 
     const float* kslab = kbase + bm.slab + (size_t)kvh * bm.capacity * HD;
     const float* vslab = vbase + bm.slab + (size_t)kvh * HD * bm.capacity;
     RowState st = {-INFINITY, 0.f, 0.f, 0.f};
-    for (int j = 0; j <= i; ++j) visit_key<HD>(st, q0, q1, kslab + (size_t)j * HD, vslab + j, bm.capacity, scale);
+    for (int j = 0; j <= bm.prior + i; ++j) visit_key<HD>(st, q0, q1, kslab + (size_t)j * HD, vslab + j, bm.capacity, scale);
     float* orow = o + (size_t)(bm.row0 + i) * Hq * HD + h * HD;
     orow[lane] = st.acc0 / st.l;
     if (HD == 128) orow[lane + 64] = st.acc1 / st.l;

@@ -65,15 +65,16 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_bf16_kernel(const BlockMe
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int r = lane & 31, h = lane >> 5;
     const int ld = (Hq + 2 * Hkv) * HD;
-    const int len = bm.len;
+    const int len = bm.prior + bm.len;   // cache rows once this call's rows are in
+    const int prior = bm.prior;          // query row i of the call is cache row prior + i
 
     const bf16* kslab = kbase + bm.slab + (size_t)kvh * bm.capacity * HD;
     const bf16* vslab = vbase + bm.slab + (size_t)kvh * HD * bm.capacity;
 
     // ---- Q^T operand: lane (q = r, h) holds Q[q][kk*16 + h*8 .. +7] -----------
-    const int qrow = it.row0 + wave * 32 + r;         // block-local
+    const int qrow = prior + it.row0 + wave * 32 + r;   // as a cache row
     const int qrow_c = min(qrow, len - 1);
-    const bf16* qp = qkv + (size_t)(bm.row0 + qrow_c) * ld + head * HD + h * 8;
+    const bf16* qp = qkv + (size_t)(bm.row0 + qrow_c - prior) * ld + head * HD + h * 8;
     bf16x8 qf[KK];
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16);
@@ -85,8 +86,8 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_bf16_kernel(const BlockMe
         for (int e = 0; e < 16; ++e) oacc[d][e] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
 
-    const int q_hi_wg = min(it.row0 + PREFILL_QTILE, len) - 1;   // last query row of the workgroup
-    const int q_hi_wave = it.row0 + wave * 32 + 31;              // last query row of this wave
+    const int q_hi_wg = min(prior + it.row0 + PREFILL_QTILE, len) - 1;   // last query row of the workgroup
+    const int q_hi_wave = prior + it.row0 + wave * 32 + 31;              // last query row of this wave
     const int n_tiles = q_hi_wg / KV_TILE + 1;
 
     // ---- staging ----------------------------------------------------------------
@@ -216,7 +217,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_bf16_kernel(const BlockMe
         }
     };
 
-    const int q_lo_wave = it.row0 + wave * 32;   // first query row of this wave
+    const int q_lo_wave = prior + it.row0 + wave * 32;   // first query row of this wave
     for (int kt = 0; kt < n_tiles; ++kt) {
         const int kv0 = kt * KV_TILE;
         const bf16* ks = lds + (kt & 1) * 2 * KTILE;
@@ -235,7 +236,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_bf16_kernel(const BlockMe
     l_run += __shfl_xor(l_run, 32, 64);
     if (qrow < len) {
         const float inv = 1.0f / l_run;
-        bf16* op = o + (size_t)(bm.row0 + qrow) * Hq * HD + head * HD;
+        bf16* op = o + (size_t)(bm.row0 + qrow - prior) * Hq * HD + head * HD;
 #pragma unroll
         for (int d = 0; d < DT; ++d)
 #pragma unroll

@@ -31,6 +31,8 @@ struct BlockMeta {
     int32_t capacity;    // slab rows
     int32_t pos_offset;  // added to the block-local index to get the rotary position
     int64_t slab;        // element offset of the block's slabs in d_k / d_v
+    int32_t prior;       // prefill of a further chunk: rows the cache already holds (row i of the call is cache row prior + i)
+    int32_t pad_;
 };
 
 // Per-row 1/rms handed from one kernel to the next as per-column-group sums of

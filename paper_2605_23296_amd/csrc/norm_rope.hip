@@ -88,7 +88,7 @@ __global__ __launch_bounds__(NT) void rope_kvwrite_kernel(const BlockMeta* __res
     for (int idx = threadIdx.x; idx < ntok * half; idx += NT) {
         const int tok = idx / half, i = idx - tok * half;
         const double inv_freq = exp2(-2.0 * (double)i / (double)hd * log2_theta);
-        const double ang = (double)(bm.pos_offset + p0 + tok) * inv_freq;
+        const double ang = (double)(bm.pos_offset + bm.prior + p0 + tok) * inv_freq;
         double sn, cn;
         sincos(ang, &sn, &cn);
         cs[idx] = make_float2((float)cn, (float)sn);
@@ -114,7 +114,7 @@ __global__ __launch_bounds__(NT) void rope_kvwrite_kernel(const BlockMeta* __res
             ohi[j] = hi[j] * t.x + lo[j] * t.y;
         }
         T* dst = src;
-        if (head >= Hq) dst = kslab + ((size_t)(head - Hq) * bm.capacity + p0 + tok) * hd + c * 8;
+        if (head >= Hq) dst = kslab + ((size_t)(head - Hq) * bm.capacity + bm.prior + p0 + tok) * hd + c * 8;
         store8(dst, olo);
         store8(dst + half, ohi);
     }
@@ -136,8 +136,8 @@ __global__ __launch_bounds__(NT) void rope_kvwrite_kernel(const BlockMeta* __res
             const int dd = idx / (ROPE_TILE / 8), c = idx - dd * (ROPE_TILE / 8);
             const int t0 = c * 8;
             if (t0 >= ntok) continue;
-            T* dst = vslab + ((size_t)kvh * hd + dd) * bm.capacity + p0 + t0;
-            if (t0 + 8 <= ntok) {
+            T* dst = vslab + ((size_t)kvh * hd + dd) * bm.capacity + bm.prior + p0 + t0;
+            if (t0 + 8 <= ntok && (bm.prior & 7) == 0) {   // 16-byte stores need an aligned cache row
                 float v[8];
 #pragma unroll
                 for (int j = 0; j < 8; ++j) v[j] = to_f32(vt[(t0 + j) * vld + dd]);

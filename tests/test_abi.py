@@ -221,3 +221,21 @@ def test_stack_call_rejects_bad_arguments_without_a_device():
     assert L.compact_workspace_bytes(ctx, 512, 4, 160, C.byref(m)) == 0
     assert n.value >= m.value + 2 * 512 * 256 * 4 + 2 * 4 * 256 * 4
     assert L.compact_stack_workspace_bytes(ctx, 512, 0, 160, C.byref(n)) == 1
+
+
+def test_prefill_extend_rejects_bad_arguments_without_a_device():
+    lay = _fake_layer()
+    L, ctx, w = lay.L, lay.ctx, C.byref(lay.w)
+    x = C.c_void_p(0x30000)
+    ws = C.c_void_p(0x40000)
+    cu = (C.c_int32 * 3)(0, 100, 200)
+    kv, keep = _kv([128, 128], [28, 29])
+    call = lambda kv=kv, y=x, ws=ws: L.compact_prefill_extend(ctx, w, 2, cu, x, C.byref(kv), y, None, ws, 1 << 30, None)
+    assert call() == 3                                    # block 1: 29 cached + 100 new rows > 128
+    assert b"chunk" in L.compact_last_error(ctx)
+    assert keep["len"][0] == 28 and keep["len"][1] == 29  # untouched on failure
+    kv2, keep2 = _kv([128, 128], [-1, 0])
+    assert call(kv=kv2) == 1
+    kv3, _ = _kv([128, 128], [28, 28])
+    assert call(kv=kv3, y=None) == 1
+    assert call(kv=kv3, ws=None) == 4
