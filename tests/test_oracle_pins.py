@@ -632,3 +632,60 @@ def test_chunk_rows_subset_and_causality_inside_a_chunk(rng):
     pert = lay.extend_block(x2[4:], pre["K"], pre["V"])
     np.testing.assert_array_equal(pert["y"][:3], full["y"][:3])
     assert np.abs(pert["y"][3:] - full["y"][3:]).max() > 1e-4
+
+
+# ---------------------------------------------------------------------------
+# block-scaled 4-bit weights ("mxfp4 weights", paper Sec. IV-B; OCP MX v1.0)
+# ---------------------------------------------------------------------------
+def test_fp4_code_values_match_the_specification_table():
+    from oracle import mxfp4 as Q
+    rows = [ln.split() for ln in open(os.path.join(HERE, "golden", "fp4_e2m1_values.txt")) if ln.strip() and not ln.startswith("#")]
+    assert len(rows) == 16
+    for bits, val in rows:
+        got = Q.e2m1_value(int(bits, 2))
+        assert got == float(val) and np.signbit(got) == np.signbit(float(val)), bits
+
+
+def test_e8m0_scales_are_powers_of_two():
+    from oracle import mxfp4 as Q
+    assert Q.e8m0_value(127) == 1.0 and Q.e8m0_value(126) == 0.5 and Q.e8m0_value(130) == 8.0
+    assert Q.e8m0_value(0) == 2.0 ** -127 and Q.e8m0_value(254) == 2.0 ** 127
+    with pytest.raises(ValueError):
+        Q.e8m0_value(255)
+
+
+def test_mxfp4_packing_order_and_block_scales_by_planting_single_codes():
+    """One non-zero code at a time: element k must come out at index k, scaled by the
+    scale byte of block k // 32 only."""
+    from oracle import mxfp4 as Q
+    K = 96
+    for k in (0, 1, 2, 31, 32, 33, 63, 64, 95):
+        codes = np.zeros((2, K // 2), dtype=np.uint8)
+        scales = np.full((2, K // 32), 127, dtype=np.uint8)
+        codes[1, k // 2] = 0x7 << (4 * (k % 2))          # +6.0 at element k of row 1
+        scales[1, k // 32] = 125                         # x 1/4 for that block only
+        scales[0, k // 32] = 140                         # another row's scale must not matter
+        w = Q.dequantize(codes, scales)
+        expect = np.zeros((2, K))
+        expect[1, k] = 1.5
+        np.testing.assert_array_equal(w, expect)
+
+
+def test_mxfp4_dequantize_is_exact_on_representable_matrices(rng):
+    """Build a matrix from values of the form (+-){0,.5,1,1.5,2,3,4,6} * 2^s per block of 32, encode it by
+    searching the sixteen codes (brute force), and get the same matrix back."""
+    from oracle import mxfp4 as Q
+    vals = np.array([0, .5, 1, 1.5, 2, 3, 4, 6])
+    R, K = 5, 128
+    mag = rng.integers(0, 8, size=(R, K))
+    sgn = rng.integers(0, 2, size=(R, K))
+    exps = rng.integers(-12, 5, size=(R, K // 32))
+    w = np.where(sgn == 1, -1.0, 1.0) * vals[mag] * np.repeat(2.0 ** exps, 32, axis=1)
+    codes = np.zeros((R, K // 2), dtype=np.uint8)
+    for r in range(R):
+        for k in range(K):
+            target = w[r, k] / 2.0 ** exps[r, k // 32]
+            c = [c for c in range(16) if Q.e2m1_value(c) == target and np.signbit(Q.e2m1_value(c)) == (sgn[r, k] == 1)][0]
+            codes[r, k // 2] |= c << (4 * (k % 2))
+    scales = (exps + 127).astype(np.uint8)
+    np.testing.assert_array_equal(Q.dequantize(codes, scales), w)
