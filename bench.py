@@ -24,7 +24,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 from paper_2605_23296_amd import binding as B                       # noqa: E402
-from paper_2605_23296_amd.workloads import WORKLOADS, make_inputs, make_stack_weights  # noqa: E402
+from paper_2605_23296_amd.workloads import WORKLOADS, make_inputs, make_mxfp4_experts, make_stack_weights  # noqa: E402
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
@@ -38,7 +38,7 @@ def layer_params(layer):
     return attn + layer.n_experts * d + layer.top_k * 3 * F * d      # parameters touched per token
 
 
-def algorithmic_work(layer, lens, S, distinct_experts_per_step=None):
+def algorithmic_work(layer, lens, S, distinct_experts_per_step=None, expert_bits=16.0):
     """Work the method must do, per pass (each weight once per call, the causal
     half of attention, each cached KV byte once per decode step).  For a routed
     layer a decode step must read the weights of every expert that some row of
@@ -58,7 +58,7 @@ def algorithmic_work(layer, lens, S, distinct_experts_per_step=None):
         attn = (layer.Dq + 2 * layer.Dkv) * d + d * layer.Dq
         experts = sum(distinct_experts_per_step) if distinct_experts_per_step else S * min(layer.n_experts, N * layer.top_k)
         # the router (E x d) runs through the prefill-size GEMM class and is not counted here
-        w["skinny_bytes"] = 2.0 * (S * attn + experts * 3 * F * d)
+        w["skinny_bytes"] = 2.0 * S * attn + experts * 3 * F * d * expert_bits / 8.0
     return w
 
 
@@ -251,6 +251,9 @@ def main():
     ap.add_argument("--prefix-aware", action="store_true",
                     help="time the prefix-aware target-at-end layout instead (paper Sec. IV, Dispatch): the history is "
                          "prefilled once as one block, every worker then decodes against its prefix of that shared cache")
+    ap.add_argument("--mxfp4", action="store_true",
+                    help="routed workloads: the experts come as block-scaled 4-bit arrays (paper Sec. IV-B, mxfp4 weights); "
+                         "decode steps stream those, the prefill reads their exact bf16 expansion")
     ap.add_argument("--stack", type=int, default=0, metavar="L",
                     help="time a depth of L layers instead (compact_stack_forward; per-layer weights and caches), and "
                          "beside it the paper's sequential baseline: the whole history as ONE block, the same number of "
@@ -280,6 +283,18 @@ def main():
         del src, dst
     inp = make_inputs(wl, device=dev, gen_device=dev)
     layer = inp.layer
+    if args.mxfp4:
+        if layer.n_experts == 0:
+            print("bench.py: --mxfp4 needs a routed workload (--workload moe_16x8192)", file=sys.stderr)
+            sys.exit(2)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(wl.seed + 77)
+        q4 = make_mxfp4_experts(layer, gen, dev)
+        lay0 = B.Layer(layer, None)
+        for name in ("w_exp_gate_up", "w_exp_down"):       # the 16-bit copy = the exact expansion of the 4-bit arrays
+            lay0.compact_mxfp4_dequant(q4[name + "_q"], q4[name + "_s"], inp.weights[name])
+        inp.weights.update(q4)
+        torch.cuda.synchronize()
     lens, S, N, T = inp.block_lens, inp.x_decode.shape[0], len(inp.block_lens), inp.cu_seqlens[-1]
     lay = B.Layer(layer, inp.weights)
     dt = lay.torch_dtype
@@ -308,7 +323,7 @@ def main():
 
     # per-kernel-class durations from HIP events on the launch stream, one class per extra pass
     n_distinct = distinct_experts(lay, inp, kv, bufs) if layer.n_experts > 0 else None
-    work = algorithmic_work(layer, lens, S, n_distinct)
+    work = algorithmic_work(layer, lens, S, n_distinct, 4.25 if args.mxfp4 else 16.0)
     classes = {
         "gemm_bf16": (B.K_GEMM, "mfma", work["gemm_flops"], PEAK_BF16_TFLOPS),
         "attn_prefill": (B.K_ATTN_PREFILL, "mfma", work["attn_prefill_flops"], PEAK_BF16_TFLOPS),
@@ -345,7 +360,8 @@ def main():
                                                         "%d..%d" % (min(lens), max(lens)), S, layer.d_model,
                                                         layer.n_q_heads, layer.n_kv_heads, layer.head_dim, layer.ffn_dim,
                                                         "" if layer.n_experts == 0 else
-                                                        " x %d experts top-%d" % (layer.n_experts, layer.top_k)),
+                                                        " x %d experts top-%d%s" % (layer.n_experts, layer.top_k,
+                                                                                    ", 4-bit block-scaled experts in decode" if args.mxfp4 else "")),
                    "total_prefill_tokens": T, "decode_tokens": N * S},
         "prefill_tokens_per_s": T / t_prefill, "decode_tokens_per_s": N * S / t_decode,
         "ms_prefill": t_prefill * 1e3, "ms_decode": t_decode * 1e3, "us_per_decode_step": t_decode * 1e6 / max(S, 1),

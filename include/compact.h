@@ -86,6 +86,18 @@ typedef struct compact_weights {
     const void* w_router;       /* MoE: [E, d]                           */
     const void* w_exp_gate_up;  /* MoE: [E, 2F, d]                       */
     const void* w_exp_down;     /* MoE: [E, d, F]                        */
+    /* Optional block-scaled 4-bit copy of the expert weights (the "mxfp4 weights" the
+     * paper's largest model is served with, Sec. IV-B; OCP Microscaling Formats v1.0):
+     * FP4 E2M1 elements, two per byte with the even-indexed element in the low nibble
+     * (*_q: uint8 [E, rows, K/2]), and one E8M0 scale 2^(e-127) per 32 consecutive
+     * elements along K (*_s: uint8 [E, rows, K/32]; e in 8..246, 255 = NaN is not
+     * supported).  All four or none.  When given, decode steps with at most 16 rows
+     * stream these instead of the 16-bit copy, which must then hold exactly their
+     * expanded values (compact_mxfp4_dequant writes them); bf16 storage only.      */
+    const void* w_exp_gate_up_q;
+    const void* w_exp_gate_up_s;
+    const void* w_exp_down_q;
+    const void* w_exp_down_s;
 } compact_weights;
 
 /* Per-block KV caches.  Block b owns one K slab and one V slab, both starting
@@ -272,6 +284,10 @@ int compact_attn_decode_prefix(compact_ctx* ctx, int32_t n_workers, const void* 
                                const compact_kv* shared, const int32_t* h_prefix_len,
                                const compact_kv* tails, void* d_o, void* d_workspace, size_t ws_bytes,
                                void* hip_stream);
+/* Expands block-scaled 4-bit weights (layout: see compact_weights) to bf16
+ * d_out [rows, K]; exact.  K % 32 == 0.                                      */
+int compact_mxfp4_dequant(compact_ctx* ctx, const void* d_codes, const void* d_scales, int64_t rows,
+                          int32_t K, void* d_out, void* hip_stream);
 /* Router: logits in fp32, top-k ids (descending, ties to the lower id) and
  * softmax gate over the selected logits, for rows of m [rows, d].           */
 int compact_moe_route(compact_ctx* ctx, const void* d_m, const void* d_w_router, int64_t rows,

@@ -25,7 +25,7 @@ EXPORTS = [
     "compact_rmsnorm", "compact_rope_kvwrite", "compact_gemm", "compact_attn_prefill",
     "compact_attn_decode", "compact_moe_route", "compact_moe_ffn",
     "compact_prefix_workspace_bytes", "compact_prefix_decode_step", "compact_attn_decode_prefix",
-    "compact_stack_workspace_bytes", "compact_stack_forward", "compact_prefill_extend",
+    "compact_stack_workspace_bytes", "compact_stack_forward", "compact_prefill_extend", "compact_mxfp4_dequant",
 ]
 
 
@@ -38,7 +38,8 @@ class LayerCfg(C.Structure):
 
 class Weights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("g_attn", "w_qkv", "w_o", "g_ffn", "w_gate_up", "w_down",
-                                          "w_router", "w_exp_gate_up", "w_exp_down")]
+                                          "w_router", "w_exp_gate_up", "w_exp_down",
+                                          "w_exp_gate_up_q", "w_exp_gate_up_s", "w_exp_down_q", "w_exp_down_s")]
 
 
 class KV(C.Structure):
@@ -94,6 +95,7 @@ def lib():
     L.compact_prefix_workspace_bytes.argtypes = [vp, i32, i32, i32, P(sz)]
     L.compact_prefix_decode_step.argtypes = [vp, P(Weights), i32, vp, P(KV), P(i32), P(KV), vp, P(RouteOut), vp, sz, vp]
     L.compact_attn_decode_prefix.argtypes = [vp, i32, vp, P(KV), P(i32), P(KV), vp, vp, sz, vp]
+    L.compact_mxfp4_dequant.argtypes = [vp, vp, vp, i64, i32, vp, vp]
     L.compact_stack_workspace_bytes.argtypes = [vp, i64, i32, i32, P(sz)]
     L.compact_stack_forward.argtypes = [vp, i32, P(Weights), i32, P(i32), vp, i32, vp, P(KV), vp, vp, vp, sz, vp]
     for name in EXPORTS:
@@ -290,6 +292,12 @@ class Layer:
         return n.value, ms.value
 
     # -- per-kernel entry points --------------------------------------------------
+    def compact_mxfp4_dequant(self, codes, scales, out):
+        """codes uint8 [..., K/2], scales uint8 [..., K/32] -> out bf16 [..., K]."""
+        K = codes.shape[-1] * 2
+        self.check(self.L.compact_mxfp4_dequant(self.ctx, _ptr(codes), _ptr(scales), codes.numel() // (K // 2), K, _ptr(out),
+                                                _stream()))
+
     def compact_rmsnorm(self, x, g, y):
         self.check(self.L.compact_rmsnorm(self.ctx, _ptr(x), _ptr(g), _ptr(y), x.shape[0], _stream()))
 

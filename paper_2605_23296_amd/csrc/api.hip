@@ -339,6 +339,13 @@ static int check_weights(compact_ctx* ctx, const compact_weights* w) {
         if (!w->w_gate_up || !w->w_down) return set_err(ctx, COMPACT_EINVAL, "null dense FFN weights");
     } else {
         if (!w->w_router || !w->w_exp_gate_up || !w->w_exp_down) return set_err(ctx, COMPACT_EINVAL, "null MoE weights");
+        const int nq = (w->w_exp_gate_up_q != nullptr) + (w->w_exp_gate_up_s != nullptr) + (w->w_exp_down_q != nullptr) +
+                       (w->w_exp_down_s != nullptr);
+        if (nq != 0 && nq != 4) return set_err(ctx, COMPACT_EINVAL, "4-bit expert weights: give all four arrays or none");
+        if (nq == 4 && ctx->cfg.dtype != COMPACT_BF16)
+            return set_err(ctx, COMPACT_EUNSUPPORTED, "4-bit expert weights need bf16 storage");
+        if (nq == 4 && (ctx->cfg.d_model % 32 != 0 || ctx->cfg.ffn_dim % 32 != 0))
+            return set_err(ctx, COMPACT_ESHAPE, "4-bit expert weights need d_model % 32 == 0 and ffn_dim % 32 == 0");
     }
     return COMPACT_OK;
 }
@@ -557,8 +564,7 @@ static int decode_impl(compact_ctx* ctx, const compact_weights* w, int n_blocks,
     const int N = n_blocks;
     const int Dq = c.n_q_heads * c.head_dim, Dtot = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
     int ks = 1;
-    // RMSNorm + QKV projection.  bf16 storage and whole 512-wide K slices: the
-    // projection stages bf16(x * g) itself and leaves the row sums of squares, the
+    // RMSNorm + QKV projection.  bf16 storage: the projection stages bf16(x * g) itself and leaves the row sums of squares, the
     // epilogue multiplies by 1 / rms before the rotation.
     if (c.dtype == COMPACT_BF16 && skinny_norm_in_supported(N, Dtot, c.d_model)) {
         ks = skinny_ksplit(N, Dtot, c.d_model);
@@ -633,27 +639,42 @@ static int decode_impl(compact_ctx* ctx, const compact_weights* w, int n_blocks,
         if (pending_norm) TRY(launch_rownorm_apply(ctx, (const bf16*)b.hg, rn, (bf16*)b.m, N, c.d_model, s));
         int32_t* idx = route && route->d_expert_idx ? route->d_expert_idx : b.idx;
         float* gate = route && route->d_gate ? route->d_gate : b.gate;
-        TRY(launch_moe_route(ctx, b.m, w->w_router, N, idx, gate, b.logits, s));
+        TRY(launch_moe_route(ctx, b.m, w->w_router, N, idx, gate, b.logits, s, b.partials));
         if (bf && N <= 16) {
             // few rows per expert: stream every routed expert's weights once (split-K
             // partials in the expert-sorted row order), SwiGLU, down projection, and a
             // combine that applies the gate weights to the fp32 sums
             const int rk = N * c.top_k;
             TRY(launch_moe_plan(ctx, idx, gate, N, moe_mtile(c), b.plan, s));
-            int ks1 = skinny_ksplit(1, 2 * c.ffn_dim, c.d_model);
+            const bool q4 = w->w_exp_gate_up_q != nullptr;   // block-scaled 4-bit copy of the experts
+            // every routed expert has at most N <= 16 rows, i.e. exactly one tile of the plan's tile map:
+            // that map lists the routed experts (then -1), so only min(rk, E) grid slices are launched
+            const int n_listed = std::min(rk, c.n_experts);
+            const int ks1 = q4 ? mxfp4_ksplit(c.d_model) : skinny_ksplit(1, 2 * c.ffn_dim, c.d_model);
             {
                 ProfileScope ps(ctx, COMPACT_K_GEMM_SKINNY, s);
-                TRY(launch_gemm_skinny_grouped(ctx, (const bf16*)b.m, b.plan.sorted_token, (const bf16*)w->w_exp_gate_up,
-                                               (int64_t)2 * c.ffn_dim * c.d_model, b.plan.offsets, c.n_experts, rk, b.partials,
-                                               2 * c.ffn_dim, c.d_model, ks1, s));
+                if (q4)
+                    TRY(launch_gemm_skinny_grouped_mxfp4(ctx, (const bf16*)b.m, b.plan.sorted_token,
+                                                         (const uint8_t*)w->w_exp_gate_up_q, (const uint8_t*)w->w_exp_gate_up_s,
+                                                         b.plan.offsets, c.n_experts, rk, b.partials, 2 * c.ffn_dim, c.d_model,
+                                                         ks1, s, b.plan.tile_expert, n_listed));
+                else
+                    TRY(launch_gemm_skinny_grouped(ctx, (const bf16*)b.m, b.plan.sorted_token, (const bf16*)w->w_exp_gate_up,
+                                                   (int64_t)2 * c.ffn_dim * c.d_model, b.plan.offsets, c.n_experts, rk,
+                                                   b.partials, 2 * c.ffn_dim, c.d_model, ks1, s, b.plan.tile_expert, n_listed));
             }
             TRY(launch_swiglu_reduce(ctx, b.partials, ks1, b.act, rk, c.ffn_dim, s));
-            int ks2 = skinny_ksplit(1, c.d_model, c.ffn_dim);
+            const int ks2 = q4 ? mxfp4_ksplit(c.ffn_dim) : skinny_ksplit(1, c.d_model, c.ffn_dim);
             {
                 ProfileScope ps(ctx, COMPACT_K_GEMM_SKINNY, s);
-                TRY(launch_gemm_skinny_grouped(ctx, (const bf16*)b.act, nullptr, (const bf16*)w->w_exp_down,
-                                               (int64_t)c.d_model * c.ffn_dim, b.plan.offsets, c.n_experts, rk, b.partials,
-                                               c.d_model, c.ffn_dim, ks2, s));
+                if (q4)
+                    TRY(launch_gemm_skinny_grouped_mxfp4(ctx, (const bf16*)b.act, nullptr, (const uint8_t*)w->w_exp_down_q,
+                                                         (const uint8_t*)w->w_exp_down_s, b.plan.offsets, c.n_experts, rk,
+                                                         b.partials, c.d_model, c.ffn_dim, ks2, s, b.plan.tile_expert, n_listed));
+                else
+                    TRY(launch_gemm_skinny_grouped(ctx, (const bf16*)b.act, nullptr, (const bf16*)w->w_exp_down,
+                                                   (int64_t)c.d_model * c.ffn_dim, b.plan.offsets, c.n_experts, rk, b.partials,
+                                                   c.d_model, c.ffn_dim, ks2, s, b.plan.tile_expert, n_listed));
             }
             TRY(launch_moe_combine_partials(ctx, b.partials, ks2, rk, b.h, b.plan.slot_of, b.plan.sorted_gate, N, y, s));
         } else {
@@ -1095,6 +1116,15 @@ extern "C" int compact_attn_decode(compact_ctx* ctx, int32_t n_blocks, const voi
         return set_err(ctx, COMPACT_EWORKSPACE, "workspace too small for the split-KV partials");
     TRY(upload_plan(ctx, plan, s));
     return run_attn_decode(ctx, plan, n_blocks, 0, d_q, kv, (float*)d_workspace, d_o, s);
+}
+
+extern "C" int compact_mxfp4_dequant(compact_ctx* ctx, const void* d_codes, const void* d_scales, int64_t rows, int32_t K,
+                                     void* d_out, void* hip_stream) {
+    if (!ctx) return COMPACT_EINVAL;
+    if (!d_codes || !d_scales || !d_out) return set_err(ctx, COMPACT_EINVAL, "null codes, scales or output");
+    if (rows < 0) return set_err(ctx, COMPACT_EINVAL, "rows must be >= 0");
+    return launch_mxfp4_dequant(ctx, (const uint8_t*)d_codes, (const uint8_t*)d_scales, (bf16*)d_out, rows, K,
+                                (hipStream_t)hip_stream);
 }
 
 extern "C" int compact_moe_route(compact_ctx* ctx, const void* d_m, const void* d_w_router, int64_t rows,

@@ -167,6 +167,15 @@ int launch_gemm_bf16(compact_ctx* ctx, const bf16* A, const bf16* B, const void*
                      int64_t M, int N, int K, int epilogue, const GroupedArgs* grouped, hipStream_t s);
 int gemm_bf16_mtile();
 
+// mxfp4.hip : block-scaled 4-bit expert weights
+int mxfp4_ksplit(int K);
+int launch_mxfp4_dequant(compact_ctx* ctx, const uint8_t* codes, const uint8_t* scales, bf16* out, int64_t rows, int K,
+                         hipStream_t s);
+int launch_gemm_skinny_grouped_mxfp4(compact_ctx* ctx, const bf16* X, const int32_t* a_gather, const uint8_t* Wq,
+                                     const uint8_t* Ws, const int32_t* offsets, int n_experts, int total_rows,
+                                     float* partials, int N, int K, int ks, hipStream_t s,
+                                     const int32_t* expert_list = nullptr, int n_listed = 0);
+
 // gemm_skinny.hip : partials[ks][M][N] (fp32) = A[M,K] B[N,K]^T split over K
 int skinny_ksplit(int M, int N, int K);
 // norm_g (nullable): A holds un-normalised rows x; the operand becomes bf16(x * norm_g) and
@@ -179,7 +188,9 @@ bool skinny_norm_in_supported(int M, int N, int K);
 // given); partials[ks][total_rows][N] keep the sorted order
 int launch_gemm_skinny_grouped(compact_ctx* ctx, const bf16* X, const int32_t* a_gather, const bf16* W, int64_t w_expert_stride,
                                const int32_t* offsets, int n_experts, int total_rows, float* partials, int N, int K, int ks,
-                               hipStream_t s);
+                               hipStream_t s, const int32_t* expert_list = nullptr, int n_listed = 0);
+// expert_list (nullable): the experts to run, one per grid slice, -1 = none (the tile map of the
+// routing plan when no expert has more rows than a tile); spares launching a slice per idle expert
 // decode gate/up projection with the SwiGLU fused in (no partials): act[M, F] =
 // silu(r X Wg^T) * (r X Wu^T); X may hold un-normalised rows (x * g) whose 1/rms r
 // comes from `norm` (null: r = 1)
@@ -240,7 +251,8 @@ struct MoePlan {              // device buffers carved from the workspace
     int32_t max_mtiles;
 };
 int launch_moe_route(compact_ctx* ctx, const void* m, const void* w_router, int64_t rows, int32_t* idx,
-                     float* gate, float* logits, hipStream_t s);
+                     float* gate, float* logits, hipStream_t s,
+                     float* partials_ws = nullptr);   // partials_ws: [ks][rows][E] scratch; enables the few-rows path
 int launch_moe_plan(compact_ctx* ctx, const int32_t* idx, const float* gate, int64_t rows, int mtile,
                     const MoePlan& plan, hipStream_t s);
 // decode: y[t] = h[t] + sum_j gate * (sum over K-slices of partials[slot_of[t*k + j]]), one rounding

@@ -29,6 +29,7 @@ int skinny_ksplit(int M, int N, int K) {
 // weight matrix, and the partials keep the sorted order: P[slice][sorted row][N].
 // Experts nobody was routed to leave at once.
 struct SkinnyGroup {
+    const int32_t* expert_list;  // [gridDim.z] experts to run, -1 = none (null: expert = blockIdx.z)
     const int32_t* offsets;   // [E + 1]
     const int32_t* a_gather;  // [total_rows] or null
     int64_t w_expert_stride;  // elements
@@ -38,7 +39,7 @@ struct SkinnyGroup {
 // Front half of an RMSNorm folded into the activation staging (null g: off): the
 // staged operand is bf16(x * g) and the workgroups of the first column tile leave
 // ssq_parts[slice][row] = sum of x^2 over the slice; the consumer of the partials
-// multiplies by 1 / rms.  Needs whole 512-wide slices (one wavefront stages one row).
+// multiplies by 1 / rms.
 struct SkinnyNormIn {
     const bf16* g = nullptr;
     float* ssq_parts = nullptr;
@@ -55,7 +56,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const bf16* __r
     const int lane = t & 63, wave = t >> 6;
     int row_base = 0, p_rows = M;
     if (GROUPED) {
-        const int e = blockIdx.z;
+        const int e = grp.expert_list ? grp.expert_list[blockIdx.z] : (int)blockIdx.z;
+        if (e < 0) return;
         row_base = grp.offsets[e];
         M = min(grp.offsets[e + 1] - row_base, MT * 16);
         if (M <= 0) return;
@@ -82,31 +84,43 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const bf16* __r
             if (s < nsteps) a[s] = *reinterpret_cast<const bf16x8*>(wp + s * 32);
     }
 
-    const int cpr = klen / 8;  // 16-byte chunks per row
-    for (int q = t; q < MT * 16 * cpr; q += WAVES * 64) {
-        const int row = q / cpr, cc = q - row * cpr;
-        bf16x8 v;
+    const int cpr = klen / 8;  // 16-byte chunks per row (at most 64)
+    if (!GROUPED && nin.g) {
+        // RMSNorm front half: a wavefront stages whole rows, so that the row's sum of
+        // squares over this slice is one butterfly (fixed order)
+        for (int row = wave; row < MT * 16; row += WAVES) {
+            bf16x8 v;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = (bf16)0.f;
-        if (row < M) {
-            size_t src = row_base + row;
-            if (GROUPED && grp.a_gather) src = grp.a_gather[src];
-            v = *reinterpret_cast<const bf16x8*>(X + src * K + k0 + cc * 8);
-        }
-        if (!GROUPED && nin.g) {   // cpr == 64: this wavefront holds the whole slice of one row
-            const bf16x8 gv = *reinterpret_cast<const bf16x8*>(nin.g + k0 + cc * 8);
+            for (int j = 0; j < 8; ++j) v[j] = (bf16)0.f;
             float ss = 0.f;
+            if (row < M && lane < cpr) {
+                v = *reinterpret_cast<const bf16x8*>(X + (size_t)row * K + k0 + lane * 8);
+                const bf16x8 gv = *reinterpret_cast<const bf16x8*>(nin.g + k0 + lane * 8);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const float f = (float)v[j];
-                ss += f * f;
-                v[j] = (bf16)(f * (float)gv[j]);
+                for (int j = 0; j < 8; ++j) {
+                    const float f = (float)v[j];
+                    ss += f * f;
+                    v[j] = (bf16)(f * (float)gv[j]);
+                }
             }
 #pragma unroll
             for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
             if (lane == 0 && blockIdx.y == 0 && row < M) nin.ssq_parts[(size_t)slice * M + row] = ss;
+            if (lane < cpr) *reinterpret_cast<bf16x8*>(xs + row * LDX + lane * 8) = v;
         }
-        *reinterpret_cast<bf16x8*>(xs + row * LDX + cc * 8) = v;
+    } else {
+        for (int q = t; q < MT * 16 * cpr; q += WAVES * 64) {
+            const int row = q / cpr, cc = q - row * cpr;
+            bf16x8 v;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = (bf16)0.f;
+            if (row < M) {
+                size_t src = row_base + row;
+                if (GROUPED && grp.a_gather) src = grp.a_gather[src];
+                v = *reinterpret_cast<const bf16x8*>(X + src * K + k0 + cc * 8);
+            }
+            *reinterpret_cast<bf16x8*>(xs + row * LDX + cc * 8) = v;
+        }
     }
     __syncthreads();
     if (!active) return;
@@ -293,7 +307,7 @@ static int launch_skinny_cfg(compact_ctx* ctx, const bf16* A, const bf16* B, flo
 // more rows the staged activation slice grows, so 8 wavefronts (128 weight rows)
 // share it: half the activation traffic per weight byte, the same number of
 // wavefronts per compute unit.
-bool skinny_norm_in_supported(int M, int N, int K) { return M >= 1 && M <= 64 && N % 16 == 0 && K % SKINNY_KSLICE == 0; }
+bool skinny_norm_in_supported(int M, int N, int K) { return M >= 1 && M <= 64 && N % 16 == 0 && K % 64 == 0; }
 
 int launch_gemm_skinny(compact_ctx* ctx, const bf16* A, const bf16* B, float* partials, int M, int N, int K, int ks,
                        hipStream_t s, const bf16* norm_g, float* norm_ssq_parts) {
@@ -303,7 +317,7 @@ int launch_gemm_skinny(compact_ctx* ctx, const bf16* A, const bf16* B, float* pa
     SkinnyNormIn nin;
     if (norm_g) {
         if (!skinny_norm_in_supported(M, N, K) || !norm_ssq_parts)
-            return set_err(ctx, COMPACT_ESHAPE, "folding the RMSNorm into the weight-streaming GEMM needs K % 512 == 0");
+            return set_err(ctx, COMPACT_ESHAPE, "folding the RMSNorm into the weight-streaming GEMM needs K % 64 == 0");
         nin.g = norm_g;
         nin.ssq_parts = norm_ssq_parts;
     }
@@ -319,11 +333,11 @@ int launch_gemm_skinny(compact_ctx* ctx, const bf16* A, const bf16* B, float* pa
 // partials[ks][total_rows][N], rows in expert-sorted order.
 int launch_gemm_skinny_grouped(compact_ctx* ctx, const bf16* X, const int32_t* a_gather, const bf16* W, int64_t w_expert_stride,
                                const int32_t* offsets, int n_experts, int total_rows, float* partials, int N, int K, int ks,
-                               hipStream_t s) {
+                               hipStream_t s, const int32_t* expert_list, int n_listed) {
     if (N % 16 != 0 || K % 64 != 0) return set_err(ctx, COMPACT_ESHAPE, "weight-streaming GEMM needs N % 16 == 0 and K % 64 == 0");
     if (ks != skinny_ksplit(1, N, K)) return set_err(ctx, COMPACT_EINVAL, "unexpected K split");
-    SkinnyGroup g{offsets, a_gather, w_expert_stride, total_rows};
-    dim3 grid(ks, (N + 63) / 64, n_experts);
+    SkinnyGroup g{expert_list, offsets, a_gather, w_expert_stride, total_rows};
+    dim3 grid(ks, (N + 63) / 64, expert_list ? n_listed : n_experts);
     const size_t smem = (size_t)16 * (SKINNY_KSLICE + 8) * sizeof(bf16);
     gemm_skinny_kernel<1, true, 4><<<grid, 256, smem, s>>>(X, W, partials, 0, N, K, g, SkinnyNormIn{});
     LAUNCH_CHECK(ctx);

@@ -9,8 +9,11 @@
 // gate = softmax over the selected logits.  One wavefront per row; lane l owns
 // experts l, l+64, l+128, l+192.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void topk_route_kernel(const float* __restrict__ logits, int64_t rows, int E, int k,
-                                                         int32_t* __restrict__ idx, float* __restrict__ gate) {
+// ks > 0: the logits arrive as ks split-K partials [ks][rows][E]; they are summed in
+// slice order here and the sums are written to `logits`.
+__global__ __launch_bounds__(256) void topk_route_kernel(float* __restrict__ logits, const float* __restrict__ partials, int ks,
+                                                         int64_t rows, int E, int k, int32_t* __restrict__ idx,
+                                                         float* __restrict__ gate) {
     const int64_t row = (int64_t)blockIdx.x * 4 + threadIdx.x / WAVE;
     if (row >= rows) return;
     const int lane = threadIdx.x & (WAVE - 1);
@@ -18,7 +21,17 @@ __global__ __launch_bounds__(256) void topk_route_kernel(const float* __restrict
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int e = lane + i * 64;
-        v[i] = e < E ? logits[row * E + e] : -INFINITY;
+        v[i] = -INFINITY;
+        if (e < E) {
+            if (ks > 0) {
+                float a = 0.f;
+                for (int sl = 0; sl < ks; ++sl) a += partials[((size_t)sl * rows + row) * E + e];
+                logits[row * E + e] = a;
+                v[i] = a;
+            } else {
+                v[i] = logits[row * E + e];
+            }
+        }
     }
     float sel_v[8];
     int sel_i[8];
@@ -61,10 +74,19 @@ __global__ __launch_bounds__(256) void topk_route_kernel(const float* __restrict
 }
 
 int launch_moe_route(compact_ctx* ctx, const void* m, const void* w_router, int64_t rows, int32_t* idx, float* gate,
-                     float* logits, hipStream_t s) {
+                     float* logits, hipStream_t s, float* partials_ws) {
     if (rows == 0) return COMPACT_OK;
     const compact_layer_cfg& c = ctx->cfg;
     int rc;
+    if (c.dtype == COMPACT_BF16 && partials_ws && rows <= 64 && c.n_experts % 16 == 0 && c.d_model % 64 == 0) {
+        // a few decode rows: the router matrix is streamed once by the weight-streaming kernel
+        const int ks = skinny_ksplit((int)rows, c.n_experts, c.d_model);
+        rc = launch_gemm_skinny(ctx, (const bf16*)m, (const bf16*)w_router, partials_ws, (int)rows, c.n_experts, c.d_model, ks, s);
+        if (rc != COMPACT_OK) return rc;
+        topk_route_kernel<<<(unsigned)((rows + 3) / 4), 256, 0, s>>>(logits, partials_ws, ks, rows, c.n_experts, c.top_k, idx, gate);
+        LAUNCH_CHECK(ctx);
+        return COMPACT_OK;
+    }
     if (c.dtype == COMPACT_BF16)
         rc = launch_gemm_bf16(ctx, (const bf16*)m, (const bf16*)w_router, nullptr, false, (bf16*)logits, rows,
                               c.n_experts, c.d_model, 2, nullptr, s);
@@ -72,7 +94,7 @@ int launch_moe_route(compact_ctx* ctx, const void* m, const void* w_router, int6
         rc = launch_gemm_f32(ctx, (const float*)m, (const float*)w_router, nullptr, logits, rows, c.n_experts,
                              c.d_model, 0, nullptr, s);
     if (rc != COMPACT_OK) return rc;
-    topk_route_kernel<<<(unsigned)((rows + 3) / 4), 256, 0, s>>>(logits, rows, c.n_experts, c.top_k, idx, gate);
+    topk_route_kernel<<<(unsigned)((rows + 3) / 4), 256, 0, s>>>(logits, nullptr, 0, rows, c.n_experts, c.top_k, idx, gate);
     LAUNCH_CHECK(ctx);
     return COMPACT_OK;
 }
@@ -162,11 +184,77 @@ __global__ __launch_bounds__(256) void expert_scatter_kernel(const int32_t* __re
     slot_of[i] = pos;
 }
 
+// The whole plan in one workgroup, for at most 256 routed entries (a decode step) and
+// at most 256 experts: rank = number of earlier entries with the same expert (so the
+// order inside an expert's group is the token order), counts, scan, tile map, scatter.
+__global__ __launch_bounds__(256) void moe_plan_small_kernel(const int32_t* __restrict__ idx, const float* __restrict__ gate,
+                                                             int n, int k, int E, int mtile, int32_t* __restrict__ counts,
+                                                             int32_t* __restrict__ offsets, int32_t* __restrict__ tile_expert,
+                                                             int32_t* __restrict__ tile_row0, int32_t* __restrict__ tile_rows,
+                                                             int max_mtiles, int32_t* __restrict__ sorted_token,
+                                                             float* __restrict__ sorted_gate, int32_t* __restrict__ slot_of) {
+    __shared__ int32_t se[256], off[257], toff[257];
+    const int t = threadIdx.x;
+    const int my = t < n ? idx[t] : -1;
+    se[t] = my;
+    __syncthreads();
+    int rank = 0;
+    for (int j = 0; j < t; ++j) rank += (se[j] == my) ? 1 : 0;
+    int cnt = 0;
+    if (t < E) {
+        for (int j = 0; j < n; ++j) cnt += (se[j] == t) ? 1 : 0;
+        counts[t] = cnt;
+    }
+    __syncthreads();
+    // exclusive scans of the counts and of the tiles per expert over the 256 threads
+    // (thread e = expert e; Hillis-Steele in LDS, integer sums: any order gives the same result)
+    const int tiles = (cnt + mtile - 1) / mtile;
+    off[t + 1] = cnt;
+    toff[t + 1] = tiles;
+    if (t == 0) off[0] = toff[0] = 0;
+    __syncthreads();
+    for (int st = 1; st < 256; st <<= 1) {
+        const int a = t + 1 > st ? off[t + 1 - st] : 0;
+        const int b = t + 1 > st ? toff[t + 1 - st] : 0;
+        __syncthreads();
+        off[t + 1] += a;
+        toff[t + 1] += b;
+        __syncthreads();
+    }
+    for (int e = t; e <= E; e += 256) offsets[e] = off[e];
+    if (t < E) {
+        for (int i = 0; toff[t] + i < toff[t + 1]; ++i) {
+            const int ti = toff[t] + i;
+            tile_expert[ti] = t;
+            tile_row0[ti] = off[t] + i * mtile;
+            tile_rows[ti] = min(mtile, cnt - i * mtile);
+        }
+    }
+    for (int ti = toff[E] + t; ti < max_mtiles; ti += 256) {
+        tile_expert[ti] = -1;
+        tile_row0[ti] = 0;
+        tile_rows[ti] = 0;
+    }
+    if (my >= 0) {
+        const int pos = off[my] + rank;
+        sorted_token[pos] = t / k;
+        sorted_gate[pos] = gate[t];
+        slot_of[t] = pos;
+    }
+}
+
 int launch_moe_plan(compact_ctx* ctx, const int32_t* idx, const float* gate, int64_t rows, int mtile,
                     const MoePlan& plan, hipStream_t s) {
     const compact_layer_cfg& c = ctx->cfg;
     const int64_t n = rows * c.top_k;
     if (n == 0) return COMPACT_OK;
+    if (n <= 256 && c.n_experts <= 256) {
+        moe_plan_small_kernel<<<1, 256, 0, s>>>(idx, gate, (int)n, c.top_k, c.n_experts, mtile, plan.counts, plan.offsets,
+                                                plan.tile_expert, plan.tile_row0, plan.tile_rows, plan.max_mtiles,
+                                                plan.sorted_token, plan.sorted_gate, plan.slot_of);
+        LAUNCH_CHECK(ctx);
+        return COMPACT_OK;
+    }
     zero_i32_kernel<<<1, 256, 0, s>>>(plan.counts, c.n_experts);
     // slot_of doubles as the rank buffer until the scatter overwrites it entry by entry
     expert_rank_kernel<<<(unsigned)((n + 1023) / 1024), 256, 0, s>>>(idx, n, c.n_experts, plan.counts, plan.slot_of);

@@ -1,0 +1,132 @@
+"""Block-scaled 4-bit expert weights on the GPU (paper Sec. IV-B "mxfp4 weights";
+OCP Microscaling Formats v1.0): the expansion to bf16 is checked bit for bit against
+the checker's field-by-field definition, routed decode steps that stream the 4-bit
+arrays against the fp64 layer whose expert weights are that definition's values."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import layer as O
+from oracle import mxfp4 as Q
+from paper_2605_23296_amd import binding as B
+from paper_2605_23296_amd.workloads import (WORKLOADS, LayerConfig, Workload, make_inputs, make_mxfp4_experts,
+                                            to_numpy_f64)
+from tests import harness as H
+from tests.util import rel_err, vec_rel_err
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+TOL, ELEM_TOL = 2e-2, 5e-2
+
+
+def test_expansion_is_bit_exact_for_every_code_and_a_range_of_scales():
+    lay = B.Layer(WORKLOADS["moe_16x8192"].layer, None)
+    g = torch.Generator().manual_seed(5)
+    rows, K = 37, 320
+    codes = torch.randint(0, 256, (rows, K // 2), generator=g, dtype=torch.uint8)
+    codes[0, :128] = torch.arange(256, dtype=torch.int32)[:128].to(torch.uint8)        # every byte value once ...
+    codes[1, :128] = (torch.arange(256, dtype=torch.int32)[128:]).to(torch.uint8)      # ... over two rows
+    scales = torch.randint(100, 140, (rows, K // 32), generator=g, dtype=torch.uint8)
+    scales[2] = torch.tensor([8, 60, 119, 120, 126, 127, 128, 130, 200, 246], dtype=torch.uint8)
+    out = torch.empty(rows, K, dtype=torch.bfloat16, device=DEV)
+    lay.compact_mxfp4_dequant(codes.to(DEV), scales.to(DEV), out)
+    torch.cuda.synchronize()
+    ref = Q.dequantize(codes.numpy(), scales.numpy())
+    got = to_numpy_f64(out)
+    assert np.array_equal(got, ref)
+    assert np.array_equal(np.signbit(got), np.signbit(ref))      # -0.0 stays -0.0
+
+
+def build(layer, block_lens, steps, seed=0):
+    wl = Workload("q4", layer, block_lens, len(block_lens), steps, seed=seed)
+    inp = make_inputs(wl)
+    gen = torch.Generator().manual_seed(seed + 77)
+    q4 = make_mxfp4_experts(layer, gen)
+    return inp, q4
+
+
+def oracle_weights(inp, q4):
+    w = {k: to_numpy_f64(v) for k, v in inp.weights.items() if not k.startswith("w_exp_")}
+    w["w_exp_gate_up"] = Q.dequantize(q4["w_exp_gate_up_q"].numpy(), q4["w_exp_gate_up_s"].numpy())
+    w["w_exp_down"] = Q.dequantize(q4["w_exp_down_q"].numpy(), q4["w_exp_down_s"].numpy())
+    return w
+
+
+def device_weights(lay0, inp, q4):
+    """The library's inputs: the 4-bit arrays plus the bf16 copy its own expansion writes."""
+    w = {k: v.to(DEV).contiguous() for k, v in inp.weights.items() if not k.startswith("w_exp_")}
+    for k, v in q4.items():
+        w[k] = v.to(DEV).contiguous()
+    for name in ("w_exp_gate_up", "w_exp_down"):
+        c, s = w[name + "_q"], w[name + "_s"]
+        out = torch.empty(c.shape[:-1] + (c.shape[-1] * 2,), dtype=torch.bfloat16, device=DEV)
+        lay0.compact_mxfp4_dequant(c, s, out)
+        w[name] = out
+    return w
+
+
+@pytest.mark.parametrize("d,F", [(256, 320), (1216, 1088)])
+def test_routed_decode_steps_streaming_4bit_experts(d, F):
+    """d = 256: one k-slice of two MFMA groups; d = 1216 / F = 1088: a full 1024-wide slice plus a
+    slice of 6 (2) blocks, i.e. a partial group of four.  Empty experts, experts with several rows."""
+    layer = LayerConfig(d_model=d, n_q_heads=8, n_kv_heads=2, head_dim=64, ffn_dim=F, n_experts=16, top_k=4,
+                        rope_theta=500000.0)
+    inp, q4 = build(layer, [70, 33, 129, 5, 64], 3)
+    lay0 = B.Layer(layer, None)
+    w = device_weights(lay0, inp, q4)
+    lay = B.Layer(layer, w)
+    N, S, cu = 5, 3, inp.cu_seqlens
+    dt = torch.bfloat16
+    kv = B.KVCache(layer, [L + S for L in inp.block_lens], DEV, dt)
+    lay.ensure_workspace(cu[-1], N, max(inp.block_lens) + S, DEV)
+    y_pre = torch.empty(cu[-1], d, dtype=dt, device=DEV)
+    lay.compact_prefill(cu, inp.x_prefill.to(DEV), kv, y_pre)
+    xd = inp.x_decode.to(DEV).contiguous()
+    y_dec = torch.empty(S, N, d, dtype=dt, device=DEV)
+    idx = torch.empty(S, N, 4, dtype=torch.int32, device=DEV)
+    gate = torch.empty(S, N, 4, dtype=torch.float32, device=DEV)
+    for s in range(S):
+        lay.compact_decode_step(xd[s], kv, y_dec[s], (idx[s], gate[s]))
+    torch.cuda.synchronize()
+
+    ref = O.Layer(layer.as_dict(), oracle_weights(inp, q4))
+    pre, yd, Ks, Vs, routes = ref.forward(to_numpy_f64(inp.x_prefill), cu, to_numpy_f64(inp.x_decode))
+    n_cmp = 0
+    for s in range(S):
+        for b in range(N):
+            ri, rg, rl = routes[s][b]
+            ok, _ = H.routed_rows_match(idx[s, b:b + 1].cpu().numpy(), ri[None], rl[None], 4, 8e-3)
+            if ok.all() and np.array_equal(np.sort(idx[s, b].cpu().numpy()), np.sort(ri)):
+                e = vec_rel_err(to_numpy_f64(y_dec[s, b]), yd[s, b])
+                assert e < TOL, (s, b, e)
+                assert rel_err(to_numpy_f64(y_dec[s, b]), yd[s, b]) < ELEM_TOL
+                n_cmp += 1
+    assert n_cmp >= S * N - 3
+
+
+def test_4bit_and_16bit_paths_agree_on_the_same_values():
+    """The 4-bit streaming kernels and the 16-bit ones read the same numbers (the bf16 copy is
+    the exact expansion), so a decode step must agree far inside the bf16 tolerance."""
+    layer = LayerConfig(d_model=1216, n_q_heads=8, n_kv_heads=2, head_dim=64, ffn_dim=1088, n_experts=16, top_k=4,
+                        rope_theta=500000.0)
+    inp, q4 = build(layer, [40, 17, 9], 2, seed=3)
+    lay0 = B.Layer(layer, None)
+    w = device_weights(lay0, inp, q4)
+    w16 = {k: v for k, v in w.items() if not k.endswith(("_q", "_s"))}
+    outs = []
+    for ww in (w, w16):
+        lay = B.Layer(layer, ww)
+        kv = B.KVCache(layer, [L + 2 for L in inp.block_lens], DEV, torch.bfloat16)
+        lay.ensure_workspace(inp.cu_seqlens[-1], 3, 64, DEV)
+        y_pre = torch.empty(inp.cu_seqlens[-1], 1216, dtype=torch.bfloat16, device=DEV)
+        lay.compact_prefill(inp.cu_seqlens, inp.x_prefill.to(DEV), kv, y_pre)
+        y = torch.empty(2, 3, 1216, dtype=torch.bfloat16, device=DEV)
+        idx = torch.empty(2, 3, 4, dtype=torch.int32, device=DEV)
+        gate = torch.empty(2, 3, 4, dtype=torch.float32, device=DEV)
+        for s in range(2):
+            lay.compact_decode_step(inp.x_decode[s].to(DEV).contiguous(), kv, y[s], (idx[s], gate[s]))
+        torch.cuda.synchronize()
+        outs.append((y.float().cpu(), idx.cpu()))
+    assert torch.equal(outs[0][1], outs[1][1])                 # routing does not depend on the expert format
+    d = (outs[0][0] - outs[1][0]).norm(dim=-1) / outs[1][0].norm(dim=-1)
+    assert d.max().item() < 4e-3, d.max().item()               # only the split of K differs (1024- vs 512-wide slices)
