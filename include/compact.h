@@ -215,6 +215,29 @@ int compact_prefix_decode_step(compact_ctx* ctx, const compact_weights* w, int32
                                compact_kv* tails, void* d_y, const compact_route_out* route,
                                void* d_workspace, size_t ws_bytes, void* hip_stream);
 
+/* The same pass as compact_layer_forward, scheduled the way the paper's server
+ * runs it (Sec. IV-B: chunked prefill): no step handles more than
+ * max_batched_tokens rows.  Each step takes one decode token of every block
+ * whose prefill is complete and that still has steps left, and fills the rest
+ * of the budget with the next prefill chunks of the other blocks, in block
+ * order; chunks and decode tokens share one packed batch through the
+ * projections (each weight is read once for both), chunk rows go through the
+ * prefill attention against their block's cached rows, decode rows through the
+ * split-KV decode attention.  Once every prefill is complete the remaining
+ * decode steps run batched over the blocks that still have steps left.  Blocks
+ * therefore advance at different rates; block b's step s still reads
+ * d_x_decode[s, b] and writes d_y_decode[s, b], and the outputs equal those of
+ * compact_layer_forward up to rounding.  Activation workspace is sized by
+ * max_batched_tokens, not by the total prefill length.  d_y_last [N, d] is
+ * nullable.  max_batched_tokens must exceed n_blocks.  The workspace must hold
+ * compact_mixed_workspace_bytes(ctx, max_batched_tokens, n_blocks, max L_b + n_steps). */
+int compact_mixed_workspace_bytes(const compact_ctx* ctx, int32_t max_batched_tokens, int32_t max_blocks,
+                                  int32_t max_kv_len, size_t* bytes);
+int compact_mixed_forward(compact_ctx* ctx, const compact_weights* w, int32_t n_blocks,
+                          const int32_t* h_cu_seqlens, const void* d_x_prefill, int32_t n_steps,
+                          const void* d_x_decode, compact_kv* kv, int32_t max_batched_tokens, void* d_y_last,
+                          void* d_y_decode, void* d_workspace, size_t ws_bytes, void* hip_stream);
+
 /* A depth of layers (the models of paper Sec. IV-A are 32- to 80-layer stacks
  * of the layer above; embedding and output head excluded): layer l's output
  * rows are layer l+1's input rows, in the prefill of all blocks and in each of

@@ -26,6 +26,7 @@ EXPORTS = [
     "compact_attn_decode", "compact_moe_route", "compact_moe_ffn",
     "compact_prefix_workspace_bytes", "compact_prefix_decode_step", "compact_attn_decode_prefix",
     "compact_stack_workspace_bytes", "compact_stack_forward", "compact_prefill_extend", "compact_mxfp4_dequant",
+    "compact_mixed_workspace_bytes", "compact_mixed_forward",
 ]
 
 
@@ -95,6 +96,8 @@ def lib():
     L.compact_prefix_workspace_bytes.argtypes = [vp, i32, i32, i32, P(sz)]
     L.compact_prefix_decode_step.argtypes = [vp, P(Weights), i32, vp, P(KV), P(i32), P(KV), vp, P(RouteOut), vp, sz, vp]
     L.compact_attn_decode_prefix.argtypes = [vp, i32, vp, P(KV), P(i32), P(KV), vp, vp, sz, vp]
+    L.compact_mixed_workspace_bytes.argtypes = [vp, i32, i32, i32, P(sz)]
+    L.compact_mixed_forward.argtypes = [vp, P(Weights), i32, P(i32), vp, i32, vp, P(KV), i32, vp, vp, vp, sz, vp]
     L.compact_mxfp4_dequant.argtypes = [vp, vp, vp, i64, i32, vp, vp]
     L.compact_stack_workspace_bytes.argtypes = [vp, i64, i32, i32, P(sz)]
     L.compact_stack_forward.argtypes = [vp, i32, P(Weights), i32, P(i32), vp, i32, vp, P(KV), vp, vp, vp, sz, vp]
@@ -240,6 +243,19 @@ class Layer:
         self.check(self.L.compact_layer_forward(
             self.ctx, C.byref(self.w), len(cu_seqlens) - 1, _i32arr(cu_seqlens), _ptr(x_prefill), S,
             _ptr(x_decode), C.byref(kv.c), _ptr(y_prefill), _ptr(y_last), _ptr(y_decode), wsp, wsn, _stream()))
+
+    # -- mixed batches (chunked prefill interleaved with decode) --------------------
+    def mixed_workspace_bytes(self, max_batched_tokens, max_blocks, max_kv_len):
+        n = C.c_size_t()
+        self.check(self.L.compact_mixed_workspace_bytes(self.ctx, max_batched_tokens, max_blocks, max_kv_len, C.byref(n)))
+        return n.value
+
+    def compact_mixed_forward(self, cu_seqlens, x_prefill, x_decode, kv, max_batched_tokens, y_last, y_decode):
+        wsp, wsn = self._ws()
+        S = 0 if x_decode is None else x_decode.shape[0]
+        self.check(self.L.compact_mixed_forward(
+            self.ctx, C.byref(self.w), len(cu_seqlens) - 1, _i32arr(cu_seqlens), _ptr(x_prefill), S, _ptr(x_decode),
+            C.byref(kv.c), max_batched_tokens, _ptr(y_last), _ptr(y_decode), wsp, wsn, _stream()))
 
     # -- a depth of layers --------------------------------------------------------
     def stack_workspace_bytes(self, max_tokens, max_blocks, max_kv_len):

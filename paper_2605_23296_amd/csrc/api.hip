@@ -761,6 +761,233 @@ extern "C" int compact_layer_forward(compact_ctx* ctx, const compact_weights* w,
 }
 
 // ---------------------------------------------------------------------------
+// mixed batches: prefill chunks of some blocks together with decode tokens of others
+// ---------------------------------------------------------------------------
+extern "C" int compact_mixed_workspace_bytes(const compact_ctx* ctx, int32_t max_batched_tokens, int32_t max_blocks,
+                                             int32_t max_kv_len, size_t* bytes) {
+    size_t one = 0;
+    const int rc = compact_workspace_bytes(ctx, max_batched_tokens, max_blocks, max_kv_len, &one);
+    if (rc != COMPACT_OK) return rc;
+    const size_t es = dtype_size(ctx->cfg.dtype);
+    // packed input and output rows of a mixed step, and of a decode-only step
+    *bytes = one + 2 * align_up((size_t)max_batched_tokens * ctx->cfg.d_model * es, 256) +
+             2 * align_up((size_t)max_blocks * ctx->cfg.d_model * es, 256) + 256;
+    return COMPACT_OK;
+}
+
+namespace {
+struct MixExtra {   // byte offsets inside Plan::extra of one mixed step
+    size_t dec_meta = 0, qrow = 0, src_tab = 0, dst_tab = 0;
+};
+template <typename T>
+size_t put(std::vector<char>& buf, const std::vector<T>& v) {
+    const size_t off = align_up(buf.size(), 256);
+    buf.resize(off + v.size() * sizeof(T));
+    if (!v.empty()) memcpy(buf.data() + off, v.data(), v.size() * sizeof(T));
+    return off;
+}
+}  // namespace
+
+extern "C" int compact_mixed_forward(compact_ctx* ctx, const compact_weights* w, int32_t n_blocks,
+                                     const int32_t* h_cu_seqlens, const void* d_x_prefill, int32_t n_steps,
+                                     const void* d_x_decode, compact_kv* kv, int32_t max_batched_tokens, void* d_y_last,
+                                     void* d_y_decode, void* d_workspace, size_t ws_bytes, void* hip_stream) {
+    if (!ctx) return COMPACT_EINVAL;
+    if (n_steps < 0) return set_err(ctx, COMPACT_EINVAL, "n_steps must be >= 0");
+    TRY(validate_prefill(ctx, w, n_blocks, h_cu_seqlens, d_x_prefill, kv, d_workspace, n_steps));
+    if (n_steps > 0 && (!d_x_decode || !d_y_decode)) return set_err(ctx, COMPACT_EINVAL, "null decode input or output");
+    if (max_batched_tokens <= n_blocks)
+        return set_err(ctx, COMPACT_EINVAL, "max_batched_tokens must exceed n_blocks (every decoding block takes one row)");
+    const compact_layer_cfg& c = ctx->cfg;
+    hipStream_t s = (hipStream_t)hip_stream;
+    const int N = n_blocks, S = n_steps, TM = max_batched_tokens;
+    const size_t es = dtype_size(c.dtype);
+    const bool bf = c.dtype == COMPACT_BF16;
+    const int Dq = c.n_q_heads * c.head_dim, Dtot = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
+    int max_len = 0;
+    for (int b = 0; b < N; ++b) max_len = std::max(max_len, h_cu_seqlens[b + 1] - h_cu_seqlens[b]);
+
+    // workspace: [prefill region for TM rows][decode region for N blocks][xp, yp: TM rows][xs, ys: N rows]
+    Carver cp(d_workspace);
+    PrefillBufs pb;
+    carve_prefill(cp, c, TM, pb);
+    const size_t off = align_up(cp.off, 256);
+    Carver cd((char*)d_workspace + off);
+    DecodeBufs db;
+    const int max_chunks = chunks_for(max_len + S);
+    carve_decode(cd, c, N, max_chunks, db);
+    size_t end = off + align_up(cd.off, 256);
+    char* base = (char*)d_workspace;
+    void* xp = base + end;
+    end += align_up((size_t)TM * c.d_model * es, 256);
+    void* yp = base + end;
+    end += align_up((size_t)TM * c.d_model * es, 256);
+    void* xs = base + end;
+    end += align_up((size_t)N * c.d_model * es, 256);
+    void* ys = base + end;
+    end += align_up((size_t)N * c.d_model * es, 256);
+    if (end > ws_bytes) return set_err(ctx, COMPACT_EWORKSPACE, "workspace too small for this mixed pass");
+
+    std::vector<int> done(N, 0), sdone(N, 0);   // prefilled rows / finished decode steps per block
+    for (int b = 0; b < N; ++b) kv->h_len[b] = 0;
+    for (;;) {
+        std::vector<int> dec, pre;
+        for (int b = 0; b < N; ++b) {
+            const int L = h_cu_seqlens[b + 1] - h_cu_seqlens[b];
+            if (done[b] < L)
+                pre.push_back(b);
+            else if (sdone[b] < S)
+                dec.push_back(b);
+        }
+        if (pre.empty() && dec.empty()) break;
+
+        if (pre.empty()) {
+            // ---- decode-only step over the blocks that still have steps left ----------
+            const int n = (int)dec.size();
+            Plan plan;
+            plan.meta.resize(n);
+            std::vector<int32_t> src_tab(n), dst_tab(n);
+            for (int i = 0; i < n; ++i) {
+                const int b = dec[i];
+                BlockMeta& m = plan.meta[i];
+                m.row0 = i;
+                m.len = kv->h_len[b];
+                m.capacity = kv->h_capacity[b];
+                m.pos_offset = kv->h_pos_offset ? kv->h_pos_offset[b] : 0;
+                m.slab = kv->h_slab_offset[b];
+                plan.max_len = std::max(plan.max_len, m.len);
+                src_tab[i] = -(sdone[b] * N + b) - 2;    // row of x_decode [S * N, d] (base 1)
+                dst_tab[i] = sdone[b] * N + b;           // row of y_decode (base 0)
+            }
+            add_kv_chunks(plan, 1);
+            MixExtra mx;
+            mx.src_tab = put(plan.extra, src_tab);
+            mx.dst_tab = put(plan.extra, dst_tab);
+            TRY(upload_plan(ctx, plan, s));
+            TRY(launch_move_rows(ctx, nullptr, d_x_decode, (const int32_t*)(plan.d_extra + mx.src_tab), xs, nullptr, nullptr, n, s));
+            TRY(decode_impl(ctx, w, n, 0, xs, kv, ys, nullptr, db, plan, s));
+            TRY(launch_move_rows(ctx, ys, nullptr, nullptr, d_y_decode, nullptr, (const int32_t*)(plan.d_extra + mx.dst_tab), n, s));
+            for (int b : dec) {
+                sdone[b] += 1;
+                kv->h_len[b] += 1;
+            }
+            continue;
+        }
+
+        // ---- mixed step: chunks of the blocks still in prefill (block order, within the
+        // token budget), one token of every block that is decoding -------------------
+        int budget = TM - (int)dec.size();
+        Plan plan;
+        std::vector<int> part, rows_of;   // participating blocks and their rows in this step
+        for (int b : pre) {
+            if (budget == 0) break;
+            const int L = h_cu_seqlens[b + 1] - h_cu_seqlens[b];
+            const int cnt = std::min(L - done[b], budget);
+            part.push_back(b);
+            rows_of.push_back(cnt);
+            budget -= cnt;
+        }
+        const int n_chunk = (int)part.size(), n_dec = (int)dec.size();
+        for (int b : dec) {
+            part.push_back(b);
+            rows_of.push_back(1);
+        }
+        const int n_part = (int)part.size();
+        plan.meta.resize(n_part);
+        std::vector<BlockMeta> dec_meta(n_dec);
+        std::vector<int32_t> qrow(n_dec), src_tab, dst_tab;
+        int Tm = 0;
+        for (int i = 0; i < n_part; ++i) {
+            const int b = part[i], cnt = rows_of[i];
+            BlockMeta& m = plan.meta[i];
+            m.row0 = Tm;
+            m.len = cnt;
+            m.prior = kv->h_len[b];
+            m.capacity = kv->h_capacity[b];
+            m.pos_offset = kv->h_pos_offset ? kv->h_pos_offset[b] : 0;
+            m.slab = kv->h_slab_offset[b];
+            plan.max_len = std::max(plan.max_len, cnt);
+            for (int r = 0; r < cnt; r += ROPE_TILE) plan.rope_tiles.push_back({i, r});
+            if (i < n_chunk) {
+                const int L = h_cu_seqlens[b + 1] - h_cu_seqlens[b];
+                if (bf)
+                    for (int r = 0; r < cnt; r += PREFILL_QTILE) plan.q_tiles.push_back({i, r});
+                for (int r = 0; r < cnt; ++r) {
+                    src_tab.push_back(h_cu_seqlens[b] + done[b] + r);                       // row of x_prefill (base 0)
+                    dst_tab.push_back(d_y_last && done[b] + r == L - 1 ? -b - 2 : -1);      // the block's last row -> y_last[b]
+                }
+            } else {
+                const int j = i - n_chunk;
+                dec_meta[j] = m;
+                dec_meta[j].row0 = j;
+                dec_meta[j].len = m.prior;   // cached rows before this token; the token's own row is written first
+                dec_meta[j].prior = 0;
+                qrow[j] = Tm;
+                for (int r = 0; r < m.prior + 1; r += DECODE_CHUNK) plan.kv_chunks.push_back({j, r});
+                src_tab.push_back(-(sdone[b] * N + b) - 2);
+                dst_tab.push_back(sdone[b] * N + b);
+            }
+            Tm += cnt;
+        }
+        {
+            const std::vector<BlockMeta>& mt = plan.meta;
+            std::stable_sort(plan.q_tiles.begin(), plan.q_tiles.end(), [&mt](const TileItem& a, const TileItem& b2) {
+                return mt[a.block].prior + a.row0 > mt[b2.block].prior + b2.row0;
+            });
+        }
+        MixExtra mx;
+        mx.dec_meta = put(plan.extra, dec_meta);
+        mx.qrow = put(plan.extra, qrow);
+        mx.src_tab = put(plan.extra, src_tab);
+        mx.dst_tab = put(plan.extra, dst_tab);
+        TRY(upload_plan(ctx, plan, s));
+        const int32_t* d_src = (const int32_t*)(plan.d_extra + mx.src_tab);
+        const int32_t* d_dst = (const int32_t*)(plan.d_extra + mx.dst_tab);
+
+        TRY(launch_move_rows(ctx, d_x_prefill, d_x_decode, d_src, xp, nullptr, nullptr, Tm, s));
+        TRY(launch_rmsnorm(ctx, xp, false, w->g_attn, pb.n, Tm, s));
+        TRY(gemm_full(ctx, pb.n, w->w_qkv, nullptr, false, pb.qkv, Tm, Dtot, c.d_model, 0, s));
+        TRY(launch_rope_kvwrite(ctx, plan.d_meta, plan.d_rope_tiles, (int)plan.rope_tiles.size(), pb.qkv, kv->d_k, kv->d_v, s));
+        if (bf) {
+            {
+                ProfileScope ps(ctx, COMPACT_K_ATTN_PREFILL, s);
+                TRY(launch_attn_prefill_bf16(ctx, plan.d_meta, plan.d_q_tiles, (int)plan.q_tiles.size(), (const bf16*)pb.qkv,
+                                             (const bf16*)kv->d_k, (const bf16*)kv->d_v, (bf16*)pb.o, s));
+            }
+            if (n_dec > 0)   // one query row per decoding block, read in place from the packed QKV rows
+                TRY(launch_attn_decode_bf16(ctx, (const BlockMeta*)(plan.d_extra + mx.dec_meta), plan.d_kv_chunks,
+                                            (int)plan.kv_chunks.size(), n_dec, 0, max_chunks, (const bf16*)pb.qkv,
+                                            (const bf16*)kv->d_k, (const bf16*)kv->d_v, db.attn_partials, (bf16*)pb.o, s,
+                                            (const int32_t*)(plan.d_extra + mx.qrow), Dtot));
+        } else {
+            // fp32 storage: a decoding block is a chunk of one row to the plain kernel
+            TRY(launch_attn_prefill_f32(ctx, plan.d_meta, n_part, plan.max_len, (const float*)pb.qkv, (const float*)kv->d_k,
+                                        (const float*)kv->d_v, (float*)pb.o, s));
+        }
+        TRY(gemm_full(ctx, pb.o, w->w_o, xp, false, pb.h, Tm, c.d_model, Dq, 2, s));
+        TRY(launch_rmsnorm(ctx, pb.h, true, w->g_ffn, pb.n, Tm, s));
+        if (c.n_experts == 0) {
+            TRY(gemm_full(ctx, pb.n, w->w_gate_up, nullptr, false, pb.act, Tm, c.ffn_dim, c.d_model, 1, s));
+            TRY(gemm_full(ctx, pb.act, w->w_down, pb.h, true, yp, Tm, c.d_model, c.ffn_dim, 0, s));
+        } else {
+            TRY(launch_moe_route(ctx, pb.n, w->w_router, Tm, pb.idx, pb.gate, pb.logits, s));
+            TRY(moe_ffn_rows(ctx, w, pb.n, pb.h, true, pb.idx, pb.gate, Tm, pb.act, pb.plan, pb.expert_out, yp, s));
+        }
+        TRY(launch_move_rows(ctx, yp, nullptr, nullptr, d_y_decode, d_y_last, d_dst, Tm, s));
+
+        for (int i = 0; i < n_part; ++i) {
+            const int b = part[i];
+            kv->h_len[b] += rows_of[i];
+            if (i < n_chunk)
+                done[b] += rows_of[i];
+            else
+                sdone[b] += 1;
+        }
+    }
+    return COMPACT_OK;
+}
+
+// ---------------------------------------------------------------------------
 // a depth of layers
 // ---------------------------------------------------------------------------
 extern "C" int compact_stack_workspace_bytes(const compact_ctx* ctx, int64_t max_tokens, int32_t max_blocks,

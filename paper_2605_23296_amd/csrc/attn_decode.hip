@@ -39,7 +39,8 @@ __global__ __launch_bounds__(DEC_WAVES * 64, 4) void attn_decode_bf16_kernel(con
                                                                             const bf16* __restrict__ kbase,
                                                                             const bf16* __restrict__ vbase,
                                                                             float* __restrict__ partials, int Hq, int Hkv,
-                                                                            float scale_log2) {
+                                                                            float scale_log2, const int32_t* __restrict__ qrow,
+                                                                            int q_stride) {
     constexpr int KS = HD / 32;            // k-steps of the QK product
     constexpr int DT = HD / 16;            // 16-row tiles of O^T, one per wavefront (the first DT wavefronts)
     constexpr int PLD = HD + 2;            // partial record: HD values, max, sum
@@ -90,7 +91,8 @@ __global__ __launch_bounds__(DEC_WAVES * 64, 4) void attn_decode_bf16_kernel(con
     // the group's query rows go through LDS: they are needed only once the K rows
     // have arrived, and parking them in registers until then would cost occupancy
     for (int i = t; i < G * (HD / 8); i += DEC_WAVES * 64)
-        *reinterpret_cast<bf16x8*>(qs + i * 8) = *reinterpret_cast<const bf16x8*>(q + ((size_t)b * Hq + kvh * G) * HD + i * 8);
+        *reinterpret_cast<bf16x8*>(qs + i * 8) =
+            *reinterpret_cast<const bf16x8*>(q + (size_t)(qrow ? qrow[b] : b) * q_stride + (size_t)kvh * G * HD + i * 8);
     __syncthreads();
 
     // ---- S^T = K Q^T over the wavefront's window; the window's column maxima ------
@@ -181,7 +183,7 @@ __global__ __launch_bounds__(DEC_WAVES * 64, 4) void attn_decode_bf16_kernel(con
 template <int HD>
 __global__ __launch_bounds__(HD) void attn_decode_combine_kernel(const BlockMeta* __restrict__ meta, int step, int max_chunks,
                                                                  const float* __restrict__ partials, bf16* __restrict__ o,
-                                                                 int Hq) {
+                                                                 int Hq, const int32_t* __restrict__ qrow) {
     constexpr int PLD = HD + 2;
     __shared__ float wgt[COMBINE_MAX_CHUNKS];
     __shared__ float red_m[HD / 64], red_l[HD / 64];
@@ -218,7 +220,7 @@ __global__ __launch_bounds__(HD) void attn_decode_combine_kernel(const BlockMeta
     }
     for (; ch < nch; ++ch) acc += wgt[ch] * rec[ch * PLD + dd];
     __syncthreads();
-    o[((size_t)b * Hq + head) * HD + dd] = (bf16)(acc / red_l[0]);
+    o[((size_t)(qrow ? qrow[b] : b) * Hq + head) * HD + dd] = (bf16)(acc / red_l[0]);
 }
 
 size_t attn_decode_partial_floats(const compact_layer_cfg& cfg, int n_blocks, int max_chunks) {
@@ -226,10 +228,12 @@ size_t attn_decode_partial_floats(const compact_layer_cfg& cfg, int n_blocks, in
 }
 
 int launch_attn_decode_bf16(compact_ctx* ctx, const BlockMeta* d_meta, const TileItem* d_chunks, int n_chunks, int n_blocks,
-                            int step, int max_chunks, const bf16* q, const bf16* d_k, const bf16* d_v, float* partials, bf16* o, hipStream_t s) {
+                            int step, int max_chunks, const bf16* q, const bf16* d_k, const bf16* d_v, float* partials, bf16* o,
+                            hipStream_t s, const int32_t* d_qrow, int q_stride) {
     const compact_layer_cfg& c = ctx->cfg;
     const float scale_log2 = LOG2E / sqrtf((float)c.head_dim);
     if (n_chunks == 0) return COMPACT_OK;
+    if (!d_qrow) q_stride = c.n_q_heads * c.head_dim;   // q [n_blocks, Hq * hd], row b for block b
     dim3 grid(n_chunks, c.n_kv_heads);
     dim3 cgrid(c.n_q_heads, n_blocks);
     if (max_chunks > COMBINE_MAX_CHUNKS) return set_err(ctx, COMPACT_ECAPACITY, "KV cache longer than the decode combine supports");
@@ -237,18 +241,18 @@ int launch_attn_decode_bf16(compact_ctx* ctx, const BlockMeta* d_meta, const Til
         {
             ProfileScope ps(ctx, COMPACT_K_ATTN_DECODE, s);
             attn_decode_bf16_kernel<128><<<grid, DEC_WAVES * 64, 0, s>>>(d_meta, d_chunks, step, max_chunks, q, d_k, d_v, partials,
-                                                                           c.n_q_heads, c.n_kv_heads, scale_log2);
+                                                                           c.n_q_heads, c.n_kv_heads, scale_log2, d_qrow, q_stride);
         }
         LAUNCH_CHECK(ctx);
-        attn_decode_combine_kernel<128><<<cgrid, 128, 0, s>>>(d_meta, step, max_chunks, partials, o, c.n_q_heads);
+        attn_decode_combine_kernel<128><<<cgrid, 128, 0, s>>>(d_meta, step, max_chunks, partials, o, c.n_q_heads, d_qrow);
     } else {
         {
             ProfileScope ps(ctx, COMPACT_K_ATTN_DECODE, s);
             attn_decode_bf16_kernel<64><<<grid, DEC_WAVES * 64, 0, s>>>(d_meta, d_chunks, step, max_chunks, q, d_k, d_v, partials,
-                                                                          c.n_q_heads, c.n_kv_heads, scale_log2);
+                                                                          c.n_q_heads, c.n_kv_heads, scale_log2, d_qrow, q_stride);
         }
         LAUNCH_CHECK(ctx);
-        attn_decode_combine_kernel<64><<<cgrid, 64, 0, s>>>(d_meta, step, max_chunks, partials, o, c.n_q_heads);
+        attn_decode_combine_kernel<64><<<cgrid, 64, 0, s>>>(d_meta, step, max_chunks, partials, o, c.n_q_heads, d_qrow);
     }
     LAUNCH_CHECK(ctx);
     return COMPACT_OK;

@@ -143,6 +143,10 @@ int launch_swiglu_reduce(compact_ctx* ctx, const float* partials, int ks, void* 
 int launch_residual_reduce(compact_ctx* ctx, const float* partials, int ks, const void* resid, void* y,
                            int rows, int cols, hipStream_t s);
 // copies the last row of every block of y [T, d] to y_last [N, d]
+// rows between packed buffers and the caller's (table value v >= 0: row v of base 0, v <= -2: row -v-2 of base 1,
+// -1: skip; null table: row i of base 0)
+int launch_move_rows(compact_ctx* ctx, const void* src0, const void* src1, const int32_t* src_tab, void* dst0, void* dst1,
+                     const int32_t* dst_tab, int rows, hipStream_t s);
 int launch_gather_last_rows(compact_ctx* ctx, const BlockMeta* d_meta, int n_blocks, const void* y,
                             void* y_last, hipStream_t s);
 
@@ -229,7 +233,9 @@ size_t attn_decode_partial_floats(const compact_layer_cfg& cfg, int n_blocks, in
 int launch_attn_decode_bf16(compact_ctx* ctx, const BlockMeta* d_meta, const TileItem* d_chunks, int n_chunks, int n_blocks,
                             int step, int max_chunks,
                             const bf16* q, const bf16* d_k, const bf16* d_v, float* partials, bf16* o,
-                            hipStream_t s);
+                            hipStream_t s, const int32_t* d_qrow = nullptr, int q_stride = 0);
+// d_qrow (nullable): block b's query is row d_qrow[b] of q, rows q_stride elements apart (its output goes to the same
+// row of o [rows, Hq * hd]); null: q and o are [n_blocks, Hq * hd]
 
 // attn_decode_prefix.hip (bf16): cascade over the shared prefix + private tails
 int launch_attn_decode_prefix_bf16(compact_ctx* ctx, const BlockMeta* d_tail_meta, const BlockMeta& shared,

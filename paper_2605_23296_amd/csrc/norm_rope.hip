@@ -408,3 +408,33 @@ int launch_gather_last_rows(compact_ctx* ctx, const BlockMeta* d_meta, int n_blo
     LAUNCH_CHECK(ctx);
     return COMPACT_OK;
 }
+
+// ---------------------------------------------------------------------------
+// Row mover of the mixed-batch scheduler: packed row i is read from / written to
+// the row a table names.  Table value v >= 0: row v of base 0; v <= -2: row
+// (-v - 2) of base 1; v == -1: no row (skip).  A null table means row i of base 0.
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(NT) void move_rows_kernel(const T* __restrict__ src0, const T* __restrict__ src1,
+                                                       const int32_t* __restrict__ src_tab, T* __restrict__ dst0,
+                                                       T* __restrict__ dst1, const int32_t* __restrict__ dst_tab, int d) {
+    const int i = blockIdx.x;
+    const int sv = src_tab ? src_tab[i] : i;
+    const int dv = dst_tab ? dst_tab[i] : i;
+    if (sv == -1 || dv == -1) return;
+    const T* src = sv >= 0 ? src0 + (size_t)sv * d : src1 + (size_t)(-sv - 2) * d;
+    T* dst = dv >= 0 ? dst0 + (size_t)dv * d : dst1 + (size_t)(-dv - 2) * d;
+    for (int c = threadIdx.x; c < d; c += NT) dst[c] = src[c];
+}
+
+int launch_move_rows(compact_ctx* ctx, const void* src0, const void* src1, const int32_t* src_tab, void* dst0, void* dst1,
+                     const int32_t* dst_tab, int rows, hipStream_t s) {
+    if (rows == 0) return COMPACT_OK;
+    const int d = ctx->cfg.d_model;
+    if (ctx->cfg.dtype == COMPACT_BF16)
+        move_rows_kernel<bf16><<<rows, NT, 0, s>>>((const bf16*)src0, (const bf16*)src1, src_tab, (bf16*)dst0, (bf16*)dst1, dst_tab, d);
+    else
+        move_rows_kernel<float><<<rows, NT, 0, s>>>((const float*)src0, (const float*)src1, src_tab, (float*)dst0, (float*)dst1, dst_tab, d);
+    LAUNCH_CHECK(ctx);
+    return COMPACT_OK;
+}

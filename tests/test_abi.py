@@ -239,3 +239,25 @@ def test_prefill_extend_rejects_bad_arguments_without_a_device():
     kv3, _ = _kv([128, 128], [28, 28])
     assert call(kv=kv3, y=None) == 1
     assert call(kv=kv3, ws=None) == 4
+
+
+def test_mixed_forward_rejects_bad_arguments_without_a_device():
+    lay = _fake_layer()
+    L, ctx, w = lay.L, lay.ctx, C.byref(lay.w)
+    x = C.c_void_p(0x30000)
+    ws = C.c_void_p(0x40000)
+    cu = (C.c_int32 * 3)(0, 100, 200)
+    kv, keep = _kv([128, 128], [0, 0])
+    call = lambda budget=64, steps=4, xd=x, ws=ws, kv=kv: L.compact_mixed_forward(
+        ctx, w, 2, cu, x, steps, xd, C.byref(kv) if kv is not None else None, budget, None, x, ws, 1 << 30, None)
+    assert call(budget=2) == 1                         # every decoding block needs a row of its own, plus a chunk row
+    assert b"max_batched_tokens" in L.compact_last_error(ctx)
+    assert call(steps=-1) == 1
+    assert call(xd=None) == 1
+    assert call(ws=None) == 4
+    assert call(kv=None) == 1
+    assert call(steps=29) == 3                         # 100 + 29 rows do not fit 128
+    n, m = C.c_size_t(), C.c_size_t()
+    assert L.compact_mixed_workspace_bytes(ctx, 64, 2, 160, C.byref(n)) == 0
+    assert L.compact_workspace_bytes(ctx, 200, 2, 160, C.byref(m)) == 0
+    assert 0 < n.value < m.value                       # sized by the budget, not by the 200 prefill tokens

@@ -1,0 +1,127 @@
+"""Mixed batches on the GPU (compact_mixed_forward: prefill chunks of some blocks in one
+batch with decode tokens of others, paper Sec. IV-B chunked prefill): the schedule must
+not change what is computed, so the outputs are checked against the fp64 checker's plain
+prefill-then-decode pass, through the C ABI, for several token budgets."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import layer as O
+from paper_2605_23296_amd import binding as B
+from paper_2605_23296_amd.workloads import WORKLOADS, LayerConfig, Workload, make_inputs, to_numpy_f64
+from tests.util import rel_err, vec_rel_err
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def run_mixed(inp, budget, pos_offset=None, weights=None):
+    layer, cu = inp.layer, inp.cu_seqlens
+    N, S = len(inp.block_lens), inp.x_decode.shape[0]
+    lay = B.Layer(layer, weights or {k: v.to(DEV).contiguous() for k, v in inp.weights.items()})
+    dt = lay.torch_dtype
+    kv = B.KVCache(layer, [L + S + 3 for L in inp.block_lens], DEV, dt, pos_offset)
+    kv.k.fill_(float("nan"))
+    kv.v.fill_(float("nan"))
+    lay.ws = torch.empty(lay.mixed_workspace_bytes(budget, N, max(inp.block_lens) + S), dtype=torch.uint8, device=DEV)
+    y_last = torch.full((N, layer.d_model), float("nan"), dtype=dt, device=DEV)
+    y_dec = torch.full((S, N, layer.d_model), float("nan"), dtype=dt, device=DEV)
+    lay.compact_mixed_forward(cu, inp.x_prefill.to(DEV), inp.x_decode.to(DEV).contiguous() if S else None, kv, budget,
+                              y_last, y_dec if S else None)
+    torch.cuda.synchronize()
+    assert kv.lens() == [L + S for L in inp.block_lens]
+    return dict(y_last=y_last, y_dec=y_dec, kv=kv)
+
+
+def check(inp, budget, tol, elem_tol, ref_out, pos_offset=None):
+    g = run_mixed(inp, budget, pos_offset)
+    pre, y_dec, Ks, Vs = ref_out
+    errs, elem = {}, {}
+
+    def cmp(tag, got, r):
+        errs[tag] = vec_rel_err(got, r)
+        elem[tag] = rel_err(got, r)
+
+    cmp("y_last", to_numpy_f64(g["y_last"]), np.stack([p["y"][-1] for p in pre]))
+    if y_dec.shape[0]:
+        cmp("y_dec", to_numpy_f64(g["y_dec"]), y_dec)
+    for b in range(len(inp.block_lens)):
+        cmp("K%d" % b, to_numpy_f64(g["kv"].block_k(b)), Ks[b])
+        cmp("V%d" % b, to_numpy_f64(g["kv"].block_v(b)), Vs[b])
+    worst, worst_e = max(errs, key=errs.get), max(elem, key=elem.get)
+    print("budget", budget, "worst vector error", worst, "%.3e" % errs[worst], "| worst element error", worst_e, "%.3e" % elem[worst_e])
+    assert errs[worst] < tol, {k: "%.2e" % v for k, v in errs.items()}
+    assert elem[worst_e] < elem_tol, {k: "%.2e" % v for k, v in elem.items()}
+
+
+def oracle_pass(inp, pos_offset=None):
+    ref = O.Layer(inp.layer.as_dict(), {k: to_numpy_f64(v) for k, v in inp.weights.items()})
+    pre, y_dec, Ks, Vs, _ = ref.forward(to_numpy_f64(inp.x_prefill), inp.cu_seqlens, to_numpy_f64(inp.x_decode), pos_offset)
+    return pre, y_dec, Ks, Vs
+
+
+def test_tiny_fp32_mixed_schedules_in_full():
+    inp = make_inputs(WORKLOADS["tiny_fp32"], block_lens=[128, 65, 1, 97], decode_steps=5, gain_jitter=True)
+    po = [0, 7, 3, 100]
+    ref = oracle_pass(inp, po)
+    for budget in (5, 64, 100, 1000):       # 5: chunks of 1-5 rows; 1000: everything in one step
+        check(inp, budget, 1e-5, 1e-5, ref, po)
+
+
+def test_bf16_mixed_schedules_ragged_blocks():
+    """Budgets on and off the tile sizes; early blocks decode while late ones still prefill
+    (budget 256: block 0 alone needs three steps), and finish their steps before the others."""
+    layer = LayerConfig(d_model=512, n_q_heads=4, n_kv_heads=2, head_dim=128, ffn_dim=1024, rope_theta=500000.0)
+    wl = Workload("small_dense", layer, [700, 130, 257, 40], 4, 6)
+    inp = make_inputs(wl, gain_jitter=True)
+    ref = oracle_pass(inp)
+    for budget in (256, 203, 4096):
+        check(inp, budget, 2e-2, 5e-2, ref)
+
+
+def test_bf16_mixed_routed_layer_keeps_the_caches_right():
+    layer = LayerConfig(d_model=256, n_q_heads=8, n_kv_heads=2, head_dim=64, ffn_dim=320, n_experts=16, top_k=4,
+                        rope_theta=500000.0)
+    wl = Workload("small_moe", layer, [200, 75, 30], 3, 4)
+    inp = make_inputs(wl)
+    g = run_mixed(inp, 96)
+    pre, y_dec, Ks, Vs = oracle_pass(inp)
+    # the prefill rows' K/V depend on no routing; decode rows follow routed outputs only through x_decode (given)
+    for b in range(3):
+        assert vec_rel_err(to_numpy_f64(g["kv"].block_k(b)), Ks[b]) < 2e-2
+        assert vec_rel_err(to_numpy_f64(g["kv"].block_v(b)), Vs[b]) < 2e-2
+    err = np.sort(np.array([vec_rel_err(to_numpy_f64(g["y_dec"][s, b]), y_dec[s, b]) for s in range(4) for b in range(3)]))
+    assert err[len(err) // 2] < 2e-2      # near-ties in the router may move single rows
+
+
+def test_dense_ragged32_mixed_matches_the_plain_pass_at_full_size():
+    """The named ragged workload (32 blocks of 512..8192 tokens) with 8 decode steps under an 8192-token
+    budget against compact_layer_forward (which test_gpu_full_size.py checks against the fp64 checker at
+    this size): prefill K/V rows bitwise (projections are row-wise), everything else within the bf16 tolerance."""
+    wl = WORKLOADS["dense_ragged32"]
+    S = 8
+    inp = make_inputs(wl, device=DEV, gen_device=DEV, decode_steps=S)
+    g = run_mixed(inp, 8192, weights=inp.weights)
+    layer, cu, lens = inp.layer, inp.cu_seqlens, inp.block_lens
+    N, T = len(lens), cu[-1]
+    lay = B.Layer(layer, inp.weights)
+    dt = torch.bfloat16
+    kv = B.KVCache(layer, [L + S + 3 for L in lens], DEV, dt)
+    lay.ensure_workspace(T, N, max(lens) + S, DEV)
+    y_last = torch.empty(N, layer.d_model, dtype=dt, device=DEV)
+    y_dec = torch.empty(S, N, layer.d_model, dtype=dt, device=DEV)
+    lay.compact_layer_forward(cu, inp.x_prefill, inp.x_decode.contiguous(), kv, None, y_last, y_dec)
+    torch.cuda.synchronize()
+
+    def vec_err(a, b):
+        a, b = a.float(), b.float()
+        return ((a - b).norm(dim=-1) / b.norm(dim=-1)).max().item()
+
+    assert vec_err(g["y_last"], y_last) < 2e-2
+    assert vec_err(g["y_dec"], y_dec) < 2e-2
+    for b in (0, int(np.argmin(lens)), int(np.argmax(lens)), N - 1):
+        L = lens[b]
+        assert torch.equal(g["kv"].block_k(b)[:L], kv.block_k(b)[:L])
+        assert torch.equal(g["kv"].block_v(b)[:L], kv.block_v(b)[:L])
+        assert vec_err(g["kv"].block_k(b)[L:].reshape(S, -1), kv.block_k(b)[L:].reshape(S, -1)) < 2e-2
+        assert vec_err(g["kv"].block_v(b)[L:].reshape(S, -1), kv.block_v(b)[L:].reshape(S, -1)) < 2e-2
