@@ -195,6 +195,33 @@ def prefix_aware_pass(args, wl, inp, lay, bufs):
     }
 
 
+def mixed_pass(args, wl, inp, lay, kv, bufs):
+    """The pass under a token budget per step (chunked prefill interleaved with decode) and, beside it,
+    the plain pass (all prefill, then S batched steps) on the same inputs."""
+    layer, dev = inp.layer, bufs["x"].device
+    lens, S, N, T = inp.block_lens, inp.x_decode.shape[0], len(inp.block_lens), inp.cu_seqlens[-1]
+    plain_ws = lay.ws
+    for _ in range(max(1, args.warmup)):
+        run_pass(lay, inp, kv, bufs)
+    t_plain = timed(lambda: run_pass(lay, inp, kv, bufs), args.steps)
+    need = lay.mixed_workspace_bytes(args.mixed, N, max(lens) + S)
+    lay.ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    mixed = lambda: lay.compact_mixed_forward(inp.cu_seqlens, bufs["x"], bufs["xd"], kv, args.mixed, bufs["y_last"], bufs["y_dec"])
+    for _ in range(max(1, args.warmup)):
+        mixed()
+    t_mixed = timed(mixed, args.steps)
+    return {
+        "metric": "compaction_decode_tokens_per_s", "value": N * S / t_mixed, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": max(1, args.warmup), "ms_per_step": t_mixed * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": layer.dtype, "data": "synthetic",
+        "config": {"workload": "%s under a budget of %d rows per step (prefill chunks + decode tokens in one batch)"
+                               % (wl.name, args.mixed), "total_prefill_tokens": T, "decode_tokens": N * S},
+        "workspace_bytes": need,
+        "plain_pass": {"ms_per_step": t_plain * 1e3, "value": N * S / t_plain, "workspace_bytes": plain_ws.numel(),
+                       "mixed_over_plain_time": t_mixed / t_plain},
+    }
+
+
 def stack_pass(args, wl, inp, lay, bufs):
     """L layers deep: the parallel pass (N blocks, S batched steps) and the sequential
     baseline at matched decode volume (one block = the whole history, N * S steps)."""
@@ -254,6 +281,9 @@ def main():
     ap.add_argument("--mxfp4", action="store_true",
                     help="routed workloads: the experts come as block-scaled 4-bit arrays (paper Sec. IV-B, mxfp4 weights); "
                          "decode steps stream those, the prefill reads their exact bf16 expansion")
+    ap.add_argument("--mixed", type=int, default=0, metavar="TOKENS",
+                    help="time the token-budgeted mixed schedule instead (compact_mixed_forward: prefill chunks and decode "
+                         "tokens in one batch, at most TOKENS rows per step) beside the plain prefill-then-decode pass")
     ap.add_argument("--stack", type=int, default=0, metavar="L",
                     help="time a depth of L layers instead (compact_stack_forward; per-layer weights and caches), and "
                          "beside it the paper's sequential baseline: the whole history as ONE block, the same number of "
@@ -311,6 +341,9 @@ def main():
     if args.stack > 0:
         del kv
         print(json.dumps(stack_pass(args, wl, inp, lay, bufs)))
+        return
+    if args.mixed > 0:
+        print(json.dumps(mixed_pass(args, wl, inp, lay, kv, bufs)))
         return
 
     for _ in range(args.warmup):
