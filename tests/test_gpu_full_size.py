@@ -15,7 +15,7 @@ import torch
 
 from oracle import layer as O
 from paper_2605_23296_amd import binding as B
-from paper_2605_23296_amd.workloads import WORKLOADS, make_inputs, to_numpy_f64
+from paper_2605_23296_amd.workloads import WORKLOADS, make_inputs, make_mxfp4_experts, to_numpy_f64
 from tests import harness as H
 from tests.util import rel_err, vec_rel_err
 
@@ -40,6 +40,25 @@ class LazyF64:
 
     def __getitem__(self, key):
         return to_numpy_f64(self.t[key])
+
+
+class LazyQ4:
+    """Expert weights given as block-scaled 4-bit arrays: expert e is expanded to float64 on
+    demand by the checker's own definition of the format (oracle/mxfp4.py), from the codes."""
+
+    def __init__(self, codes, scales):
+        self.codes, self.scales = codes, scales
+        self.shape = tuple(codes.shape[:-1]) + (codes.shape[-1] * 2,)
+
+        self._last = (None, None)
+
+    def __getitem__(self, key):
+        from oracle import mxfp4 as Q
+        key = key if isinstance(key, tuple) else (key,)
+        e = int(key[0])
+        if self._last[0] != e:
+            self._last = (e, Q.dequantize(self.codes[e].cpu().numpy(), self.scales[e].cpu().numpy()))
+        return self._last[1][key[1:]] if len(key) > 1 else self._last[1]
 
 
 def sample_rows(L, rng, n=10):
@@ -78,9 +97,21 @@ def run_gpu(inp, with_routes):
     return out
 
 
-def check_workload(name, blocks=None, n_rows=10):
+def check_workload(name, blocks=None, n_rows=10, mxfp4=False):
     wl = WORKLOADS[name]
     inp = make_inputs(wl, device="cuda", gen_device="cuda")
+    q4 = None
+    if mxfp4:
+        # the experts are 4-bit arrays; the library expands them into its 16-bit copy (read by the prefill),
+        # the checker expands the same arrays by its own definition
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(wl.seed + 77)
+        q4 = make_mxfp4_experts(inp.layer, gen, "cuda")
+        lay0 = B.Layer(inp.layer, None)
+        for nm in ("w_exp_gate_up", "w_exp_down"):
+            lay0.compact_mxfp4_dequant(q4[nm + "_q"], q4[nm + "_s"], inp.weights[nm])
+        inp.weights.update(q4)
+        torch.cuda.synchronize()
     layer, lens, cu = inp.layer, inp.block_lens, inp.cu_seqlens
     N, S = len(lens), inp.x_decode.shape[0]
     moe = layer.n_experts > 0
@@ -92,7 +123,12 @@ def check_workload(name, blocks=None, n_rows=10):
 
     w = {}
     for k_, v in inp.weights.items():
-        w[k_] = LazyF64(v) if k_.startswith("w_exp_") else to_numpy_f64(v)
+        if k_.endswith(("_q", "_s")):
+            continue
+        if k_.startswith("w_exp_"):
+            w[k_] = LazyQ4(q4[k_ + "_q"], q4[k_ + "_s"]) if mxfp4 else LazyF64(v)
+        else:
+            w[k_] = to_numpy_f64(v)
     ref = O.Layer(layer.as_dict(), w)
     errs, elem, n_close = {}, {}, 0
 
@@ -158,3 +194,9 @@ def test_dense_ragged32_full_size():
 
 def test_moe_16x8192_full_size():
     check_workload("moe_16x8192", blocks=[0, 15], n_rows=6)
+
+
+def test_moe_16x8192_full_size_with_4bit_experts():
+    """The routed workload with block-scaled 4-bit experts (bench.py --mxfp4): decode steps stream the
+    4-bit arrays, the prefill reads their expansion; the checker's experts come from the same arrays."""
+    check_workload("moe_16x8192", blocks=[0, 15], n_rows=6, mxfp4=True)

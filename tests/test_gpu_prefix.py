@@ -34,6 +34,7 @@ def fill_cache(kv, b, K, V):
     ("dense_8x4096", [512] * 2 + [513] * 3 + [1000] * 4, [2] * 9),            # 9 workers: 36 columns, three groups
     ("moe_16x8192", [64, 300, 301], [5, 1, 257]),                             # head_dim 64, group of 8
     ("dense_8x4096", [0, 0, 40], [3, 1, 2]),                                  # workers without any prefix
+    ("dense_8x4096", [90 * (b + 1) for b in range(24)], [1 + b % 3 for b in range(24)]),   # 24 workers: six column groups
 ])
 def test_prefix_decode_attention_kernel(wl, prefix, tail):
     layer = WORKLOADS[wl].layer
