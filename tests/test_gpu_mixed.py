@@ -125,3 +125,15 @@ def test_dense_ragged32_mixed_matches_the_plain_pass_at_full_size():
         assert torch.equal(g["kv"].block_v(b)[:L], kv.block_v(b)[:L])
         assert vec_err(g["kv"].block_k(b)[L:].reshape(S, -1), kv.block_k(b)[L:].reshape(S, -1)) < 2e-2
         assert vec_err(g["kv"].block_v(b)[L:].reshape(S, -1), kv.block_v(b)[L:].reshape(S, -1)) < 2e-2
+
+
+def test_mixed_degenerate_schedules_fp32():
+    """The smallest budget the call accepts (one chunk row per step once every block decodes), blocks of
+    one token, no decode steps at all, and a single block."""
+    wl = WORKLOADS["tiny_fp32"]
+    inp = make_inputs(wl, block_lens=[5, 1, 9], decode_steps=3, gain_jitter=True)
+    check(inp, 4, 1e-5, 1e-5, oracle_pass(inp))
+    inp0 = make_inputs(wl, block_lens=[5, 1, 9], decode_steps=0)
+    check(inp0, 4, 1e-5, 1e-5, oracle_pass(inp0))
+    one = make_inputs(wl, block_lens=[33], decode_steps=2)
+    check(one, 16, 1e-5, 1e-5, oracle_pass(one))
