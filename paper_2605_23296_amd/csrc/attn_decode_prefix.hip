@@ -258,14 +258,25 @@ __global__ __launch_bounds__(PFX_CT) void attn_decode_prefix_combine_kernel(cons
 #pragma unroll
     for (int i = 1; i < PFX_CT / 64; ++i) l += red[i];
     const int sl = t / TPR, e = t % TPR;
+    // four records in flight per thread; a record that carries no weight (a tail chunk nobody wrote)
+    // is read from a valid address and dropped
     float2 acc = float2{0.f, 0.f};
-    for (int i = sl; i < n; i += NS) {
-        const float wi = wgt[i];
-        if (wi != 0.f) {
-            const float2 v = *reinterpret_cast<const float2*>(base + (size_t)roff[i] * PLD + 2 * e);
-            acc.x += wi * v.x;
-            acc.y += wi * v.y;
+    for (int i0 = sl; i0 < n; i0 += 4 * NS) {
+        float2 v[4];
+        float wi[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = i0 + u * NS;
+            wi[u] = i < n ? wgt[i] : 0.f;
+            const int ro = i < n ? max(roff[i], 0) : 0;
+            v[u] = *reinterpret_cast<const float2*>(base + (size_t)ro * PLD + 2 * e);
         }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (wi[u] != 0.f) {
+                acc.x += wi[u] * v[u].x;
+                acc.y += wi[u] * v[u].y;
+            }
     }
     part[sl][e] = acc;
     __syncthreads();
