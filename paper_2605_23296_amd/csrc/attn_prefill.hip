@@ -92,8 +92,23 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_bf16_kernel(const BlockMe
 
     // ---- staging ----------------------------------------------------------------
     bf16x8 kreg[NLD], vreg[NLD];
+    // chunk i of a thread sits 256 / KCH rows (K) resp. 32 rows (V^T) below chunk i - 1: one per-lane
+    // offset each, everything else of the address is wave-uniform
+    const unsigned koff0 = (unsigned)((t / KCH) * HD + (t % KCH) * 8);
+    const unsigned voff0 = (unsigned)((t >> 3) * bm.capacity + (t & 7) * 8);
     auto load_tile = [&](int kt) {
         const int kv0 = kt * KV_TILE;
+        if (kv0 + KV_TILE <= len) {   // the whole tile lies inside the cache: no clamps, no zeroing
+            const bf16* kt0 = kslab + (size_t)kv0 * HD;
+            const bf16* vt0 = vslab + kv0;
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) {
+                kreg[i] = *reinterpret_cast<const bf16x8*>(kt0 + (size_t)i * (256 / KCH) * HD + koff0);
+                vreg[i] = *reinterpret_cast<const bf16x8*>(vt0 + (size_t)i * 32 * bm.capacity + voff0);
+            }
+            return;
+        }
+
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             const int q = t + i * 256;
