@@ -90,65 +90,68 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_bf16_kernel(const BlockMe
     const int q_hi_wave = prior + it.row0 + wave * 32 + 31;              // last query row of this wave
     const int n_tiles = q_hi_wg / KV_TILE + 1;
 
-    // ---- staging ----------------------------------------------------------------
-    bf16x8 kreg[NLD], vreg[NLD];
-    // chunk i of a thread sits 256 / KCH rows (K) resp. 32 rows (V^T) below chunk i - 1: one per-lane
-    // offset each, everything else of the address is wave-uniform
-    const unsigned koff0 = (unsigned)((t / KCH) * HD + (t % KCH) * 8);
-    const unsigned voff0 = (unsigned)((t >> 3) * bm.capacity + (t & 7) * 8);
-    auto load_tile = [&](int kt) {
+    // ---- staging: 16-byte global loads that land in LDS directly ---------------------
+    // A wave-instruction fills 64 consecutive 16-byte chunks of a tile; chunk L of the K tile is
+    // (row L / KCH, position L % KCH) and holds the row's chunk (L % KCH) ^ swz(row), chunk L of the
+    // V^T tile likewise with 8 chunks per row: each lane picks the global address that belongs in
+    // its slot.  Wavefront w issues instructions w, w + 4, ...; nothing passes through registers.
+    unsigned koff[NLD], voff[NLD];   // element offsets inside a tile's source rows, fixed per lane
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+        const int L = (i * 4 + wave) * 64 + lane;
+        const int krow = L / KCH, kc = (L % KCH) ^ swz<KCH>(krow);
+        koff[i] = (unsigned)(krow * HD + kc * 8);
+        const int vrow = L >> 3, vc = (L & 7) ^ swz<8>(vrow);
+        voff[i] = (unsigned)(vrow * bm.capacity + vc * 8);
+    }
+    auto issue_tile = [&](int kt, int stage) {
         const int kv0 = kt * KV_TILE;
-        if (kv0 + KV_TILE <= len) {   // the whole tile lies inside the cache: no clamps, no zeroing
+        bf16* ks = lds + stage * 2 * KTILE;
+        bf16* vs = ks + KTILE;
+        if (kv0 + KV_TILE <= len) {   // the whole tile lies inside the cache: no clamps
             const bf16* kt0 = kslab + (size_t)kv0 * HD;
             const bf16* vt0 = vslab + kv0;
 #pragma unroll
             for (int i = 0; i < NLD; ++i) {
-                kreg[i] = *reinterpret_cast<const bf16x8*>(kt0 + (size_t)i * (256 / KCH) * HD + koff0);
-                vreg[i] = *reinterpret_cast<const bf16x8*>(vt0 + (size_t)i * 32 * bm.capacity + voff0);
+                load16_to_lds(kt0 + koff[i], ks + (i * 4 + wave) * 64 * 8);
+                load16_to_lds(vt0 + voff[i], vs + (i * 4 + wave) * 64 * 8);
             }
-            return;
-        }
-
+        } else {   // last tile of the block: rows past the end are clamped (their scores are masked)
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            const int q = t + i * 256;
-            {   // K: row = token, KCH chunks per row
-                const int row = q / KCH, c = q % KCH;
-                const int tok = min(kv0 + row, len - 1);
-                kreg[i] = *reinterpret_cast<const bf16x8*>(kslab + (size_t)tok * HD + c * 8);
-            }
-            {   // V^T: row = head-dim index, 8 chunks of 8 tokens per row
-                const int row = q >> 3, c = q & 7;
-                const int tok = min(kv0 + c * 8, bm.capacity - 8);
-                bf16x8 v = *reinterpret_cast<const bf16x8*>(vslab + (size_t)row * bm.capacity + tok);
-                if (kv0 + KV_TILE > len) {
-#pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        if (kv0 + c * 8 + j >= len) v[j] = (bf16)0.f;
-                }
-                vreg[i] = v;
+            for (int i = 0; i < NLD; ++i) {
+                const int L = (i * 4 + wave) * 64 + lane;
+                const int krow = L / KCH, kc = (L % KCH) ^ swz<KCH>(krow);
+                const int tok = min(kv0 + krow, len - 1);
+                load16_to_lds(kslab + (size_t)tok * HD + kc * 8, ks + (i * 4 + wave) * 64 * 8);
+                const int vrow = L >> 3, vc = (L & 7) ^ swz<8>(vrow);
+                const int vt = min(kv0 + vc * 8, bm.capacity - 8);
+                load16_to_lds(vslab + (size_t)vrow * bm.capacity + vt, vs + (i * 4 + wave) * 64 * 8);
             }
         }
     };
-    auto store_tile = [&](int stage) {
-        bf16* ks = lds + stage * 2 * KTILE;
-        bf16* vs = ks + KTILE;
+    // After a wavefront's own loads of a LAST tile have landed: zero the V^T entries of tokens past
+    // the block's end (whatever the slab holds there must not reach the MFMA; their probabilities are 0).
+    auto fix_tail = [&](int kt, int stage) {
+        const int kv0 = kt * KV_TILE;
+        if (kv0 + KV_TILE <= len) return;
+        bf16* vs = lds + stage * 2 * KTILE + KTILE;
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
-            const int q = t + i * 256;
-            {
-                const int row = q / KCH, c = q % KCH;
-                *reinterpret_cast<bf16x8*>(ks + row * HD + ((c ^ swz<KCH>(row)) << 3)) = kreg[i];
-            }
-            {
-                const int row = q >> 3, c = q & 7;
-                *reinterpret_cast<bf16x8*>(vs + row * KV_TILE + ((c ^ swz<8>(row)) << 3)) = vreg[i];
+            const int L = (i * 4 + wave) * 64 + lane;
+            const int vrow = L >> 3, vc = (L & 7) ^ swz<8>(vrow);
+            if (kv0 + vc * 8 + 8 > len) {
+                bf16x8 v = *reinterpret_cast<bf16x8*>(vs + (size_t)L * 8);
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (kv0 + vc * 8 + j >= len) v[j] = (bf16)0.f;
+                *reinterpret_cast<bf16x8*>(vs + (size_t)L * 8) = v;
             }
         }
     };
 
-    load_tile(0);
-    store_tile(0);
+    issue_tile(0, 0);
+    wait_all_memory();
+    fix_tail(0, 0);
     __syncthreads();
 
     // token of MFMA row i of S^T tile tt: tt*32 + pi(i); pi keeps each lane's
@@ -238,12 +241,16 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_bf16_kernel(const BlockMe
         const bf16* ks = lds + (kt & 1) * 2 * KTILE;
         const bf16* vs = ks + KTILE;
         const bool more = kt + 1 < n_tiles;
-        if (more) load_tile(kt + 1);
+        // the other stage was last read in the previous iteration, which every wavefront has left
+        if (more) issue_tile(kt + 1, (kt + 1) & 1);
 
         if (kv0 <= q_hi_wave) {   // otherwise the whole tile is above this wave's diagonal
             tile_step(kv0 + KV_TILE - 1 > q_lo_wave, kv0, ks, vs);   // diag: some entry may be masked
         }
-        if (more) store_tile((kt + 1) & 1);
+        if (more) {
+            wait_all_memory();
+            fix_tail(kt + 1, (kt + 1) & 1);
+        }
         __syncthreads();
     }
 
