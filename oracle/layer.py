@@ -423,3 +423,36 @@ class Stack:
                 xs = np.stack([st[b]["y"] for b in range(N)])
             y_dec[s] = xs
         return y_pre, y_dec, Ks, Vs
+
+    def forward_prefix(self, x_history, cu_seqlens, x_decode):
+        """The depth of layers in the prefix-aware target-at-end layout (Sec. IV,
+        Dispatch): every layer prefills the whole history as one causal block
+        (its cache is shared by the workers), then in each decode step worker b's
+        token goes through all layers, attending in layer l rows 0 .. cu[b+1]-1
+        of that layer's shared cache plus its own tail in that layer.  Returns
+        (y_decode [S, N, d] of the last layer, per-layer shared (K, V), per-layer
+        per-worker tail K lists, tail V lists)."""
+        x = _f64(x_history)
+        N = len(cu_seqlens) - 1
+        shared = []
+        for lay in self.layers:
+            pre = lay.prefill_block(x)
+            shared.append((pre["K"], pre["V"]))
+            x = pre["y"]
+        S = x_decode.shape[0]
+        lay0 = self.layers[0]
+        Kt = [[np.zeros((0, lay0.Hkv, lay0.hd)) for _ in range(N)] for _ in self.layers]
+        Vt = [[np.zeros((0, lay0.Hkv, lay0.hd)) for _ in range(N)] for _ in self.layers]
+        y_dec = np.zeros((S, N, lay0.d), dtype=F64)
+        for s in range(S):
+            xs = _f64(x_decode[s])
+            for li, lay in enumerate(self.layers):
+                ys = np.zeros_like(xs)
+                for b in range(N):
+                    st = lay.decode_block_prefix(xs[b], shared[li][0], shared[li][1], int(cu_seqlens[b + 1]),
+                                                 Kt[li][b], Vt[li][b])
+                    Kt[li][b], Vt[li][b] = st["Kt"], st["Vt"]
+                    ys[b] = st["y"]
+                xs = ys
+            y_dec[s] = xs
+        return y_dec, shared, Kt, Vt

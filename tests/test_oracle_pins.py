@@ -689,3 +689,24 @@ def test_mxfp4_dequantize_is_exact_on_representable_matrices(rng):
             codes[r, k // 2] |= c << (4 * (k % 2))
     scales = (exps + 127).astype(np.uint8)
     np.testing.assert_array_equal(Q.dequantize(codes, scales), w)
+
+
+def test_stack_prefix_aware_worker_equals_a_lone_stack_run_on_its_truncated_history(rng):
+    """Through the whole depth, worker k of the prefix-aware layout equals an ordinary
+    single-block stack run on the history cut after block k (a different code path:
+    private caches per layer, no shared cache)."""
+    cfg = small_cfg()
+    ws = [small_weights(cfg, rng) for _ in range(3)]
+    st = O.Stack(cfg, ws)
+    lens = [5, 3, 6]
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    x = rng.standard_normal((cu[-1], 32))
+    xd = rng.standard_normal((3, 3, 32))
+    yd, shared, Kt, Vt = st.forward_prefix(x, cu, xd)
+    for b in range(3):
+        T_b = int(cu[b + 1])
+        _, yd1, Ks1, Vs1 = st.forward(x[:T_b], [0, T_b], xd[:, b:b + 1])
+        np.testing.assert_allclose(yd[:, b], yd1[:, 0], rtol=1e-10, atol=1e-12)
+        for li in range(3):
+            np.testing.assert_allclose(Kt[li][b], Ks1[li][0][T_b:], rtol=1e-10, atol=1e-12)
+            np.testing.assert_allclose(shared[li][0][:T_b], Ks1[li][0][:T_b], rtol=1e-10, atol=1e-12)
