@@ -145,34 +145,36 @@ def cpu_baseline(inp, n_dec=8):
 
 
 def prefix_aware_pass(args, wl, inp, lay, bufs):
-    """Prefix-aware layout: one prefill of the whole history as a single block, then S
-    decode steps in which worker b attends the first cu[b+1] rows of the shared cache
-    plus its own tail.  Algorithmic KV bytes per step: every shared row once (not once
-    per worker) plus the tails."""
+    """Prefix-aware layout: every layer prefills the whole history as ONE block into a shared cache, then S
+    decode steps in which worker b attends the first cu[b+1] rows of that cache plus its own tail
+    (compact_prefix_stack_forward; --stack L for a depth of L layers, else one layer).  Algorithmic KV bytes
+    per step and layer: every shared row once (not once per worker) plus the tails.  With --stack the
+    sequential baseline (one block, N * S decode tokens one after another) is timed beside it."""
     layer, dev = inp.layer, bufs["x"].device
     lens, S, N, T = inp.block_lens, inp.x_decode.shape[0], len(inp.block_lens), inp.cu_seqlens[-1]
     dt = lay.torch_dtype
-    shared = B.KVCache(layer, [T], dev, dt)
-    lay.ensure_workspace(T, 1, T, dev)
-    need = lay.prefix_workspace_bytes(N, T, S)
-    if lay.ws.numel() < need:
-        lay.ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    L = max(1, args.stack)
+    weights = make_stack_weights(wl, L, device=dev, gen_device=dev) if args.stack > 0 else [inp.weights]
+    shared = [B.KVCache(layer, [T], dev, dt) for _ in range(L)]
+    need = lay.prefix_stack_workspace_bytes(T, N, S + 8)
+    if args.stack > 0:
+        need = max(need, lay.stack_workspace_bytes(T, 1, T + N * S))
+    lay.ws = torch.empty(need, dtype=torch.uint8, device=dev)
     prefix = [int(c) for c in inp.cu_seqlens[1:]]
 
     def one_pass(n_steps):
-        tails = B.KVCache(layer, [S + 8] * N, dev, dt)
-        lay.compact_prefill([0, T], bufs["x"], shared, bufs["y_pre"])
-        for s in range(n_steps):
-            lay.compact_prefix_decode_step(bufs["xd"][s], shared, prefix, tails, bufs["y_dec"][s])
+        tails = [B.KVCache(layer, [S + 8] * N, dev, dt) for _ in range(L)]
+        lay.compact_prefix_stack_forward(weights, prefix, bufs["x"], bufs["xd"][:n_steps] if n_steps else None, shared, tails,
+                                         bufs["y_dec"] if n_steps else None)
 
-    for _ in range(args.warmup):
+    for _ in range(max(1, args.warmup)):
         one_pass(S)
     t_pass = timed(lambda: one_pass(S), args.steps)
-    t_prefill = timed(lambda: one_pass(0), max(2, args.steps // 2))
+    t_prefill = timed(lambda: one_pass(0), max(1, args.steps // 2))
     t_decode = max(t_pass - t_prefill, 1e-9)
     kv_tok = 2 * layer.Dkv * 2
-    shared_once = float(sum((max(prefix) + N * (s + 1)) * kv_tok for s in range(S)))
-    per_worker = float(sum((sum(prefix) + N * (s + 1)) * kv_tok for s in range(S)))
+    shared_once = float(L * sum((max(prefix) + N * (s + 1)) * kv_tok for s in range(S)))
+    per_worker = float(L * sum((sum(prefix) + N * (s + 1)) * kv_tok for s in range(S)))
     lay.compact_profile_select(B.K_ATTN_DECODE)
     one_pass(S)
     torch.cuda.synchronize()
@@ -182,17 +184,35 @@ def prefix_aware_pass(args, wl, inp, lay, bufs):
                 peak=PEAK_HBM_GBS, unit="GB/s", frac=shared_once / (ms / 1e3) / 1e9 / PEAK_HBM_GBS,
                 note="algorithmic bytes = every shared cache row once per step for all workers together + the tails; "
                      "reading each worker's prefix separately would move %.1fx as much" % (per_worker / shared_once))
-    return {
+    out = {
         "metric": "compaction_decode_tokens_per_s", "value": N * S / t_pass, "unit": "tokens/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": t_pass * 1e3, "higher_is_better": True, "scaling": "weak",
+        "steps": args.steps, "warmup": max(1, args.warmup), "ms_per_step": t_pass * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": layer.dtype, "data": "synthetic",
-        "config": {"workload": "%s, prefix-aware target-at-end layout: one %d-token prefill, %d workers with prefixes "
-                               "%d..%d, %d decode steps each" % (wl.name, T, N, prefix[0], prefix[-1], S),
-                   "total_prefill_tokens": T, "decode_tokens": N * S},
+        "config": {"workload": "%s, prefix-aware target-at-end layout, %d layer(s): one %d-token prefill, %d workers with "
+                               "prefixes %d..%d, %d decode steps each" % (wl.name, L, T, N, prefix[0], prefix[-1], S),
+                   "total_prefill_tokens": T, "decode_tokens": N * S, "n_layers": L},
         "prefill_tokens_per_s": T / t_prefill, "decode_tokens_per_s": N * S / t_decode, "ms_prefill": t_prefill * 1e3,
-        "ms_decode": t_decode * 1e3, "us_per_decode_step": t_decode * 1e6 / max(S, 1),
+        "ms_decode": t_decode * 1e3, "us_per_decode_step_per_layer": t_decode * 1e6 / max(S, 1) / L,
+        "ms_per_decode_token": t_pass * 1e3 / (N * S),
         "roofline": dict(kernel="attn_decode_prefix", **attn), "kernels": {"attn_decode_prefix": attn},
     }
+    if args.stack > 0:
+        del shared
+        Ls = args.seq_layers if args.seq_layers > 0 else L
+        kv1 = [B.KVCache(layer, [T + N * S], dev, dt) for _ in range(Ls)]
+        xd1 = bufs["xd"].reshape(S * N, 1, layer.d_model)
+        yd1 = torch.empty_like(xd1)
+        seq = lambda steps: lay.compact_stack_forward(weights[:Ls], [0, T], bufs["x"], xd1[:steps] if steps else None, kv1,
+                                                      bufs["y_last"][:1], yd1 if steps else None)
+        seq(8)
+        t_seq = timed(lambda: seq(S * N), 1) * L / Ls
+        t_seq_pre = timed(lambda: seq(0), 1) * L / Ls
+        out["sequential_single_block"] = {
+            "what": "the whole %d-token history as one block, the same %d decode tokens one after another" % (T, N * S),
+            "layers_measured": Ls, "scaled_to_layers": L, "ms_per_step": t_seq * 1e3, "ms_prefill": t_seq_pre * 1e3,
+            "ms_decode": (t_seq - t_seq_pre) * 1e3, "ms_per_decode_token": t_seq * 1e3 / (N * S),
+            "parallel_speedup": t_seq / t_pass}
+    return out
 
 
 def mixed_pass(args, wl, inp, lay, kv, bufs):

@@ -259,6 +259,25 @@ int compact_stack_forward(compact_ctx* ctx, int32_t n_layers, const compact_weig
                           const void* d_x_decode, compact_kv* kv, void* d_y_last, void* d_y_decode,
                           void* d_workspace, size_t ws_bytes, void* hip_stream);
 
+/* The depth of layers in the prefix-aware target-at-end layout (the paper's own
+ * configuration, Sec. IV Dispatch + Sec. IV-A models): every layer prefills the
+ * whole history d_x_history [history_tokens, d] as ONE causal block into its
+ * shared cache shared[l] (one block of capacity >= history_tokens), then every
+ * one of n_steps batched decode steps runs worker b's token through all layers,
+ * attending in layer l rows 0 .. h_prefix_len[b]-1 of shared[l] plus its own
+ * tail in tails[l] (as compact_prefix_decode_step).  d_x_decode / d_y_decode
+ * [S, N, d] are layer 0's step inputs and the last layer's step outputs.  w,
+ * shared, tails are host arrays [n_layers]; all layers' caches share one
+ * geometry.  With n_layers = 1 this is the prefix-aware pass of one layer with
+ * a single work list for all steps.  bf16 storage only.  shared[l].h_len[0] ends
+ * at history_tokens, tails[l].h_len[b] grows by n_steps.                      */
+int compact_prefix_stack_workspace_bytes(const compact_ctx* ctx, int64_t history_tokens, int32_t n_workers,
+                                         int32_t max_tail_len, size_t* bytes);
+int compact_prefix_stack_forward(compact_ctx* ctx, int32_t n_layers, const compact_weights* w, int32_t n_workers,
+                                 const int32_t* h_prefix_len, int64_t history_tokens, const void* d_x_history,
+                                 int32_t n_steps, const void* d_x_decode, compact_kv* shared, compact_kv* tails,
+                                 void* d_y_decode, void* d_workspace, size_t ws_bytes, void* hip_stream);
+
 /* ---- per-kernel timing ----------------------------------------------------
  * When enabled, every launch of the selected kernel class is bracketed by HIP
  * events on the launch stream.  compact_profile_read synchronises those

@@ -27,6 +27,7 @@ EXPORTS = [
     "compact_prefix_workspace_bytes", "compact_prefix_decode_step", "compact_attn_decode_prefix",
     "compact_stack_workspace_bytes", "compact_stack_forward", "compact_prefill_extend", "compact_mxfp4_dequant",
     "compact_mixed_workspace_bytes", "compact_mixed_forward",
+    "compact_prefix_stack_workspace_bytes", "compact_prefix_stack_forward",
 ]
 
 
@@ -98,6 +99,8 @@ def lib():
     L.compact_attn_decode_prefix.argtypes = [vp, i32, vp, P(KV), P(i32), P(KV), vp, vp, sz, vp]
     L.compact_mixed_workspace_bytes.argtypes = [vp, i32, i32, i32, P(sz)]
     L.compact_mixed_forward.argtypes = [vp, P(Weights), i32, P(i32), vp, i32, vp, P(KV), i32, vp, vp, vp, sz, vp]
+    L.compact_prefix_stack_workspace_bytes.argtypes = [vp, i64, i32, i32, P(sz)]
+    L.compact_prefix_stack_forward.argtypes = [vp, i32, P(Weights), i32, P(i32), i64, vp, i32, vp, P(KV), P(KV), vp, vp, sz, vp]
     L.compact_mxfp4_dequant.argtypes = [vp, vp, vp, i64, i32, vp, vp]
     L.compact_stack_workspace_bytes.argtypes = [vp, i64, i32, i32, P(sz)]
     L.compact_stack_forward.argtypes = [vp, i32, P(Weights), i32, P(i32), vp, i32, vp, P(KV), vp, vp, vp, sz, vp]
@@ -280,6 +283,30 @@ class Layer:
         self.check(self.L.compact_stack_forward(
             self.ctx, nl, warr, len(cu_seqlens) - 1, _i32arr(cu_seqlens), _ptr(x_prefill), S, _ptr(x_decode), karr,
             _ptr(y_last), _ptr(y_decode), wsp, wsn, _stream()))
+
+    def prefix_stack_workspace_bytes(self, history_tokens, n_workers, max_tail_len):
+        n = C.c_size_t()
+        self.check(self.L.compact_prefix_stack_workspace_bytes(self.ctx, history_tokens, n_workers, max_tail_len, C.byref(n)))
+        return n.value
+
+    def compact_prefix_stack_forward(self, layer_weights, prefix_len, x_history, x_decode, shared, tails, y_decode):
+        """layer_weights: one dict per layer; shared, tails: one KVCache per layer."""
+        wsp, wsn = self._ws()
+        nl = len(layer_weights)
+        warr = (Weights * nl)()
+        for l, wd in enumerate(layer_weights):
+            for name, _ in Weights._fields_:
+                t = wd.get(name)
+                setattr(warr[l], name, t.data_ptr() if t is not None else None)
+        sarr, tarr = (KV * nl)(), (KV * nl)()
+        for l in range(nl):
+            for name, _ in KV._fields_:
+                setattr(sarr[l], name, getattr(shared[l].c, name))
+                setattr(tarr[l], name, getattr(tails[l].c, name))
+        S = 0 if x_decode is None else x_decode.shape[0]
+        self.check(self.L.compact_prefix_stack_forward(
+            self.ctx, nl, warr, tails[0].N, _i32arr(prefix_len), x_history.shape[0], _ptr(x_history), S, _ptr(x_decode),
+            sarr, tarr, _ptr(y_decode), wsp, wsn, _stream()))
 
     # -- prefix-aware layout ------------------------------------------------------
     def prefix_workspace_bytes(self, n_workers, max_prefix_len, max_tail_len):

@@ -1191,6 +1191,106 @@ extern "C" int compact_prefix_decode_step(compact_ctx* ctx, const compact_weight
     return COMPACT_OK;
 }
 
+extern "C" int compact_prefix_stack_workspace_bytes(const compact_ctx* ctx, int64_t history_tokens, int32_t n_workers,
+                                                    int32_t max_tail_len, size_t* bytes) {
+    size_t pre = 0, dec = 0;
+    int rc = compact_workspace_bytes(ctx, history_tokens, 1, 1, &pre);
+    if (rc != COMPACT_OK) return rc;
+    if (history_tokens > INT32_MAX) return set_err(const_cast<compact_ctx*>(ctx), COMPACT_EINVAL, "history too long");
+    rc = compact_prefix_workspace_bytes(ctx, n_workers, (int32_t)history_tokens, max_tail_len, &dec);
+    if (rc != COMPACT_OK) return rc;
+    const size_t es = dtype_size(ctx->cfg.dtype);
+    *bytes = pre + dec + 2 * align_up((size_t)history_tokens * ctx->cfg.d_model * es, 256) +
+             2 * align_up((size_t)n_workers * ctx->cfg.d_model * es, 256) + 256;
+    return COMPACT_OK;
+}
+
+extern "C" int compact_prefix_stack_forward(compact_ctx* ctx, int32_t n_layers, const compact_weights* w, int32_t n_workers,
+                                            const int32_t* h_prefix_len, int64_t history_tokens, const void* d_x_history,
+                                            int32_t n_steps, const void* d_x_decode, compact_kv* shared, compact_kv* tails,
+                                            void* d_y_decode, void* d_workspace, size_t ws_bytes, void* hip_stream) {
+    if (!ctx) return COMPACT_EINVAL;
+    if (n_layers < 1) return set_err(ctx, COMPACT_EINVAL, "n_layers must be >= 1");
+    if (n_steps < 0) return set_err(ctx, COMPACT_EINVAL, "n_steps must be >= 0");
+    if (!w || !shared || !tails) return set_err(ctx, COMPACT_EINVAL, "null per-layer weights or caches");
+    if (history_tokens < 1 || history_tokens > INT32_MAX) return set_err(ctx, COMPACT_EINVAL, "history_tokens must be >= 1");
+    if (n_steps > 0 && (!d_x_decode || !d_y_decode)) return set_err(ctx, COMPACT_EINVAL, "null decode input or output");
+    const compact_layer_cfg& c = ctx->cfg;
+    hipStream_t s = (hipStream_t)hip_stream;
+    const int N = n_workers;
+    const int32_t T = (int32_t)history_tokens;
+    const int32_t cu[2] = {0, T};
+    for (int l = 0; l < n_layers; ++l) TRY(validate_prefill(ctx, &w[l], 1, cu, d_x_history, &shared[l], d_workspace, 0));
+    // the decode plan doubles as the argument check of the prefix-aware part (layer 0's caches, with the
+    // shared length the prefill below will leave); the other layers must share that geometry
+    Plan dplan;
+    PrefixArgs pa;
+    {
+        const int32_t before = shared[0].h_len[0];
+        shared[0].h_len[0] = T;
+        const int rc = build_prefix_plan(ctx, N, &shared[0], h_prefix_len, &tails[0], n_steps, dplan, pa);
+        shared[0].h_len[0] = before;   // nothing is changed until every check has passed
+        if (rc != COMPACT_OK) return rc;
+    }
+    for (int l = 1; l < n_layers; ++l) {
+        TRY(check_kv(ctx, &tails[l], N));
+        bool same = shared[l].h_capacity[0] == shared[0].h_capacity[0] && shared[l].h_slab_offset[0] == shared[0].h_slab_offset[0];
+        for (int b = 0; same && b < N; ++b)
+            same = tails[l].h_capacity[b] == tails[0].h_capacity[b] && tails[l].h_slab_offset[b] == tails[0].h_slab_offset[b] &&
+                   tails[l].h_len[b] == tails[0].h_len[b];
+        if (!same) return set_err(ctx, COMPACT_EINVAL, "the caches of all layers must share one geometry");
+    }
+    const size_t es = dtype_size(c.dtype);
+
+    // workspace: [prefill region for the history][decode region][records][two [T, d]][two [N, d]]
+    Carver cp(d_workspace);
+    PrefillBufs pb;
+    carve_prefill(cp, c, T, pb);
+    const size_t off = align_up(cp.off, 256);
+    Carver cd((char*)d_workspace + off);
+    DecodeBufs db;
+    carve_decode(cd, c, N, 1, db);
+    pa.records = (float*)cd.take((size_t)pa.total_recs * c.n_kv_heads * (c.head_dim + 2) * 4);
+    size_t end = off + align_up(cd.off, 256);
+    char* base = (char*)d_workspace;
+    void *big[2], *small[2];
+    for (int i = 0; i < 2; ++i) {
+        big[i] = base + end;
+        end += align_up((size_t)T * c.d_model * es, 256);
+    }
+    for (int i = 0; i < 2; ++i) {
+        small[i] = base + end;
+        end += align_up((size_t)N * c.d_model * es, 256);
+    }
+    if (end > ws_bytes) return set_err(ctx, COMPACT_EWORKSPACE, "workspace too small for this prefix-aware stack");
+    for (int l = 0; l < n_layers; ++l) shared[l].h_len[0] = T;
+
+    // every layer prefills the whole history as one causal block: its cache serves all workers
+    Plan pplan;
+    build_prefill_plan(&shared[0], 1, cu, pplan);
+    const void* x = d_x_history;
+    for (int l = 0; l < n_layers; ++l) {
+        void* y = big[l & 1];
+        TRY(prefill_impl(ctx, &w[l], 1, cu, x, &shared[l], y, nullptr, nullptr, d_workspace, off, pplan, s));
+        x = y;
+    }
+    if (n_steps > 0) TRY(upload_plan(ctx, dplan, s));   // behind the prefill kernels on the stream
+    const size_t row_bytes = (size_t)N * c.d_model * es;
+    for (int st = 0; st < n_steps; ++st) {
+        const void* xs = (const char*)d_x_decode + st * row_bytes;
+        for (int l = 0; l < n_layers; ++l) {
+            void* ys = l == n_layers - 1 ? (void*)((char*)d_y_decode + st * row_bytes) : small[l & 1];
+            pa.d_k = shared[l].d_k;
+            pa.d_v = shared[l].d_v;
+            TRY(decode_impl(ctx, &w[l], N, st, xs, &tails[l], ys, nullptr, db, dplan, s, &pa));
+            xs = ys;
+        }
+    }
+    for (int l = 0; l < n_layers; ++l)
+        for (int b = 0; b < N; ++b) tails[l].h_len[b] += n_steps;
+    return COMPACT_OK;
+}
+
 extern "C" int compact_attn_decode_prefix(compact_ctx* ctx, int32_t n_workers, const void* d_q, const compact_kv* shared,
                                           const int32_t* h_prefix_len, const compact_kv* tails, void* d_o,
                                           void* d_workspace, size_t ws_bytes, void* hip_stream) {

@@ -261,3 +261,54 @@ def test_mixed_forward_rejects_bad_arguments_without_a_device():
     assert L.compact_mixed_workspace_bytes(ctx, 64, 2, 160, C.byref(n)) == 0
     assert L.compact_workspace_bytes(ctx, 200, 2, 160, C.byref(m)) == 0
     assert 0 < n.value < m.value                       # sized by the budget, not by the 200 prefill tokens
+
+
+def test_prefix_stack_call_rejects_bad_arguments_without_a_device():
+    lay = _fake_layer("dense_8x4096")
+    L, ctx = lay.L, lay.ctx
+    x = C.c_void_p(0x30000)
+    ws = C.c_void_p(0x40000)
+    warr = (B.Weights * 2)()
+    for l in range(2):
+        for name, _ in B.Weights._fields_:
+            setattr(warr[l], name, getattr(lay.w, name))
+
+    def kvarr(caps, lens, n=2, caps1=None):
+        arr, keep = (B.KV * n)(), []
+        for l in range(n):
+            kv, k = _kv(caps if (l == 0 or caps1 is None) else caps1, list(lens))
+            keep.append(k)
+            for name, _ in B.KV._fields_:
+                setattr(arr[l], name, getattr(kv, name))
+        return arr, keep
+
+    shared, ks = kvarr([1024], [0])
+    tails, kt = kvarr([64, 64, 64], [0, 0, 0])
+
+    def call(prefix=(100, 200, 1000), T=1000, steps=4, nl=2, shared=shared, tails=tails, ws=ws, xd=x):
+        pl = (C.c_int32 * len(prefix))(*prefix)
+        return L.compact_prefix_stack_forward(ctx, nl, warr, 3, pl, T, x, steps, xd, shared, tails, x, ws, 1 << 40, None)
+
+    assert call(nl=0) == 1
+    assert call(T=0) == 1
+    assert call(T=1025) == 3                                  # the history does not fit the shared cache
+    assert call(prefix=(100, 50, 1000)) == 1                  # prefixes must not decrease
+    assert call(prefix=(100, 200, 1001)) == 1                 # prefix beyond the history
+    assert call(steps=65) == 3                                # tails too small
+    assert call(steps=-1) == 1
+    assert call(xd=None) == 1
+    assert call(ws=None) == 4
+    other, ko = kvarr([64, 64, 64], [0, 0, 0], caps1=[64, 64, 72])
+    assert call(tails=other) == 1
+    assert b"geometry" in L.compact_last_error(ctx)
+    assert ks[0]["len"][0] == 0 and ks[1]["len"][0] == 0      # untouched on failure
+    n = C.c_size_t()
+    assert L.compact_prefix_stack_workspace_bytes(ctx, 1000, 3, 8, C.byref(n)) == 0 and n.value > 0
+    flay = _fake_layer()                                      # fp32 storage has no prefix-aware path
+    w32 = (B.Weights * 1)()
+    for name, _ in B.Weights._fields_:
+        setattr(w32[0], name, getattr(flay.w, name))
+    s32, _a = kvarr([128], [0], n=1)
+    t32, _b = kvarr([16, 16, 16], [0, 0, 0], n=1)
+    pl = (C.c_int32 * 3)(10, 20, 100)
+    assert flay.L.compact_prefix_stack_forward(flay.ctx, 1, w32, 3, pl, 100, x, 2, x, s32, t32, x, ws, 1 << 40, None) == 5

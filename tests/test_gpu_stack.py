@@ -123,3 +123,86 @@ def test_dense_8x4096_stack_equals_the_single_layer_calls_bitwise():
         for b in (0, N - 1):
             assert torch.equal(g["kvs"][l].block_k(b), kvs[l].block_k(b))
             assert torch.equal(g["kvs"][l].block_v(b), kvs[l].block_v(b))
+
+
+def run_prefix_stack(inp, weights, n_steps):
+    layer, cu = inp.layer, inp.cu_seqlens
+    N, T, nl = len(inp.block_lens), cu[-1], len(weights)
+    wdev = [{k: v.to(DEV).contiguous() for k, v in w.items()} for w in weights]
+    lay = B.Layer(layer, wdev[0])
+    dt = torch.bfloat16
+    shared = [B.KVCache(layer, [T + 5], DEV, dt) for _ in range(nl)]
+    tails = [B.KVCache(layer, [n_steps + 3] * N, DEV, dt) for _ in range(nl)]
+    for c in shared + tails:
+        c.k.fill_(float("nan"))
+        c.v.fill_(float("nan"))
+    lay.ws = torch.empty(lay.prefix_stack_workspace_bytes(T, N, n_steps), dtype=torch.uint8, device=DEV)
+    y_dec = torch.empty(n_steps, N, layer.d_model, dtype=dt, device=DEV)
+    lay.compact_prefix_stack_forward(wdev, [int(c) for c in cu[1:]], inp.x_prefill.to(DEV), inp.x_decode[:n_steps].to(DEV).contiguous(),
+                                     shared, tails, y_dec)
+    torch.cuda.synchronize()
+    for l in range(nl):
+        assert shared[l].lens() == [T] and tails[l].lens() == [n_steps] * N
+    return dict(y_dec=y_dec, shared=shared, tails=tails, wdev=wdev)
+
+
+def test_prefix_aware_stack_of_three_layers():
+    """The paper's own configuration in small: prefix-aware workers through a depth of layers."""
+    layer = LayerConfig(d_model=512, n_q_heads=4, n_kv_heads=2, head_dim=128, ffn_dim=1024, rope_theta=500000.0)
+    wl = Workload("small_dense", layer, [300, 77, 513, 40], 4, 3)
+    inp = make_inputs(wl)
+    ws = make_stack_weights(wl, 3, gain_jitter=True)
+    g = run_prefix_stack(inp, ws, 3)
+    ref = O.Stack(layer.as_dict(), [{k: to_numpy_f64(v) for k, v in w.items()} for w in ws])
+    yd, shared, Kt, Vt = ref.forward_prefix(to_numpy_f64(inp.x_prefill), inp.cu_seqlens, to_numpy_f64(inp.x_decode))
+    errs = {"y_dec": vec_rel_err(to_numpy_f64(g["y_dec"]), yd)}
+    elem = {"y_dec": rel_err(to_numpy_f64(g["y_dec"]), yd)}
+    for li in range(3):
+        errs["Ks%d" % li] = vec_rel_err(to_numpy_f64(g["shared"][li].block_k(0)), shared[li][0])
+        errs["Vs%d" % li] = vec_rel_err(to_numpy_f64(g["shared"][li].block_v(0)), shared[li][1])
+        for b in range(4):
+            errs["Kt%d_%d" % (li, b)] = vec_rel_err(to_numpy_f64(g["tails"][li].block_k(b)), Kt[li][b])
+            errs["Vt%d_%d" % (li, b)] = vec_rel_err(to_numpy_f64(g["tails"][li].block_v(b)), Vt[li][b])
+    worst = max(errs, key=errs.get)
+    print("worst vector error", worst, "%.3e" % errs[worst], "| y_dec element error %.3e" % elem["y_dec"])
+    assert errs[worst] < 2e-2, {k: "%.2e" % v for k, v in errs.items()}
+    assert elem["y_dec"] < 5e-2
+
+
+def test_prefix_aware_stack_equals_the_single_layer_calls_bitwise_at_full_size():
+    """dense_8x4096 (one 32768-token history, 8 workers), two layers, three steps: the stack call must give
+    the bits of compact_prefill + compact_prefix_decode_step applied layer by layer."""
+    wl = WORKLOADS["dense_8x4096"]
+    S, nl = 3, 2
+    inp = make_inputs(wl, device=DEV, gen_device=DEV, decode_steps=S)
+    ws = make_stack_weights(wl, nl, device=DEV, gen_device=DEV)
+    g = run_prefix_stack(inp, ws, S)
+    layer, cu = inp.layer, inp.cu_seqlens
+    N, T = len(inp.block_lens), cu[-1]
+    dt = torch.bfloat16
+    prefix = [int(c) for c in cu[1:]]
+    lays = [B.Layer(layer, w) for w in g["wdev"]]
+    shared = [B.KVCache(layer, [T + 5], DEV, dt) for _ in range(nl)]
+    tails = [B.KVCache(layer, [S + 3] * N, DEV, dt) for _ in range(nl)]
+    x = inp.x_prefill
+    for l in range(nl):
+        lays[l].ensure_workspace(T, 1, T, DEV)
+        y = torch.empty(T, layer.d_model, dtype=dt, device=DEV)
+        lays[l].compact_prefill([0, T], x, shared[l], y)
+        x = y
+        need = lays[l].prefix_workspace_bytes(N, T, S)
+        if lays[l].ws.numel() < need:
+            lays[l].ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    for s in range(S):
+        xs = inp.x_decode[s].contiguous()
+        for l in range(nl):
+            ys = torch.empty(N, layer.d_model, dtype=dt, device=DEV)
+            lays[l].compact_prefix_decode_step(xs, shared[l], prefix, tails[l], ys)
+            xs = ys
+        assert torch.equal(g["y_dec"][s], xs), s
+    torch.cuda.synchronize()
+    for l in range(nl):
+        assert torch.equal(g["shared"][l].block_k(0), shared[l].block_k(0))
+        for b in (0, N - 1):
+            assert torch.equal(g["tails"][l].block_k(b), tails[l].block_k(b))
+            assert torch.equal(g["tails"][l].block_v(b), tails[l].block_v(b))
