@@ -137,3 +137,17 @@ def test_mixed_degenerate_schedules_fp32():
     check(inp0, 4, 1e-5, 1e-5, oracle_pass(inp0))
     one = make_inputs(wl, block_lens=[33], decode_steps=2)
     check(one, 16, 1e-5, 1e-5, oracle_pass(one))
+
+
+def test_mixed_random_schedules_fp32():
+    """Random block lengths, step counts and budgets (seeded): the schedule never changes the result."""
+    wl = WORKLOADS["tiny_fp32"]
+    rng = np.random.default_rng(2024)
+    for _ in range(6):
+        n = int(rng.integers(1, 7))
+        lens = [int(v) for v in rng.integers(1, 150, size=n)]
+        steps = int(rng.integers(0, 7))
+        budget = int(rng.integers(n + 1, 200))
+        inp = make_inputs(wl, block_lens=lens, decode_steps=steps, gain_jitter=True)
+        print("lens", lens, "steps", steps, end=" ")
+        check(inp, budget, 1e-5, 1e-5, oracle_pass(inp))
