@@ -108,10 +108,10 @@ def timed(fn, reps):
     return (time.perf_counter() - t0) / reps
 
 
-def cpu_baseline(inp, n_dec=8):
-    """The fp64 checker as it stands, on the host cores: prefill of one whole
-    block and n_dec decode steps of that block, extrapolated linearly over the
-    independent blocks (exact in work, not in cache behaviour)."""
+def cpu_baseline(inp, n_blocks=2, n_dec=32):
+    """The fp64 checker as it stands, on the host cores: prefill of n_blocks whole blocks
+    (the first and the last) and n_dec decode steps of each, extrapolated linearly over the
+    independent blocks and steps (exact in work, not in cache behaviour)."""
     import numpy as np
     from oracle import layer as O
     from paper_2605_23296_amd.workloads import to_numpy_f64
@@ -120,27 +120,39 @@ def cpu_baseline(inp, n_dec=8):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         cores = os.cpu_count() or 1
-    lay = O.Layer(inp.layer.as_dict(), {k: to_numpy_f64(v) for k, v in inp.weights.items()})
-    L = inp.block_lens[0]
-    x = to_numpy_f64(inp.x_prefill[:L])
-    t0 = time.perf_counter()
-    pre = lay.prefill_block(x)
-    t_pre = time.perf_counter() - t0
-    K, V = pre["K"], pre["V"]
-    xd = to_numpy_f64(inp.x_decode[:n_dec, 0])
-    t0 = time.perf_counter()
-    for s in range(n_dec):
-        st = lay.decode_block(xd[s], K, V)
-        K, V = st["K"], st["V"]
-    t_dec = (time.perf_counter() - t0) / n_dec
+    w = {}
+    for k, v in inp.weights.items():
+        if k.endswith(("_q", "_s")):
+            continue
+        w[k] = to_numpy_f64(v)
+    lay = O.Layer(inp.layer.as_dict(), w)
     N, S = len(inp.block_lens), inp.x_decode.shape[0]
-    total = N * t_pre + N * S * t_dec
+    blocks = sorted(set([0, N - 1]))[:n_blocks]
+    n_dec = min(n_dec, S)
+    t_pre = t_dec = 0.0
+    tok = 0
+    for b in blocks:
+        x = to_numpy_f64(inp.x_prefill[inp.cu_seqlens[b]:inp.cu_seqlens[b + 1]])
+        t0 = time.perf_counter()
+        pre = lay.prefill_block(x)
+        t_pre += time.perf_counter() - t0
+        tok += x.shape[0]
+        K, V = pre["K"], pre["V"]
+        xd = to_numpy_f64(inp.x_decode[:n_dec, b])
+        t0 = time.perf_counter()
+        for s in range(n_dec):
+            st = lay.decode_block(xd[s], K, V)
+            K, V = st["K"], st["V"]
+        t_dec += time.perf_counter() - t0
+    T = inp.cu_seqlens[-1]
+    per_tok_pre, per_step = t_pre / tok, t_dec / max(n_dec * len(blocks), 1)
+    total = T * per_tok_pre + N * S * per_step
     return {
         "value": N * S / total, "unit": "decode tokens/s (prefill time included)",
         "cores": int(cores), "kind": "oracle",
-        "sample": "fp64 numpy checker: full prefill of 1 of %d blocks (%d tokens, %.1f s) + %d of %d decode steps of "
-                  "that block (%.3f s/step); extrapolated linearly to all blocks and steps" % (N, L, t_pre, n_dec, S, t_dec),
-        "prefill_tokens_per_s": L / t_pre, "decode_tokens_per_s": 1.0 / t_dec,
+        "sample": "fp64 numpy checker: full prefill of %d of %d blocks (%d tokens, %.1f s) + %d of %d decode steps of each "
+                  "(%.3f s/step); extrapolated linearly in prefill tokens and decode steps" % (len(blocks), N, tok, t_pre, n_dec, S, per_step),
+        "prefill_tokens_per_s": 1.0 / per_tok_pre, "decode_tokens_per_s": 1.0 / per_step,
     }
 
 
