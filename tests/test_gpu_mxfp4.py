@@ -130,3 +130,25 @@ def test_4bit_and_16bit_paths_agree_on_the_same_values():
     assert torch.equal(outs[0][1], outs[1][1])                 # routing does not depend on the expert format
     d = (outs[0][0] - outs[1][0]).norm(dim=-1) / outs[1][0].norm(dim=-1)
     assert d.max().item() < 4e-3, d.max().item()               # only the split of K differs (1024- vs 512-wide slices)
+
+
+def test_more_than_16_rows_fall_back_to_the_16bit_copy_with_the_same_bits():
+    """With more than 16 decode rows the routed step runs the prefill-size expert GEMM on the 16-bit copy;
+    giving the 4-bit arrays as well must not change a bit (they hold the same values)."""
+    layer = LayerConfig(d_model=256, n_q_heads=8, n_kv_heads=2, head_dim=64, ffn_dim=320, n_experts=16, top_k=4,
+                        rope_theta=500000.0)
+    inp, q4 = build(layer, [9] * 20, 2, seed=5)
+    lay0 = B.Layer(layer, None)
+    w = device_weights(lay0, inp, q4)
+    w16 = {k: v for k, v in w.items() if not k.endswith(("_q", "_s"))}
+    outs = []
+    for ww in (w, w16):
+        lay = B.Layer(layer, ww)
+        kv = B.KVCache(layer, [L + 2 for L in inp.block_lens], DEV, torch.bfloat16)
+        lay.ensure_workspace(inp.cu_seqlens[-1], 20, 16, DEV)
+        y_last = torch.empty(20, 256, dtype=torch.bfloat16, device=DEV)
+        y = torch.empty(2, 20, 256, dtype=torch.bfloat16, device=DEV)
+        lay.compact_layer_forward(inp.cu_seqlens, inp.x_prefill.to(DEV), inp.x_decode.to(DEV).contiguous(), kv, None, y_last, y)
+        torch.cuda.synchronize()
+        outs.append((y.clone(), y_last.clone()))
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
