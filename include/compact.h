@@ -167,7 +167,11 @@ int compact_prefill_extend(compact_ctx* ctx, const compact_weights* w, int32_t n
 /* One batched decode step (the concurrent workers each emitting one summary
  * token): d_x [N, d] holds one new token per block, at rotary position
  * pos_offset[b] + len[b].  Its K/V row is appended at row len[b], it attends
- * rows 0..len[b] inclusive, and h_len[b] is incremented.  Writes d_y [N, d]. */
+ * rows 0..len[b] inclusive, and h_len[b] is incremented.  Writes d_y [N, d].
+ * Calls that come back with the same cache geometry on the same stream, every
+ * block one row longer, reuse the metadata the first of them uploaded (no
+ * host-to-device copy per step); anything else rebuilds it.  The results do
+ * not depend on which of the two happens. */
 int compact_decode_step(compact_ctx* ctx, const compact_weights* w, int32_t n_blocks,
                         const void* d_x, compact_kv* kv, void* d_y,
                         const compact_route_out* route, void* d_workspace, size_t ws_bytes,

@@ -110,11 +110,14 @@ extern "C" int compact_create(const compact_layer_cfg* cfg, compact_ctx** out) {
     return COMPACT_OK;
 }
 
+static void drop_step_cache(compact_ctx* ctx);
+
 extern "C" void compact_destroy(compact_ctx* ctx) {
     if (!ctx) return;
     if (ctx->d_meta) (void)hipFree(ctx->d_meta);
     if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
     if (ctx->stage_event) (void)hipEventDestroy(ctx->stage_event);
+    drop_step_cache(ctx);
     for (auto& e : ctx->prof_events) {
         (void)hipEventDestroy(e.start);
         (void)hipEventDestroy(e.stop);
@@ -275,6 +278,7 @@ struct Plan {
 };
 
 static int upload_plan(compact_ctx* ctx, Plan& p, hipStream_t s) {
+    ++ctx->upload_serial;   // the device views of every earlier plan are gone
     const size_t b0 = align_up(p.meta.size() * sizeof(BlockMeta), 256);
     const size_t b1 = align_up(p.rope_tiles.size() * sizeof(TileItem), 256);
     const size_t b2 = align_up(p.q_tiles.size() * sizeof(TileItem), 256);
@@ -556,6 +560,52 @@ struct PrefixArgs {
     float* records = nullptr;
 };
 
+// Step-by-step callers (compact_decode_step, compact_prefix_decode_step) come back with the same
+// caches one token longer each time.  The plan of the first call is built to cover `headroom`
+// steps and stays on the device; later calls reuse it with step = k instead of building and
+// uploading a new one, as long as nothing else has uploaded metadata in between, the stream and
+// the cache geometry are the same and every block has grown by the same k.
+struct StepCache {
+    bool valid = false;
+    uint64_t serial = 0;             // ctx->upload_serial right after this plan went up
+    std::vector<int64_t> geom;       // everything the plan depends on except the lengths
+    std::vector<int32_t> base_len;   // lengths the plan was built for
+    int headroom = 0;                // steps the uploaded lists cover
+    Plan plan;
+    PrefixArgs pa;
+};
+
+static void drop_step_cache(compact_ctx* ctx) {
+    delete ctx->step_cache;
+    ctx->step_cache = nullptr;
+}
+
+// Steps taken since the cached plan was built, or -1 when it does not cover this call.
+static int step_cache_lookup(const compact_ctx* ctx, const std::vector<int64_t>& geom, const int32_t* h_len, int n) {
+    const StepCache* sc = ctx->step_cache;
+    if (!sc || !sc->valid || sc->serial != ctx->upload_serial || sc->geom != geom) return -1;
+    const int k = h_len[0] - sc->base_len[0];
+    if (k < 0 || k >= sc->headroom) return -1;
+    for (int b = 1; b < n; ++b)
+        if (h_len[b] - sc->base_len[b] != k) return -1;
+    return k;
+}
+
+static StepCache& step_cache_begin(compact_ctx* ctx) {
+    if (!ctx->step_cache) ctx->step_cache = new StepCache;
+    *ctx->step_cache = StepCache();
+    return *ctx->step_cache;
+}
+
+static void step_cache_commit(compact_ctx* ctx, StepCache& sc, std::vector<int64_t>& geom, const int32_t* h_len, int n,
+                              int headroom) {
+    sc.geom.swap(geom);
+    sc.base_len.assign(h_len, h_len + n);
+    sc.headroom = headroom;
+    sc.serial = ctx->upload_serial;
+    sc.valid = true;
+}
+
 // one decode step for all blocks; plan.meta.len = cached tokens before step 0.
 static int decode_impl(compact_ctx* ctx, const compact_weights* w, int n_blocks, int step, const void* x,
                        compact_kv* kv, void* y, const compact_route_out* route, const DecodeBufs& b,
@@ -699,21 +749,38 @@ static int validate_decode(compact_ctx* ctx, const compact_weights* w, int n_blo
     return COMPACT_OK;
 }
 
+// Steps one uploaded decode plan is built to cover (bounded by the room left in the slabs).
+constexpr int STEP_PLAN_HEADROOM = 1024;
+
 extern "C" int compact_decode_step(compact_ctx* ctx, const compact_weights* w, int32_t n_blocks, const void* d_x,
                                    compact_kv* kv, void* d_y, const compact_route_out* route, void* d_workspace,
                                    size_t ws_bytes, void* hip_stream) {
     if (!ctx) return COMPACT_EINVAL;
     TRY(validate_decode(ctx, w, n_blocks, d_x, kv, d_y, d_workspace, 1));
     hipStream_t s = (hipStream_t)hip_stream;
-    Plan plan;
-    build_decode_plan(kv, n_blocks, plan);
-    add_kv_chunks(plan, 1);
+    int max_len = 0, room = STEP_PLAN_HEADROOM;
+    std::vector<int64_t> geom = {0, (int64_t)(intptr_t)s, n_blocks};
+    for (int b = 0; b < n_blocks; ++b) {
+        max_len = std::max(max_len, kv->h_len[b]);
+        room = std::min(room, kv->h_capacity[b] - kv->h_len[b]);
+        geom.push_back(kv->h_capacity[b]);
+        geom.push_back(kv->h_pos_offset ? kv->h_pos_offset[b] : 0);
+        geom.push_back(kv->h_slab_offset[b]);
+    }
     Carver cv(d_workspace);
     DecodeBufs b;
-    carve_decode(cv, ctx->cfg, n_blocks, chunks_for(plan.max_len + 1), b);
+    carve_decode(cv, ctx->cfg, n_blocks, chunks_for(max_len + 1), b);
     if (cv.off > ws_bytes) return set_err(ctx, COMPACT_EWORKSPACE, "workspace too small for this decode step");
-    TRY(upload_plan(ctx, plan, s));
-    TRY(decode_impl(ctx, w, n_blocks, 0, d_x, kv, d_y, route, b, plan, s));
+    int k = step_cache_lookup(ctx, geom, kv->h_len, n_blocks);
+    if (k < 0) {
+        StepCache& sc = step_cache_begin(ctx);
+        build_decode_plan(kv, n_blocks, sc.plan);
+        add_kv_chunks(sc.plan, room);
+        TRY(upload_plan(ctx, sc.plan, s));
+        step_cache_commit(ctx, sc, geom, kv->h_len, n_blocks, room);
+        k = 0;
+    }
+    TRY(decode_impl(ctx, w, n_blocks, k, d_x, kv, d_y, route, b, ctx->step_cache->plan, s));
     for (int b2 = 0; b2 < n_blocks; ++b2) kv->h_len[b2] += 1;
     return COMPACT_OK;
 }
@@ -1177,16 +1244,54 @@ extern "C" int compact_prefix_decode_step(compact_ctx* ctx, const compact_weight
     if (!d_workspace) return set_err(ctx, COMPACT_EWORKSPACE, "null workspace");
     if (!shared || !tails) return set_err(ctx, COMPACT_EINVAL, "null shared or tails");
     hipStream_t s = (hipStream_t)hip_stream;
-    Plan plan;
-    PrefixArgs pa;
-    TRY(build_prefix_plan(ctx, n_workers, shared, h_prefix_len, tails, 1, plan, pa));
+    // a plan built for one step covers every further step that opens no new chunk in any tail
+    // (the record slots, hence the workspace, stay the same) and still fits the slabs
+    int k = -1, room = DECODE_CHUNK;
+    std::vector<int64_t> geom;
+    if (ctx->step_cache && ctx->step_cache->valid && h_prefix_len && n_workers >= 1 && n_workers <= 64 &&
+        shared->d_k && shared->d_v && shared->h_len && shared->h_capacity && shared->h_slab_offset && tails->d_k &&
+        tails->d_v && tails->h_len && tails->h_capacity && tails->h_slab_offset) {
+        geom = {1, (int64_t)(intptr_t)s, n_workers, shared->h_len[0], shared->h_capacity[0], shared->h_slab_offset[0]};
+        for (int b = 0; b < n_workers; ++b) {
+            geom.push_back(h_prefix_len[b]);
+            geom.push_back(tails->h_capacity[b]);
+            geom.push_back(tails->h_slab_offset[b]);
+        }
+        k = step_cache_lookup(ctx, geom, tails->h_len, n_workers);
+    }
+    if (k < 0) {
+        Plan plan;
+        PrefixArgs pa;
+        TRY(build_prefix_plan(ctx, n_workers, shared, h_prefix_len, tails, 1, plan, pa));   // validates everything
+        geom = {1, (int64_t)(intptr_t)s, n_workers, shared->h_len[0], shared->h_capacity[0], shared->h_slab_offset[0]};
+        for (int b = 0; b < n_workers; ++b) {
+            geom.push_back(h_prefix_len[b]);
+            geom.push_back(tails->h_capacity[b]);
+            geom.push_back(tails->h_slab_offset[b]);
+            const int len = tails->h_len[b];
+            room = std::min(room, std::min(tails->h_capacity[b] - len, chunks_for(len + 1) * DECODE_CHUNK - len));
+        }
+        Carver cv(d_workspace);
+        DecodeBufs b;
+        carve_decode(cv, ctx->cfg, n_workers, 1, b);
+        (void)cv.take((size_t)pa.total_recs * ctx->cfg.n_kv_heads * (ctx->cfg.head_dim + 2) * 4);
+        if (cv.off > ws_bytes) return set_err(ctx, COMPACT_EWORKSPACE, "workspace too small for this prefix-aware decode step");
+        StepCache& sc = step_cache_begin(ctx);
+        sc.plan = std::move(plan);
+        sc.pa = std::move(pa);
+        TRY(upload_plan(ctx, sc.plan, s));
+        step_cache_commit(ctx, sc, geom, tails->h_len, n_workers, room);
+        k = 0;
+    }
+    StepCache& sc = *ctx->step_cache;
     Carver cv(d_workspace);
     DecodeBufs b;
     carve_decode(cv, ctx->cfg, n_workers, 1, b);
-    pa.records = (float*)cv.take((size_t)pa.total_recs * ctx->cfg.n_kv_heads * (ctx->cfg.head_dim + 2) * 4);
+    sc.pa.records = (float*)cv.take((size_t)sc.pa.total_recs * ctx->cfg.n_kv_heads * (ctx->cfg.head_dim + 2) * 4);
     if (cv.off > ws_bytes) return set_err(ctx, COMPACT_EWORKSPACE, "workspace too small for this prefix-aware decode step");
-    TRY(upload_plan(ctx, plan, s));
-    TRY(decode_impl(ctx, w, n_workers, 0, d_x, tails, d_y, route, b, plan, s, &pa));
+    sc.pa.d_k = shared->d_k;
+    sc.pa.d_v = shared->d_v;
+    TRY(decode_impl(ctx, w, n_workers, k, d_x, tails, d_y, route, b, sc.plan, s, &sc.pa));
     for (int b2 = 0; b2 < n_workers; ++b2) tails->h_len[b2] += 1;
     return COMPACT_OK;
 }

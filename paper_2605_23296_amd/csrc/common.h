@@ -69,6 +69,8 @@ struct compact_ctx {
     hipEvent_t stage_event = nullptr;
     bool stage_pending = false;
     size_t meta_bytes = 0;
+    uint64_t upload_serial = 0;          // counts metadata uploads: whoever cached device views checks it
+    struct StepCache* step_cache = nullptr;   // plan kept between step-by-step decode calls (owned; see api.hip)
     // profiling
     int profile_class = COMPACT_K_NONE;
     std::vector<ProfileSlot> prof_events;
