@@ -150,6 +150,24 @@ def test_prefill_attention_bf16_hd64_group_of_8():
     attention_case(small, [200, 1, 77, 513], seed=12)
 
 
+def test_prefill_attention_bf16_odd_gqa_group_takes_the_one_head_per_workgroup_kernel():
+    # the two-heads-per-workgroup kernel needs an even GQA group; 3 query heads per KV head and plain
+    # multi-head attention (group of 1) run the four-wavefront kernel at head_dim 128
+    g3 = copy.deepcopy(DENSE)
+    g3.n_q_heads, g3.n_kv_heads = 6, 2
+    attention_case(g3, [1, 64, 129, 300, 385], seed=14, pos_offset=[0, 5, 0, 900, 3])
+    mha = copy.deepcopy(DENSE)
+    mha.n_q_heads, mha.n_kv_heads = 3, 3
+    attention_case(mha, [65, 200], seed=15)
+
+
+def test_prefill_attention_bf16_two_heads_per_workgroup_long_block():
+    # long enough for the four-stage K/V ring to wrap several times (34 tiles), ragged last tile
+    two = copy.deepcopy(DENSE)
+    two.n_q_heads, two.n_kv_heads = 4, 2
+    attention_case(two, [2150, 130], seed=16)
+
+
 def test_prefill_attention_fp32():
     l2 = fp32_variant(DENSE)
     l2.n_q_heads, l2.n_kv_heads = 8, 2
