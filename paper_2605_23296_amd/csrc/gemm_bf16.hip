@@ -187,13 +187,17 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmParams
             for (int j = 0; j < TN; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], xf[i], acc[i][j], 0, 0, 0);
     };
-    // Pins the instruction order of one k-step: the LDS reads of the next k-step's
-    // fragments go out two per MFMA at the start of the group (the last of them
-    // still has most of the group to land), then the global loads one per MFMA.
+    // Pins the instruction order of one k-step: one MFMA first, then the LDS reads of
+    // the next k-step's fragments two per MFMA (the last of them still has most of
+    // the group to land), then the global loads one per MFMA.  The MFMA goes first
+    // because its wait for this k-step's fragments comes out as "all LDS reads done"
+    // (while loads that write LDS are in flight the compiler cannot wait for fewer):
+    // placed behind the first reads of the next fragments it would wait for those too.
     constexpr int NRD = TM + TN, NMF = TM * TN;
-    static_assert(NRD % 2 == 0 && NMF >= NRD / 2 + NLD, "k-step shape not covered by the pinned order");
+    static_assert(NRD % 2 == 0 && NMF >= NRD / 2 + NLD + 1, "k-step shape not covered by the pinned order");
     auto pin_order = [&](auto n_loads_tag) {
         constexpr int n_loads = decltype(n_loads_tag)::value;
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
 #pragma unroll
         for (int i = 0; i < NRD / 2; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // two LDS reads
@@ -204,7 +208,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmParams
             __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // one global load
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, NMF - NRD / 2 - n_loads, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, NMF - 1 - NRD / 2 - n_loads, 0);
         __builtin_amdgcn_sched_barrier(0);
     };
 
