@@ -328,7 +328,7 @@ def main():
                          "used to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (blocks are independent; sharding is a design note, "
+        print("bench.py: the library runs on ONE GPU (blocks are independent; sharding across GPUs is a design note, "
               "not code). Re-run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
     if not torch.cuda.is_available():
