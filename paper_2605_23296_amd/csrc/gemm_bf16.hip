@@ -27,7 +27,7 @@
 #include "common.h"
 
 #define GEMM_BK 32       // k-tile
-#define GEMM_STAGES 4   // LDS ring
+#define GEMM_STAGES 5   // LDS ring (5 x 32 KB = the whole LDS of a CU)
 
 struct GemmParams {
     const bf16* X;
@@ -61,7 +61,7 @@ __device__ __forceinline__ void ring_barrier() {
 
 template <int BM, int BN, int WM, int WN, int EPI, bool GROUPED>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmParams p) {
-    constexpr int NT = WM * WN * 64, BK = GEMM_BK, NSTAGE = GEMM_STAGES, AHEAD = NSTAGE - 1;
+    constexpr int NT = WM * WN * 64, BK = GEMM_BK, NSTAGE = GEMM_STAGES;
     constexpr int WTM = BM / WM, WTN = BN / WN, TM = WTM / 32, TN = WTN / 32;
     constexpr int STAGE = (BM + BN) * BK;  // elements
     constexpr int OUTN = EPI == 1 ? BN / 2 : BN;
@@ -157,21 +157,32 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmParams
     const int sw = (r >> 2) & 3;
     const int nk = p.K / BK;
 
-    // Software pipeline over k-tiles of 32 (two MFMA k-steps).  At the top of
-    // k-tile kt the loads of k-tile kt+3 go out, into the stage whose last readers
-    // passed the previous barrier; the barrier in the middle of the k-tile follows
-    // a wait for this wave's loads of k-tile kt+1 only (the newer two stay in
-    // flight).  MFMA fragments are double-buffered in registers, so the LDS reads
-    // of one k-step run under the MFMAs of the one before.  Past the end of K the
-    // last k-tile is loaded again (into stages nobody reads) rather than branching:
-    // the k-steps stay one basic block each, which the pinned order below needs.
+    // Software pipeline over k-tiles of 32 (two MFMA k-steps), five LDS stages.  A k-tile row is 64
+    // bytes, half a cache line, so the loads go out for TWO k-tiles at a time, the two halves of every
+    // line in adjacent instructions (the second request meets the first one's line in the vector cache
+    // instead of fetching it from L2 again; issued one k-tile apart, every line crossed the L2-to-CU path
+    // twice and that path, not the matrix pipe, set the pace).  Pairs (T, T+1), T even, go out during k-tile
+    // T-3, half of the wave's 16-row units in each of its two k-steps; the barrier in the middle of a
+    // k-tile follows a wait for this wave's loads of the NEXT k-tile only (the newer ones stay in
+    // flight).  MFMA fragments are double-buffered in registers, so the LDS reads of one k-step run
+    // under the MFMAs of the one before.  Past the end of K the last k-tile is loaded again (into
+    // stages nobody reads) rather than branching.
     constexpr int NLD = XU + WU;
+    static_assert(XU % 2 == 0 && WU % 2 == 0, "the units of a tile are dealt to the two k-steps of an iteration");
     const int swave = __builtin_amdgcn_readfirstlane(wave);   // wave-uniform: LDS bases stay scalar
-    auto gload = [&](int kt, bf16* stage) {
+    // units [half * XU/2, ..) and [half * WU/2, ..) of k-tiles t0 (stage s0) and t0 + 1 (stage s1)
+    auto gload_pair = [&](int t0, bf16* s0, bf16* s1, int half) {
+        const int k0 = min(t0, nk - 1) * BK, k1 = min(t0 + 1, nk - 1) * BK;
 #pragma unroll
-        for (int i = 0; i < XU; ++i) load16_to_lds(xptr[i] + kt * BK, stage + (swave * XU + i) * 16 * BK);
+        for (int i = half * (XU / 2); i < (half + 1) * (XU / 2); ++i) {
+            load16_to_lds(xptr[i] + k0, s0 + (swave * XU + i) * 16 * BK);
+            load16_to_lds(xptr[i] + k1, s1 + (swave * XU + i) * 16 * BK);
+        }
 #pragma unroll
-        for (int i = 0; i < WU; ++i) load16_to_lds(wptr[i] + kt * BK, stage + BM * BK + (swave * WU + i) * 16 * BK);
+        for (int i = half * (WU / 2); i < (half + 1) * (WU / 2); ++i) {
+            load16_to_lds(wptr[i] + k0, s0 + BM * BK + (swave * WU + i) * 16 * BK);
+            load16_to_lds(wptr[i] + k1, s1 + BM * BK + (swave * WU + i) * 16 * BK);
+        }
     };
     auto frags = [&](const bf16* stage, int kk, bf16x8 (&xf)[TM], bf16x8 (&wf)[TN]) {
         const int ch = ((2 * kk + h) ^ sw) << 3;
@@ -212,27 +223,48 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(const GemmParams
         __builtin_amdgcn_sched_barrier(0);
     };
 
-#pragma unroll
-    for (int t0 = 0; t0 < AHEAD; ++t0) gload(min(t0, nk - 1), lds + t0 * STAGE);
-    ring_barrier<(AHEAD - 1) * NLD>();
+    // prologue: pairs (0, 1) and (2, 3); k-tile 0 has landed when all but the last load of the first pair have
+    gload_pair(0, lds, lds + STAGE, 0);
+    gload_pair(0, lds, lds + STAGE, 1);
+    gload_pair(2, lds + 2 * STAGE, lds + 3 * STAGE, 0);
+    gload_pair(2, lds + 2 * STAGE, lds + 3 * STAGE, 1);
+    ring_barrier<2 * NLD + 1>();
     bf16x8 xfA[TM], wfA[TN], xfB[TM], wfB[TN];
     frags(lds, 0, xfA, wfA);
     __builtin_amdgcn_sched_barrier(0);
 
-    for (int kt = 0; kt < nk; ++kt) {
-        const bf16* cur = lds + (kt % NSTAGE) * STAGE;
-        const bf16* nxt = lds + ((kt + 1) % NSTAGE) * STAGE;
-        bf16* fill = lds + ((kt + AHEAD) % NSTAGE) * STAGE;
-        // k-step 0: fragments of k-step 1, loads of k-tile kt + 3
-        frags(cur, 1, xfB, wfB);
-        gload(min(kt + AHEAD, nk - 1), fill);
+    auto stage_of = [&](int st) { return lds + st * STAGE; };
+    auto wrap = [](int st) { return st >= NSTAGE ? st - NSTAGE : st; };
+    int sc = 0;   // stage of k-tile kt
+    int kt = 0;
+    for (; kt + 1 < nk; kt += 2) {
+        // ---- even k-tile kt: no loads ------------------------------------------------------------
+        frags(stage_of(sc), 1, xfB, wfB);
         mfmas(xfA, wfA);
-        pin_order(std::integral_constant<int, NLD>{});
-        // k-step 1: k-tile kt + 1 has landed for everyone; its first fragments
-        ring_barrier<(AHEAD - 1) * NLD>();
-        frags(nxt, 0, xfA, wfA);
+        pin_order(std::integral_constant<int, 0>{});
+        ring_barrier<2 * NLD>();   // k-tile kt + 1 (second half of its pair) has landed; pair (kt+2, kt+3) may fly
+        frags(stage_of(wrap(sc + 1)), 0, xfA, wfA);
         mfmas(xfB, wfB);
         pin_order(std::integral_constant<int, 0>{});
+        // ---- odd k-tile kt + 1: the loads of pair (kt + 4, kt + 5), into the stages of k-tiles kt - 1 and kt ----
+        bf16* f0 = stage_of(wrap(sc + 4));
+        bf16* f1 = stage_of(sc);
+        frags(stage_of(wrap(sc + 1)), 1, xfB, wfB);
+        gload_pair(kt + 4, f0, f1, 0);
+        mfmas(xfA, wfA);
+        pin_order(std::integral_constant<int, NLD>{});
+        // k-tile kt + 2 = first halves of pair (kt+2, kt+3): all but that pair's last load, and not the NLD just issued
+        ring_barrier<NLD + 1>();
+        frags(stage_of(wrap(sc + 2)), 0, xfA, wfA);
+        gload_pair(kt + 4, f0, f1, 1);
+        mfmas(xfB, wfB);
+        pin_order(std::integral_constant<int, NLD>{});
+        sc = wrap(sc + 2);
+    }
+    if (kt < nk) {   // odd number of k-tiles: the last one on its own
+        frags(stage_of(sc), 1, xfB, wfB);
+        mfmas(xfA, wfA);
+        mfmas(xfB, wfB);
     }
     wait_all_memory();   // the repeated loads of the last k-tile must not land in the epilogue's slabs
     __syncthreads();
