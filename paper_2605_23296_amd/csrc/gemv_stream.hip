@@ -102,7 +102,7 @@ int launch_resid_norm_stream(compact_ctx* ctx, const bf16* X, const bf16* W, con
 // One tile per workgroup, any K that is a multiple of 512: weight and
 // activation fragments travel through a ring of GS_RING loads per wavefront.
 // ---------------------------------------------------------------------------
-#define GS_RING 7
+#define GS_RING 14
 __global__ __launch_bounds__(GS_WAVES * 64) void resid_out_stream_kernel(const bf16* __restrict__ X, const bf16* __restrict__ W,
                                                                           const float* __restrict__ resid, bf16* __restrict__ y,
                                                                           int M, int N, int K) {
