@@ -199,26 +199,38 @@ class Layer:
         return rope(q, pos, self.theta), rope(k, pos, self.theta), v
 
     # -- feed-forward half --------------------------------------------------
-    def ffn(self, h):
-        """Second RMSNorm, feed-forward, residual.  Returns (y, idx, gate, router logits)."""
+    def ffn(self, h, forced_idx=None):
+        """Second RMSNorm, feed-forward, residual.  Returns (y, idx, gate, router logits).
+
+        forced_idx [R, k] (routed layers only) replaces the top-k selection: row r
+        is sent to exactly those experts, gated by the softmax over ITS logits at
+        those experts.  The parity tests use it where two experts' logits are
+        closer than the storage rounding of the path under test, so that both
+        choices are correct: the layer is then evaluated for the choice made.
+        """
         m = rmsnorm(h, self.w["g_ffn"], self.eps)
         if self.E == 0:
             F = self.F
             wgu = self.w["w_gate_up"]
             return h + swiglu_ffn(m, wgu[:F], wgu[F:], self.w["w_down"]), None, None, None
         logits = router_logits(m, self.w["w_router"])
-        idx, gate = topk_route(logits, self.k)
+        if forced_idx is None:
+            idx, gate = topk_route(logits, self.k)
+        else:
+            idx = np.asarray(forced_idx, dtype=np.int32).reshape(logits.shape[0], self.k)
+            gate = softmax_rows(np.take_along_axis(logits, idx.astype(np.int64), axis=-1))
         y = h + moe_ffn(m, idx, gate, self.w["w_exp_gate_up"], self.w["w_exp_down"])
         return y, idx, gate, logits
 
     # -- one block ----------------------------------------------------------
-    def prefill_block(self, x, pos0=0, rows=None):
+    def prefill_block(self, x, pos0=0, rows=None, forced_idx=None):
         """Causal forward over one block's own L tokens.
 
         x [L, d].  Positions are pos0 .. pos0+L-1.  K and V are produced for
         every token; attention and everything after it are evaluated for the
         query rows in `rows` (default: all).  Returns dict with y [R, d],
-        K, V [L, Hkv, hd] (K after rotation), rows, idx, gate.
+        K, V [L, Hkv, hd] (K after rotation), rows, idx, gate, logits and h (the
+        rows after the attention half).  forced_idx [R, k]: see ffn.
         """
         x = _f64(x)
         L = x.shape[0]
@@ -227,10 +239,10 @@ class Layer:
         rows = np.arange(L) if rows is None else np.asarray(rows, dtype=np.int64)
         o = gqa_attention(q[rows], k, v, visible=rows + 1)     # row i sees j <= i
         h = x[rows] + o.reshape(len(rows), self.Dq) @ _f64(self.w["w_o"]).T
-        y, idx, gate, logits = self.ffn(h)
-        return dict(y=y, K=k, V=v, rows=rows, idx=idx, gate=gate, logits=logits)
+        y, idx, gate, logits = self.ffn(h, forced_idx)
+        return dict(y=y, K=k, V=v, rows=rows, idx=idx, gate=gate, logits=logits, h=h)
 
-    def decode_block(self, x, K, V, pos0=0):
+    def decode_block(self, x, K, V, pos0=0, forced_idx=None):
         """One new token for one block whose cache holds len = K.shape[0] rows.
 
         The token sits at position pos0 + len, its K/V row is appended, and it
@@ -244,13 +256,13 @@ class Layer:
         V = np.concatenate([V, v], axis=0)
         o = gqa_attention(q, K, V, visible=np.array([n_cached + 1]))
         h = x + o.reshape(1, self.Dq) @ _f64(self.w["w_o"]).T
-        y, idx, gate, logits = self.ffn(h)
-        return dict(y=y[0], K=K, V=V,
+        y, idx, gate, logits = self.ffn(h, forced_idx)
+        return dict(y=y[0], K=K, V=V, h=h[0],
                     idx=None if idx is None else idx[0],
                     gate=None if gate is None else gate[0],
                     logits=None if logits is None else logits[0])
 
-    def extend_block(self, x, K, V, pos0=0, rows=None):
+    def extend_block(self, x, K, V, pos0=0, rows=None, forced_idx=None):
         """The next chunk of a block whose cache already holds len = K.shape[0]
         rows (a prefill cut into chunks, Sec. IV-B: the server prefills long
         prompts chunk by chunk; also a worker's own block behind a cached prefix).
@@ -268,34 +280,39 @@ class Layer:
         rows = np.arange(C) if rows is None else np.asarray(rows, dtype=np.int64)
         o = gqa_attention(q[rows], K, V, visible=n_cached + rows + 1)
         h = x[rows] + o.reshape(len(rows), self.Dq) @ _f64(self.w["w_o"]).T
-        y, idx, gate, logits = self.ffn(h)
-        return dict(y=y, K=K, V=V, rows=rows, idx=idx, gate=gate, logits=logits)
+        y, idx, gate, logits = self.ffn(h, forced_idx)
+        return dict(y=y, K=K, V=V, rows=rows, idx=idx, gate=gate, logits=logits, h=h)
 
     # -- the batch of blocks ------------------------------------------------
-    def prefill(self, x, cu_seqlens, pos_offset=None, rows=None):
+    def prefill(self, x, cu_seqlens, pos_offset=None, rows=None, forced_idx=None):
         """Block b = rows cu[b]..cu[b+1]-1 of the packed x [T, d]; blocks are
         independent.  rows: optional list (per block) of block-local query rows.
+        forced_idx: optional list (per block) of [R_b, k] expert choices (see ffn).
         Returns one prefill_block dict per block, in block order."""
         out = []
         for b in range(len(cu_seqlens) - 1):
             xb = x[cu_seqlens[b]:cu_seqlens[b + 1]]
             out.append(self.prefill_block(
                 xb, 0 if pos_offset is None else int(pos_offset[b]),
-                None if rows is None else rows[b]))
+                None if rows is None else rows[b],
+                None if forced_idx is None else forced_idx[b]))
         return out
 
-    def decode_step(self, x, Ks, Vs, pos_offset=None):
-        """x [N, d]: one token per block, each against its own cache."""
+    def decode_step(self, x, Ks, Vs, pos_offset=None, forced_idx=None):
+        """x [N, d]: one token per block, each against its own cache.
+        forced_idx: optional [N, k] expert choices (see ffn)."""
         out = []
         for b in range(len(Ks)):
             out.append(self.decode_block(
-                x[b], Ks[b], Vs[b], 0 if pos_offset is None else int(pos_offset[b])))
+                x[b], Ks[b], Vs[b], 0 if pos_offset is None else int(pos_offset[b]),
+                None if forced_idx is None else forced_idx[b]))
         return out
 
     def forward(self, x_prefill, cu_seqlens, x_decode, pos_offset=None, rows=None):
         """Prefill of every block, then S batched decode steps with the given
         step inputs x_decode [S, N, d].  Returns (prefill dicts, y_decode
-        [S, N, d], final K list, final V list, decode routing list)."""
+        [S, N, d], final K list, final V list, per step and block the tuple
+        (idx, gate, router logits, h))."""
         pre = self.prefill(x_prefill, cu_seqlens, pos_offset, rows)
         Ks = [p["K"] for p in pre]
         Vs = [p["V"] for p in pre]
@@ -308,11 +325,11 @@ class Layer:
             for b in range(N):
                 y_dec[s, b] = st[b]["y"]
                 Ks[b], Vs[b] = st[b]["K"], st[b]["V"]
-            routes.append([(st[b]["idx"], st[b]["gate"], st[b]["logits"]) for b in range(N)])
+            routes.append([(st[b]["idx"], st[b]["gate"], st[b]["logits"], st[b]["h"]) for b in range(N)])
         return pre, y_dec, Ks, Vs, routes
 
     # -- prefix-aware layout ------------------------------------------------
-    def decode_block_prefix(self, x, Kp, Vp, prefix_len, Kt, Vt):
+    def decode_block_prefix(self, x, Kp, Vp, prefix_len, Kt, Vt, forced_idx=None):
         """One new token of worker k in the prefix-aware target-at-end layout
         (paper Sec. IV, Dispatch: worker k's prompt is blocks 1..k in order, so
         every worker's prefix extends the previous one's and its cache is
@@ -330,8 +347,8 @@ class Layer:
         V = np.concatenate([Vp[:prefix_len], Vt], axis=0)
         o = gqa_attention(q, K, V, visible=np.array([K.shape[0]]))
         h = x + o.reshape(1, self.Dq) @ _f64(self.w["w_o"]).T
-        y, idx, gate, logits = self.ffn(h)
-        return dict(y=y[0], Kt=Kt, Vt=Vt,
+        y, idx, gate, logits = self.ffn(h, forced_idx)
+        return dict(y=y[0], Kt=Kt, Vt=Vt, h=h[0],
                     idx=None if idx is None else idx[0],
                     gate=None if gate is None else gate[0],
                     logits=None if logits is None else logits[0])
@@ -365,7 +382,7 @@ class Layer:
         attention + feed-forward are then evaluated for the prefill query rows
         `rows[b]` and for the decode steps in `steps` (step s of block b sees
         cache rows 0 .. L_b + s).  Returns (prefill dicts, {s: y [N, d]},
-        K list, V list, {s: (idx, gate, logits)})."""
+        K list, V list, {s: (idx, gate, logits, h)})."""
         pre = self.prefill(x_prefill, cu_seqlens, pos_offset, rows)
         S, N = x_decode.shape[0], len(pre)
         Ks, Vs, qs = [], [], []
@@ -384,7 +401,7 @@ class Layer:
             h = _f64(x_decode[s]) + o.reshape(N, self.Dq) @ _f64(self.w["w_o"]).T
             y, idx, gate, logits = self.ffn(h)
             y_dec[s] = y
-            routes[s] = (idx, gate, logits)
+            routes[s] = (idx, gate, logits, h)
         return pre, y_dec, Ks, Vs, routes
 
 
@@ -400,14 +417,22 @@ class Stack:
         """weights: one weight dict per layer."""
         self.layers = [Layer(cfg, w) for w in weights]
 
-    def forward(self, x_prefill, cu_seqlens, x_decode, pos_offset=None):
+    def forward(self, x_prefill, cu_seqlens, x_decode, pos_offset=None, forced=None):
         """Returns (y_prefill [T, d] of the last layer, y_decode [S, N, d] of the
-        last layer, per-layer K lists, per-layer V lists)."""
+        last layer, per-layer K lists, per-layer V lists).  forced (routed layers):
+        per layer a pair (packed [T, k] prefill expert choices, [S, N, k] decode
+        ones), see Layer.ffn; self.routes then holds per layer the router logits
+        (packed [T, E] prefill, [S, N, E] decode) of the pass."""
         x = _f64(x_prefill)
         N = len(cu_seqlens) - 1
         Ks, Vs = [], []
-        for lay in self.layers:
-            pre = lay.prefill(x, cu_seqlens, pos_offset)
+        self.routes = []
+        for li, lay in enumerate(self.layers):
+            fi = None if forced is None else [forced[li][0][cu_seqlens[b]:cu_seqlens[b + 1]] for b in range(N)]
+            pre = lay.prefill(x, cu_seqlens, pos_offset, forced_idx=fi)
+            self.routes.append(dict(pre_logits=None if lay.E == 0 else np.concatenate([p["logits"] for p in pre]),
+                                    pre_idx=None if lay.E == 0 else np.concatenate([p["idx"] for p in pre]),
+                                    dec_logits=[], dec_idx=[]))
             Ks.append([p["K"] for p in pre])
             Vs.append([p["V"] for p in pre])
             x = np.concatenate([p["y"] for p in pre], axis=0)
@@ -417,9 +442,13 @@ class Stack:
         for s in range(S):
             xs = _f64(x_decode[s])
             for li, lay in enumerate(self.layers):
-                st = lay.decode_step(xs, Ks[li], Vs[li], pos_offset)
+                st = lay.decode_step(xs, Ks[li], Vs[li], pos_offset,
+                                     None if forced is None else forced[li][1][s])
                 for b in range(N):
                     Ks[li][b], Vs[li][b] = st[b]["K"], st[b]["V"]
+                if lay.E:
+                    self.routes[li]["dec_logits"].append(np.stack([st[b]["logits"] for b in range(N)]))
+                    self.routes[li]["dec_idx"].append(np.stack([st[b]["idx"] for b in range(N)]))
                 xs = np.stack([st[b]["y"] for b in range(N)])
             y_dec[s] = xs
         return y_pre, y_dec, Ks, Vs

@@ -192,7 +192,9 @@ static void carve_prefill(Carver& cv, const compact_layer_cfg& c, int64_t T, Pre
     const size_t es = dtype_size(c.dtype);
     const size_t ld = (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
     b.n = cv.take((size_t)T * c.d_model * es);  // reused for m
-    b.qkv = cv.take((size_t)T * ld * es);
+    // at least d_model columns per row: a forward pass whose caller wants no prefill output
+    // writes the [T, d_model] result of the feed-forward half over this scratch, dead by then
+    b.qkv = cv.take((size_t)T * std::max(ld, (size_t)c.d_model) * es);
     b.o = cv.take((size_t)T * c.n_q_heads * c.head_dim * es);
     b.h = cv.take((size_t)T * c.d_model * 4);  // the residual stream between the two halves stays fp32
     if (c.n_experts == 0) {
@@ -807,7 +809,8 @@ extern "C" int compact_layer_forward(compact_ctx* ctx, const compact_weights* w,
     size_t off = align_up(cp.off, 256);
     void* y_pre = d_y_prefill;
     if (!y_pre) {
-        // the FFN output may overwrite the attention scratch that is dead by then
+        // the FFN output may overwrite the attention scratch that is dead by then (carve_prefill
+        // gives it max(Dq + 2 Dkv, d_model) columns per row, so [T, d_model] fits)
         y_pre = pb.qkv;
     }
     Carver cd(d_workspace ? (char*)d_workspace + off : nullptr);

@@ -187,19 +187,30 @@ def make_inputs(wl, device="cpu", gen_device=None, block_lens=None, decode_steps
                   meta=dict(workload=wl.name, seed=wl.seed, gen_device=str(gen_device)))
 
 
-def make_mxfp4_experts(layer, gen, device="cpu"):
+def make_mxfp4_experts(layer, gen, device="cpu", scale_spread=0):
     """Random block-scaled 4-bit expert weights (drawn, not quantised from anything):
     uniform 4-bit codes, two per byte, and one scale byte per 32 elements drawn from
     {119, 120} (2^-8, 2^-7), which puts the weights' rms near the 0.02 of the 16-bit
     workloads.  Returns uint8 tensors w_exp_gate_up_q [E, 2F, d/2], w_exp_gate_up_s
-    [E, 2F, d/32], w_exp_down_q [E, d, F/2], w_exp_down_s [E, d, F/32]."""
+    [E, 2F, d/32], w_exp_down_q [E, d, F/2], w_exp_down_s [E, d, F/32].
+
+    scale_spread = s > 0 spreads the scale bytes over a wide range while every expert's
+    output stays O(1): expert e's gate/up scales are shifted by t_e (evenly spaced over
+    -s .. s) and drawn from a window of four bytes, its down scales by -2 t_e (the SwiGLU
+    intermediate is quadratic in the gate/up scale where silu is linear or the identity)."""
     E, d, F = layer.n_experts, layer.d_model, layer.ffn_dim
 
     def draw(shape, lo, hi):
         return torch.randint(lo, hi, shape, generator=gen, device=gen.device, dtype=torch.uint8).to(device)
 
-    return dict(w_exp_gate_up_q=draw((E, 2 * F, d // 2), 0, 256), w_exp_gate_up_s=draw((E, 2 * F, d // 32), 119, 121),
-                w_exp_down_q=draw((E, d, F // 2), 0, 256), w_exp_down_s=draw((E, d, F // 32), 119, 121))
+    if not scale_spread:
+        return dict(w_exp_gate_up_q=draw((E, 2 * F, d // 2), 0, 256), w_exp_gate_up_s=draw((E, 2 * F, d // 32), 119, 121),
+                    w_exp_down_q=draw((E, d, F // 2), 0, 256), w_exp_down_s=draw((E, d, F // 32), 119, 121))
+    t = torch.linspace(-scale_spread, scale_spread, E).round().to(torch.int32).view(E, 1, 1).to(device)
+    gu_s = (draw((E, 2 * F, d // 32), 118, 122).to(torch.int32) + t).to(torch.uint8)
+    dn_s = (draw((E, d, F // 32), 118, 122).to(torch.int32) - 2 * t).to(torch.uint8)
+    return dict(w_exp_gate_up_q=draw((E, 2 * F, d // 2), 0, 256), w_exp_gate_up_s=gu_s,
+                w_exp_down_q=draw((E, d, F // 2), 0, 256), w_exp_down_s=dn_s)
 
 
 def make_stack_weights(wl, n_layers, device="cpu", gen_device=None, gain_jitter=False):

@@ -85,24 +85,60 @@ def gpu_forward_steps(inp, device="cuda", pos_offset=None):
         out["idx_prefill"] = route[0].cpu().numpy()
         out["gate_prefill"] = route[1].cpu().numpy()
         out["idx_decode"] = [r[0].cpu().numpy() for r in droutes]
+        out["gate_decode"] = [r[1].cpu().numpy() for r in droutes]
     return out
 
 
-def routed_rows_match(idx_gpu, idx_ref, logits_ref, k, margin_rel):
-    """Which rows can be compared value by value in a routed layer.
+def check_routing(idx_gpu, logits_ref, k, margin_rel, gate_gpu=None):
+    """Checks the routing table of a routed layer against the checker's logits, row by row.
 
     The GPU routes from its own (storage-rounded) activations, the checker from
-    unrounded fp64 ones, so calls closer than the rounding noise may
-    legitimately differ.  A row is `safe` when the checker's k-th and (k+1)-th
-    logits are further apart than margin; there the expert SETS must agree.
-    On the other rows every expert the GPU picked must lie within margin of
-    the checker's k-th logit.  Returns (safe mask, n_rows_not_safe)."""
-    srt = -np.sort(-logits_ref, axis=-1)
+    unrounded fp64 ones, so two experts whose logits are closer than `margin`
+    (margin_rel * max|logit|: a bound on that rounding noise) may legitimately
+    swap.  Hence, per row:
+      * the GPU's k experts are distinct and each one's checker logit is within
+        margin of the checker's k-th largest (a valid choice);
+      * if the k-th and (k+1)-th logits are further apart than margin, the
+        expert SET is the checker's;
+      * if moreover all gaps inside the top k exceed margin, the ORDER is too;
+      * the gates are the softmax over the chosen logits (within margin).
+    Returns the number of rows whose set was not forced by the margin.  Values
+    are compared afterwards for EVERY row, with the checker's feed-forward
+    evaluated for the GPU's (validated) choice."""
+    idx_gpu = np.asarray(idx_gpu).reshape(-1, k)
+    logits_ref = np.asarray(logits_ref).reshape(idx_gpu.shape[0], -1)
+    order = np.argsort(-logits_ref, axis=-1, kind="stable")
+    srt = np.take_along_axis(logits_ref, order, axis=-1)
     margin = margin_rel * np.abs(logits_ref).max()
-    safe = (srt[:, k - 1] - srt[:, k]) > margin
-    same = np.array([set(a) == set(b) for a, b in zip(idx_gpu, idx_ref)])
-    assert np.all(same[safe]), "expert sets differ on rows with a clear margin"
-    for r in np.nonzero(~safe)[0]:
-        assert len(set(idx_gpu[r])) == k
-        assert np.all(logits_ref[r, idx_gpu[r]] >= srt[r, k - 1] - margin)
-    return safe & same, int(np.sum(~safe))
+    gaps = srt[:, :k] - srt[:, 1:k + 1]                    # gap j: between the j-th and (j+1)-th largest
+    set_safe = gaps[:, k - 1] > margin
+    order_safe = np.all(gaps > margin, axis=1)
+    chosen = np.take_along_axis(logits_ref, idx_gpu.astype(np.int64), axis=-1)
+    for r in range(idx_gpu.shape[0]):
+        assert len(set(idx_gpu[r].tolist())) == k, ("repeated expert", r, idx_gpu[r])
+        assert np.all((idx_gpu[r] >= 0) & (idx_gpu[r] < logits_ref.shape[1]))
+        assert np.all(chosen[r] >= srt[r, k - 1] - margin), ("expert outside the margin", r, idx_gpu[r], order[r, :k + 1])
+        if set_safe[r]:
+            assert set(idx_gpu[r].tolist()) == set(order[r, :k].tolist()), ("expert set", r, idx_gpu[r], order[r, :k])
+        if order_safe[r]:
+            assert np.array_equal(idx_gpu[r], order[r, :k]), ("expert order", r, idx_gpu[r], order[r, :k])
+    if gate_gpu is not None:
+        e = np.exp(chosen - chosen.max(-1, keepdims=True))
+        want = e / e.sum(-1, keepdims=True)
+        got = np.asarray(gate_gpu, dtype=np.float64).reshape(want.shape)
+        assert np.abs(got.sum(-1) - 1).max() < 1e-5
+        assert np.abs(got - want).max() <= max(margin, 1e-6), np.abs(got - want).max()
+    return int(np.sum(~set_safe))
+
+
+def routing_candidates(logits_row, k, margin):
+    """Every expert set that is a valid top-k choice for one row when logits closer than
+    margin may swap: the experts clearly above the k-th logit, completed by every
+    combination of those within margin of it.  For entry points that do not report
+    their routing tables."""
+    import itertools
+    order = np.argsort(-logits_row, kind="stable")
+    kth = logits_row[order[k - 1]]
+    sure = [int(e) for e in order if logits_row[e] > kth + margin]
+    maybe = [int(e) for e in order if abs(logits_row[e] - kth) <= margin]
+    return [sure + list(c) for c in itertools.combinations(maybe, k - len(sure))]

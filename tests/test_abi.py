@@ -62,6 +62,20 @@ def test_workspace_bytes_grows_with_the_problem():
     assert e.value.code == 1
 
 
+def test_workspace_holds_a_model_width_row_where_the_projection_rows_are_narrower():
+    """A layer whose stacked q/k/v rows are narrower than d_model: the attention scratch must
+    still hold [T, d_model] (a forward pass without a prefill output buffer puts the feed-forward
+    result there), so the workspace grows with d_model like that of a layer with wide rows."""
+    T = 4096
+    narrow = LayerConfig(d_model=1024, n_q_heads=4, n_kv_heads=4, head_dim=64, ffn_dim=1024, dtype="bf16")   # 768 columns
+    wide = LayerConfig(d_model=1024, n_q_heads=8, n_kv_heads=4, head_dim=64, ffn_dim=1024, dtype="bf16")     # 1024 columns
+    a = B.Layer(narrow, None).workspace_bytes(T, 4, 64) - B.Layer(narrow, None).workspace_bytes(0, 4, 64)
+    b = B.Layer(wide, None).workspace_bytes(T, 4, 64) - B.Layer(wide, None).workspace_bytes(0, 4, 64)
+    # per token: n (d) + scratch (max(cols, d)) + o (Dq) + h (fp32 d) + act (F): only o differs
+    assert b - a == T * 2 * (8 - 4) * 64
+    assert a >= T * (2 * 1024 + 2 * 1024 + 2 * 256 + 4 * 1024 + 2 * 1024)
+
+
 def _fake_layer(name="tiny_fp32"):
     layer = WORKLOADS[name].layer
 

@@ -8,7 +8,10 @@ blocks of the batch -- first, last, and for ragged batches the shortest and the
 longest -- from the same seeded inputs: every cached K and V row of those
 blocks, the layer output at query rows that straddle every kernel tile edge
 plus random ones, and the decode outputs at the first, second, middle and last
-step.  Tolerances are those of tests/test_gpu_layer_bf16.py."""
+step.  Tolerances are those of tests/test_gpu_layer_bf16.py.  The router at
+full size (131072 rows, ordered indices against the checker on the same input) is
+checked through its own entry point in tests/test_gpu_kernels.py; here every row of
+the prefill's routing table must hold four distinct experts and gates that sum to one."""
 import numpy as np
 import pytest
 import torch
@@ -17,16 +20,15 @@ from oracle import layer as O
 from paper_2605_23296_amd import binding as B
 from paper_2605_23296_amd.workloads import WORKLOADS, make_inputs, make_mxfp4_experts, to_numpy_f64
 from tests import harness as H
-from tests.util import rel_err, vec_rel_err
+from tests.util import ErrLog
 
 pytestmark = pytest.mark.gpu
-TOL = 2e-2          # per-vector relative error
-ELEM_TOL = 5e-2     # element-wise, floored at rms(r)
 # Routed layer: the GPU routes from its bf16 activations, the checker from fp64 ones.
 # The bf16 rounding of the 2880 normalised inputs moves a logit by about 0.4 % of the
-# logits' spread (sigma ~ 1), i.e. ~1e-3 of max|logit| ~ 4; rows whose 4th and 5th
-# logits are closer than 8e-3 * max|logit| (about eight such sigmas) may legitimately
-# route differently and are only checked for a valid choice.
+# logits' spread (sigma ~ 1), i.e. ~1e-3 of max|logit| ~ 4; experts whose logits are
+# closer than 8e-3 * max|logit| (about eight such sigmas) may legitimately swap
+# (tests/harness.py, check_routing).  Every row's output is compared, the checker's
+# feed-forward being evaluated for the experts the GPU chose.
 MOE_MARGIN = 8e-3
 
 
@@ -130,13 +132,8 @@ def check_workload(name, blocks=None, n_rows=10, mxfp4=False):
         else:
             w[k_] = to_numpy_f64(v)
     ref = O.Layer(layer.as_dict(), w)
-    errs, elem, n_close = {}, {}, 0
-
-    def cmp(tag, got, r):
-        if r.size == 0:
-            return
-        errs[tag] = vec_rel_err(got, r)
-        elem[tag] = rel_err(got, r)
+    log, n_close, n_routed = ErrLog(), 0, 0
+    cmp = log.cmp
 
     for b in blocks:
         L = lens[b]
@@ -155,22 +152,23 @@ def check_workload(name, blocks=None, n_rows=10, mxfp4=False):
         else:
             k = layer.top_k
             idx_rows = g["idx_pre"][cu[b]:cu[b + 1]][rows].cpu().numpy()
-            ok, nu = H.routed_rows_match(idx_rows, pre[0]["idx"], pre[0]["logits"], k, MOE_MARGIN)
-            n_close += nu
-            cmp("y_pre%d" % b, y_rows[ok], pre[0]["y"][ok])
-            gate_rows = g["gate_pre"][cu[b]:cu[b + 1]][rows].cpu().numpy().astype(np.float64)
-            assert np.allclose(gate_rows.sum(-1), 1.0, atol=1e-5)
+            gate_rows = g["gate_pre"][cu[b]:cu[b + 1]][rows].cpu().numpy()
+            n_close += H.check_routing(idx_rows, pre[0]["logits"], k, MOE_MARGIN, gate_rows)
+            n_routed += len(rows)
+            cmp("y_pre%d" % b, y_rows, ref.ffn(pre[0]["h"], forced_idx=idx_rows)[0])
             for s in steps:
-                idx_s, _, logits_s = routes[s]
-                ok, nu = H.routed_rows_match(g["idx_dec"][s, b:b + 1].cpu().numpy(), idx_s, logits_s, k, MOE_MARGIN)
-                n_close += nu
-                if ok.any():
-                    cmp("y_dec%d_%d" % (s, b), to_numpy_f64(g["y_dec"][s, b:b + 1]), yd[s])
-    worst, worst_e = max(errs, key=errs.get), max(elem, key=elem.get)
-    print(name, "blocks", blocks, "lens", [lens[b] for b in blocks], "| worst vector error", worst, "%.3e" % errs[worst],
-          "| worst element error", worst_e, "%.3e" % elem[worst_e], "| routed rows with a close call:", n_close)
-    assert errs[worst] < TOL, {k_: "%.2e" % v for k_, v in errs.items()}
-    assert elem[worst_e] < ELEM_TOL, {k_: "%.2e" % v for k_, v in elem.items()}
+                _, _, logits_s, h_s = routes[s]
+                idx_s = g["idx_dec"][s, b:b + 1].cpu().numpy()
+                n_close += H.check_routing(idx_s, logits_s, k, MOE_MARGIN, g["gate_dec"][s, b:b + 1].cpu().numpy())
+                n_routed += 1
+                cmp("y_dec%d_%d" % (s, b), to_numpy_f64(g["y_dec"][s, b:b + 1]), ref.ffn(h_s, forced_idx=idx_s)[0])
+    log.check("%s blocks %s lens %s | routed rows with a close call: %d of %d (all compared) |"
+              % (name, blocks, [lens[b] for b in blocks], n_close, n_routed))
+    if moe:
+        idx_all = g["idx_pre"]
+        srt = idx_all.sort(dim=1).values
+        assert bool(((idx_all >= 0) & (idx_all < layer.n_experts)).all()) and bool((srt[:, 1:] != srt[:, :-1]).all())
+        assert bool(((g["gate_pre"].sum(dim=1) - 1).abs() < 1e-5).all())
     # nothing outside the blocks' own rows was written: the slab tails stay poisoned
     kvc = g["kv"]
     for b in blocks:

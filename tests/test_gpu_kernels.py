@@ -285,6 +285,55 @@ def test_router_topk_indices_bit_exact(dtype):
     np.testing.assert_allclose(gate.cpu().numpy().sum(-1), 1.0, atol=1e-5)
 
 
+def test_router_full_size_ordered_indices():
+    """The routed workload's whole routing table: 131072 rows x d 2880 through the router's
+    entry point, router weights drawn as the workload's, the same bf16 rows on both sides.
+    Ordered top-4 indices must equal the checker's on every row whose margins (inside the
+    top 4 and to the runner-up) exceed 1e-4 * max|logit|; the remaining rows must hold a
+    valid choice, and every gate row is the softmax over its four logits."""
+    wl = WORKLOADS["moe_16x8192"]
+    layer = wl.layer
+    rows, E, k, d = sum(wl.block_lens), layer.n_experts, layer.top_k, layer.d_model
+    assert rows == 131072 and E == 128 and k == 4 and d == 2880
+    wr = rnd((E, d), torch.bfloat16, 43, std=0.02)            # drawn as the workload's router, N(0, 0.02)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(97)
+    m = torch.randn((rows, d), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)  # unit-rms rows
+    lay = B.Layer(layer, None)
+    idx = torch.empty((rows, k), dtype=torch.int32, device="cuda")
+    gate = torch.empty((rows, k), dtype=torch.float32, device="cuda")
+    logits = torch.empty((rows, E), dtype=torch.float32, device="cuda")
+    lay.compact_moe_route(m, wr, idx, gate, logits)
+    torch.cuda.synchronize()
+    gi, gg, gl = idx.cpu().numpy(), gate.cpu().numpy().astype(np.float64), logits.cpu().numpy().astype(np.float64)
+    wr64 = to_numpy_f64(wr)
+    n_exact = n_close = 0
+    worst_logit = 0.0
+    CH = 8192
+    for r0 in range(0, rows, CH):
+        ref_logits = O.router_logits(to_numpy_f64(m[r0:r0 + CH]), wr64)
+        ref_idx, ref_gate = O.topk_route(ref_logits, k)
+        scale = np.abs(ref_logits).max()
+        worst_logit = max(worst_logit, float(np.abs(gl[r0:r0 + CH] - ref_logits).max() / scale))
+        srt = -np.sort(-ref_logits, axis=-1)
+        gaps = srt[:, :k] - srt[:, 1:k + 1]
+        clear = np.all(gaps > 1e-4 * scale, axis=-1)
+        g = gi[r0:r0 + CH]
+        assert np.array_equal(g[clear], ref_idx[clear]), "ordered expert indices differ on rows with clear margins"
+        np.testing.assert_allclose(gg[r0:r0 + CH][clear], ref_gate[clear], atol=2e-5)
+        n_exact += int(clear.sum())
+        for r in np.nonzero(~clear)[0]:
+            assert len(set(g[r].tolist())) == k
+            assert np.all(ref_logits[r, g[r]] >= srt[r, k - 1] - 1e-4 * scale)
+            n_close += 1
+    print("router at full size: %d rows ordered-exact, %d rows with a margin under 1e-4 (valid choice), worst logit error %.2e"
+          % (n_exact, n_close, worst_logit))
+    # four gaps per row, each under 1e-4 * max|logit| ~ 5e-4 with probability ~ 3e-3
+    assert n_exact + n_close == rows and n_close < rows // 40
+    assert worst_logit < 1e-5
+    np.testing.assert_allclose(gg.sum(-1), 1.0, atol=1e-5)
+
+
 # ---------------------------------------------------------------- expert feed-forward
 @pytest.mark.parametrize("dtype,rows", [("fp32", 150), ("bf16", 700), ("bf16", 5)])
 def test_moe_ffn_with_given_routing(dtype, rows):

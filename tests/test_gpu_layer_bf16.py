@@ -1,16 +1,24 @@
 """bf16 storage mode against the fp64 checker, whole layer, reduced sizes.
 
-Tolerance.  The layer's outputs are hidden-state vectors (one per token) and
-cached K/V head vectors; the bound is on each vector's relative error,
-max_t ||g_t - r_t||_2 / ||r_t||_2 <= 2e-2.  An element-wise bound at the same
-2e-2 cannot hold for a bf16 pipeline at these sizes whatever the kernels do:
-the storage roundings that any bf16 layer has (normalised activations, the
-SwiGLU intermediate, attention probabilities and output, the final result; unit
-roundoff 2^-8) add up to an rms relative error of about 0.4 % of the output
-scale, and the largest of 10^5..10^8 such errors sits at 4.5..6 sigma, i.e.
-2..2.5 %.  So the element-wise error (floored at the tensor's rms) is bounded at
-5e-2 -- far outside rounding noise, well inside any indexing or masking
-mistake, which shows up as O(1) -- and the vector bound carries the 2e-2."""
+Tolerance ("max relative error 2e-2 on bf16 layer outputs").  Three measures are
+asserted on every compared tensor (tests/util.py, ErrLog):
+
+  * per output vector (a token's hidden state, a cached K/V head vector):
+    max_t ||g_t - r_t||_2 / ||r_t||_2 < 2e-2 -- the reading of the stated bound;
+  * per element, max |g - r| / max(|r|, rms(r)) < 3e-2;
+  * pooled rms error per kind of output < 5e-3.
+
+Why the element-wise bound sits at 3e-2 and not 2e-2: the storage roundings that
+any bf16 layer has (normalised activations, the SwiGLU intermediate, attention
+probabilities and output, the final result; unit roundoff 2^-8) add up to an rms
+error of about 0.4 % of the output scale whatever the kernels do
+(tests/test_bf16_floor.py measures that floor on the CPU with the checker's own
+arithmetic and only those roundings: 0.34 %, worst of 4e5 elements 1.7 %), and the largest of 10^5..10^8
+such errors sits at 4.5..6 sigma, i.e. 2..2.7 %.  An indexing or masking mistake
+shows up as O(1), a dropped rounding-free term as a pooled rms error far above
+5e-3.  Routed layers: the routing table is checked against the checker's logits
+(tests/harness.py, check_routing) and the outputs of EVERY row are compared, the
+checker's feed-forward being evaluated for the experts the GPU chose."""
 import copy
 
 import numpy as np
@@ -19,11 +27,9 @@ import torch
 
 from paper_2605_23296_amd.workloads import WORKLOADS, Workload, LayerConfig, make_inputs
 from tests import harness as H
-from tests.util import rel_err, vec_rel_err
+from tests.util import ErrLog, FP32_TOL
 
 pytestmark = pytest.mark.gpu
-TOL = 2e-2          # per-vector relative error
-ELEM_TOL = 5e-2     # element-wise, floored at rms(r)
 
 
 def sample_rows(L, rng, n=12):
@@ -42,12 +48,8 @@ def check_dense(inp, steps=None, pos_offset=None, sampled=True):
     from paper_2605_23296_amd.workloads import to_numpy_f64
     pre, yd, Ks, Vs, _ = lay.forward_sampled(to_numpy_f64(inp.x_prefill), inp.cu_seqlens, to_numpy_f64(inp.x_decode),
                                              rows, steps, pos_offset)
-    errs, elem = {}, {}
-
-    def cmp(name, got, ref):
-        errs[name] = vec_rel_err(got, ref)
-        elem[name] = rel_err(got, ref)
-
+    log = ErrLog()
+    cmp = log.cmp
     for b, L in enumerate(inp.block_lens):
         cmp("y_pre%d" % b, g["y_prefill"][inp.cu_seqlens[b]:inp.cu_seqlens[b + 1]][rows[b]], pre[b]["y"])
         cmp("K%d" % b, g["K"][b], Ks[b])
@@ -55,10 +57,7 @@ def check_dense(inp, steps=None, pos_offset=None, sampled=True):
         assert g["lens"][b] == L + S
     for s in steps:
         cmp("y_dec%d" % s, g["y_decode"][s], yd[s])
-    worst, worst_e = max(errs, key=errs.get), max(elem, key=elem.get)
-    print("worst vector error", worst, "%.3e" % errs[worst], "| worst element error", worst_e, "%.3e" % elem[worst_e])
-    assert errs[worst] < TOL, {k: "%.2e" % v for k, v in errs.items()}
-    assert elem[worst_e] < ELEM_TOL, {k: "%.2e" % v for k, v in elem.items()}
+    log.check()
     return g
 
 
@@ -88,6 +87,31 @@ def test_dense_batched_equals_one_block_at_a_time_bitwise():
         assert np.array_equal(g["K"][0], full["K"][b]) and np.array_equal(g["V"][0], full["V"][b])
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_forward_without_a_prefill_output_buffer_on_a_layer_with_narrow_projection_rows(dtype):
+    """d_model 1024 with 4 + 4 + 4 heads of 64: the stacked q/k/v rows (768 columns) are narrower
+    than d_model.  compact_layer_forward with y_prefill = NULL keeps the feed-forward output in its
+    workspace; y_last and the decode outputs must be the bits of the run that is given a buffer,
+    and match the checker."""
+    layer = LayerConfig(d_model=1024, n_q_heads=4, n_kv_heads=4, head_dim=64, ffn_dim=1024, rope_theta=500000.0, dtype=dtype)
+    wl = Workload("narrow_rows", layer, [300, 77, 513], 3, 3)
+    inp = make_inputs(wl, gain_jitter=True)
+    with_buf = check_dense(inp) if dtype == "bf16" else H.gpu_forward(inp)
+    without = H.gpu_forward(inp, want_prefill=False)
+    assert np.array_equal(with_buf["y_last"], without["y_last"])
+    assert np.array_equal(with_buf["y_decode"], without["y_decode"])
+    for b in range(3):
+        assert np.array_equal(with_buf["K"][b], without["K"][b]) and np.array_equal(with_buf["V"][b], without["V"][b])
+    last = np.stack([with_buf["y_prefill"][c - 1] for c in inp.cu_seqlens[1:]])
+    assert np.array_equal(with_buf["y_last"], last)
+    if dtype == "fp32":
+        r = H.oracle_forward(inp)
+        log = ErrLog(FP32_TOL, FP32_TOL, FP32_TOL)
+        log.cmp("y_last", without["y_last"], np.stack([p["y"][-1] for p in r["pre"]]))
+        log.cmp("y_dec", without["y_decode"], r["y_decode"])
+        log.check()
+
+
 def test_run_to_run_determinism():
     inp = make_inputs(WORKLOADS["dense_8x4096"], block_lens=[257, 300], decode_steps=2)
     a = H.gpu_forward(inp)
@@ -95,34 +119,30 @@ def test_run_to_run_determinism():
     assert np.array_equal(a["y_prefill"], b["y_prefill"]) and np.array_equal(a["y_decode"], b["y_decode"])
 
 
-def check_moe(inp, margin_rel, tol):
-    from paper_2605_23296_amd.workloads import to_numpy_f64
+def check_moe(inp, margin_rel, fp32=False):
+    """Routing tables against the checker's logits, then every output row against the
+    checker's layer evaluated for the experts the GPU chose."""
     g = H.gpu_forward_steps(inp)
     r = H.oracle_forward(inp)
+    lay = H.oracle_layer(inp)
     k = inp.layer.top_k
-    S = inp.x_decode.shape[0]
+    S, N = inp.x_decode.shape[0], len(inp.block_lens)
     n_unsafe = 0
-    errs = {}
-    err_fn = rel_err if inp.layer.dtype == "fp32" else vec_rel_err
+    log = ErrLog(FP32_TOL, FP32_TOL, FP32_TOL) if fp32 else ErrLog()
     for b, L in enumerate(inp.block_lens):
         sl = slice(inp.cu_seqlens[b], inp.cu_seqlens[b + 1])
-        ok, nu = H.routed_rows_match(g["idx_prefill"][sl], r["pre"][b]["idx"], r["pre"][b]["logits"], k, margin_rel)
-        n_unsafe += nu
-        errs["y_pre%d" % b] = err_fn(g["y_prefill"][sl][ok], r["pre"][b]["y"][ok])
-        errs["K%d" % b] = err_fn(g["K"][b], r["K"][b])
-        errs["V%d" % b] = err_fn(g["V"][b], r["V"][b])
+        n_unsafe += H.check_routing(g["idx_prefill"][sl], r["pre"][b]["logits"], k, margin_rel, g["gate_prefill"][sl])
+        y_ref = lay.ffn(r["pre"][b]["h"], forced_idx=g["idx_prefill"][sl])[0]
+        log.cmp("y_pre%d" % b, g["y_prefill"][sl], y_ref)
+        log.cmp("K%d" % b, g["K"][b], r["K"][b])
+        log.cmp("V%d" % b, g["V"][b], r["V"][b])
     for s in range(S):
-        idx_ref = np.stack([r["routes"][s][b][0] for b in range(len(inp.block_lens))])
-        logits_ref = np.stack([r["routes"][s][b][2] for b in range(len(inp.block_lens))])
-        ok, nu = H.routed_rows_match(g["idx_decode"][s], idx_ref, logits_ref, k, margin_rel)
-        n_unsafe += nu
-        if ok.any():
-            errs["y_dec%d" % s] = err_fn(g["y_decode"][s][ok], r["y_decode"][s][ok])
-    worst = max(errs, key=errs.get)
-    print("worst", worst, "%.3e" % errs[worst], "rows with a close call:", n_unsafe)
-    assert errs[worst] < tol, {k_: "%.2e" % v for k_, v in errs.items()}
-    total = inp.cu_seqlens[-1] + S * len(inp.block_lens)
-    assert n_unsafe < 0.5 * total
+        logits_ref = np.stack([r["routes"][s][b][2] for b in range(N)])
+        h_ref = np.stack([r["routes"][s][b][3] for b in range(N)])
+        n_unsafe += H.check_routing(g["idx_decode"][s], logits_ref, k, margin_rel, g["gate_decode"][s])
+        log.cmp("y_dec%d" % s, g["y_decode"][s], lay.ffn(h_ref, forced_idx=g["idx_decode"][s])[0])
+    total = inp.cu_seqlens[-1] + S * N
+    log.check("rows with a close call: %d of %d (all compared) |" % (n_unsafe, total))
 
 
 SMALL_MOE = LayerConfig(d_model=256, n_q_heads=8, n_kv_heads=2, head_dim=64, ffn_dim=320, n_experts=16, top_k=4,
@@ -133,16 +153,16 @@ def test_small_moe_layer_fp32():
     layer = copy.deepcopy(SMALL_MOE)
     layer.dtype = "fp32"
     wl = Workload("small_moe", layer, [130, 40, 1, 77], 4, 3)
-    check_moe(make_inputs(wl), margin_rel=1e-5, tol=1e-5)
+    check_moe(make_inputs(wl), margin_rel=1e-5, fp32=True)
 
 
 def test_small_moe_layer_bf16():
     wl = Workload("small_moe", copy.deepcopy(SMALL_MOE), [300, 40, 1, 513], 4, 3)
-    check_moe(make_inputs(wl), margin_rel=2e-2, tol=TOL)
+    check_moe(make_inputs(wl), margin_rel=2e-2)
 
 
 def test_moe_120b_shape_reduced():
     layer = copy.deepcopy(WORKLOADS["moe_16x8192"].layer)
     layer.n_experts = 16            # same expert shape, fewer experts: bounds the checker's time
     wl = Workload("moe_reduced", layer, [200, 65], 2, 2)
-    check_moe(make_inputs(wl), margin_rel=2e-2, tol=TOL)
+    check_moe(make_inputs(wl), margin_rel=2e-2)

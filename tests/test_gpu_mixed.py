@@ -9,7 +9,8 @@ import torch
 from oracle import layer as O
 from paper_2605_23296_amd import binding as B
 from paper_2605_23296_amd.workloads import WORKLOADS, LayerConfig, Workload, make_inputs, to_numpy_f64
-from tests.util import rel_err, vec_rel_err
+from tests import harness as H
+from tests.util import ErrLog, FP32_TOL
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
@@ -33,31 +34,24 @@ def run_mixed(inp, budget, pos_offset=None, weights=None):
     return dict(y_last=y_last, y_dec=y_dec, kv=kv)
 
 
-def check(inp, budget, tol, elem_tol, ref_out, pos_offset=None):
+def check(inp, budget, fp32, ref_out, pos_offset=None):
     g = run_mixed(inp, budget, pos_offset)
-    pre, y_dec, Ks, Vs = ref_out
-    errs, elem = {}, {}
-
-    def cmp(tag, got, r):
-        errs[tag] = vec_rel_err(got, r)
-        elem[tag] = rel_err(got, r)
-
+    pre, y_dec, Ks, Vs = ref_out[:4]
+    log = ErrLog(FP32_TOL, FP32_TOL, FP32_TOL) if fp32 else ErrLog()
+    cmp = log.cmp
     cmp("y_last", to_numpy_f64(g["y_last"]), np.stack([p["y"][-1] for p in pre]))
     if y_dec.shape[0]:
         cmp("y_dec", to_numpy_f64(g["y_dec"]), y_dec)
     for b in range(len(inp.block_lens)):
         cmp("K%d" % b, to_numpy_f64(g["kv"].block_k(b)), Ks[b])
         cmp("V%d" % b, to_numpy_f64(g["kv"].block_v(b)), Vs[b])
-    worst, worst_e = max(errs, key=errs.get), max(elem, key=elem.get)
-    print("budget", budget, "worst vector error", worst, "%.3e" % errs[worst], "| worst element error", worst_e, "%.3e" % elem[worst_e])
-    assert errs[worst] < tol, {k: "%.2e" % v for k, v in errs.items()}
-    assert elem[worst_e] < elem_tol, {k: "%.2e" % v for k, v in elem.items()}
+    log.check("budget %d |" % budget)
 
 
 def oracle_pass(inp, pos_offset=None):
     ref = O.Layer(inp.layer.as_dict(), {k: to_numpy_f64(v) for k, v in inp.weights.items()})
-    pre, y_dec, Ks, Vs, _ = ref.forward(to_numpy_f64(inp.x_prefill), inp.cu_seqlens, to_numpy_f64(inp.x_decode), pos_offset)
-    return pre, y_dec, Ks, Vs
+    pre, y_dec, Ks, Vs, routes = ref.forward(to_numpy_f64(inp.x_prefill), inp.cu_seqlens, to_numpy_f64(inp.x_decode), pos_offset)
+    return pre, y_dec, Ks, Vs, routes, ref
 
 
 def test_tiny_fp32_mixed_schedules_in_full():
@@ -65,7 +59,7 @@ def test_tiny_fp32_mixed_schedules_in_full():
     po = [0, 7, 3, 100]
     ref = oracle_pass(inp, po)
     for budget in (5, 64, 100, 1000):       # 5: chunks of 1-5 rows; 1000: everything in one step
-        check(inp, budget, 1e-5, 1e-5, ref, po)
+        check(inp, budget, True, ref, po)
 
 
 def test_bf16_mixed_schedules_ragged_blocks():
@@ -76,22 +70,51 @@ def test_bf16_mixed_schedules_ragged_blocks():
     inp = make_inputs(wl, gain_jitter=True)
     ref = oracle_pass(inp)
     for budget in (256, 203, 4096):
-        check(inp, budget, 2e-2, 5e-2, ref)
+        check(inp, budget, False, ref)
 
 
-def test_bf16_mixed_routed_layer_keeps_the_caches_right():
+def test_bf16_mixed_routed_layer_every_row():
+    """The mixed call does not report its routing tables, so the checker lists, per row, every
+    expert set that is a valid top-k choice when logits closer than the rounding margin may
+    swap (one set on most rows, two or three at a near-tie), evaluates the layer for each, and
+    the GPU's row must match one of them within the tolerances.  Every row is compared."""
     layer = LayerConfig(d_model=256, n_q_heads=8, n_kv_heads=2, head_dim=64, ffn_dim=320, n_experts=16, top_k=4,
                         rope_theta=500000.0)
     wl = Workload("small_moe", layer, [200, 75, 30], 3, 4)
     inp = make_inputs(wl)
     g = run_mixed(inp, 96)
-    pre, y_dec, Ks, Vs = oracle_pass(inp)
-    # the prefill rows' K/V depend on no routing; decode rows follow routed outputs only through x_decode (given)
-    for b in range(3):
-        assert vec_rel_err(to_numpy_f64(g["kv"].block_k(b)), Ks[b]) < 2e-2
-        assert vec_rel_err(to_numpy_f64(g["kv"].block_v(b)), Vs[b]) < 2e-2
-    err = np.sort(np.array([vec_rel_err(to_numpy_f64(g["y_dec"][s, b]), y_dec[s, b]) for s in range(4) for b in range(3)]))
-    assert err[len(err) // 2] < 2e-2      # near-ties in the router may move single rows
+    pre, y_dec, Ks, Vs, routes, ref = oracle_pass(inp)
+    k, N, S = layer.top_k, 3, 4
+    log = ErrLog()
+    for b in range(N):
+        log.cmp("K%d" % b, to_numpy_f64(g["kv"].block_k(b)), Ks[b])
+        log.cmp("V%d" % b, to_numpy_f64(g["kv"].block_v(b)), Vs[b])
+    scale = max(np.abs(p["logits"]).max() for p in pre)
+    n_multi = 0
+
+    def best_candidate(got, h, logits):
+        """got [d]; the candidate evaluation closest to it."""
+        cands = H.routing_candidates(logits, k, 2e-2 * scale)
+        assert 1 <= len(cands) <= 20
+        ys = [ref.ffn(h[None], forced_idx=np.array([c]))[0][0] for c in cands]
+        return min(ys, key=lambda y: np.linalg.norm(y - got)), len(cands) > 1
+
+    got_last = to_numpy_f64(g["y_last"])
+    want = []
+    for b in range(N):
+        y, multi = best_candidate(got_last[b], pre[b]["h"][-1], pre[b]["logits"][-1])
+        want.append(y)
+        n_multi += multi
+    log.cmp("y_last", got_last, np.stack(want))
+    got_dec = to_numpy_f64(g["y_dec"])
+    for s in range(S):
+        want = []
+        for b in range(N):
+            y, multi = best_candidate(got_dec[s, b], routes[s][b][3], routes[s][b][2])
+            want.append(y)
+            n_multi += multi
+        log.cmp("y_dec%d" % s, got_dec[s], np.stack(want))
+    log.check("rows with more than one valid expert set: %d of %d (all compared) |" % (n_multi, N + S * N))
 
 
 def test_dense_ragged32_mixed_matches_the_plain_pass_at_full_size():
@@ -132,11 +155,11 @@ def test_mixed_degenerate_schedules_fp32():
     one token, no decode steps at all, and a single block."""
     wl = WORKLOADS["tiny_fp32"]
     inp = make_inputs(wl, block_lens=[5, 1, 9], decode_steps=3, gain_jitter=True)
-    check(inp, 4, 1e-5, 1e-5, oracle_pass(inp))
+    check(inp, 4, True, oracle_pass(inp))
     inp0 = make_inputs(wl, block_lens=[5, 1, 9], decode_steps=0)
-    check(inp0, 4, 1e-5, 1e-5, oracle_pass(inp0))
+    check(inp0, 4, True, oracle_pass(inp0))
     one = make_inputs(wl, block_lens=[33], decode_steps=2)
-    check(one, 16, 1e-5, 1e-5, oracle_pass(one))
+    check(one, 16, True, oracle_pass(one))
 
 
 def test_mixed_random_schedules_fp32():
@@ -150,4 +173,4 @@ def test_mixed_random_schedules_fp32():
         budget = int(rng.integers(n + 1, 200))
         inp = make_inputs(wl, block_lens=lens, decode_steps=steps, gain_jitter=True)
         print("lens", lens, "steps", steps, end=" ")
-        check(inp, budget, 1e-5, 1e-5, oracle_pass(inp))
+        check(inp, budget, True, oracle_pass(inp))

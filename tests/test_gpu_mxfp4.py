@@ -12,11 +12,10 @@ from paper_2605_23296_amd import binding as B
 from paper_2605_23296_amd.workloads import (WORKLOADS, LayerConfig, Workload, make_inputs, make_mxfp4_experts,
                                             to_numpy_f64)
 from tests import harness as H
-from tests.util import rel_err, vec_rel_err
+from tests.util import ErrLog
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
-TOL, ELEM_TOL = 2e-2, 5e-2
 
 
 def test_expansion_is_bit_exact_for_every_code_and_a_range_of_scales():
@@ -37,11 +36,11 @@ def test_expansion_is_bit_exact_for_every_code_and_a_range_of_scales():
     assert np.array_equal(np.signbit(got), np.signbit(ref))      # -0.0 stays -0.0
 
 
-def build(layer, block_lens, steps, seed=0):
+def build(layer, block_lens, steps, seed=0, scale_spread=0):
     wl = Workload("q4", layer, block_lens, len(block_lens), steps, seed=seed)
     inp = make_inputs(wl)
     gen = torch.Generator().manual_seed(seed + 77)
-    q4 = make_mxfp4_experts(layer, gen)
+    q4 = make_mxfp4_experts(layer, gen, scale_spread=scale_spread)
     return inp, q4
 
 
@@ -65,13 +64,18 @@ def device_weights(lay0, inp, q4):
     return w
 
 
-@pytest.mark.parametrize("d,F", [(256, 320), (1216, 1088)])
-def test_routed_decode_steps_streaming_4bit_experts(d, F):
+@pytest.mark.parametrize("d,F,spread", [(256, 320, 0), (1216, 1088, 0), (1216, 1088, 30)])
+def test_routed_decode_steps_streaming_4bit_experts(d, F, spread):
     """d = 256: one k-slice of two MFMA groups; d = 1216 / F = 1088: a full 1024-wide slice plus a
-    slice of 6 (2) blocks, i.e. a partial group of four.  Empty experts, experts with several rows."""
+    slice of 6 (2) blocks, i.e. a partial group of four.  Empty experts, experts with several rows.
+    spread = 30: scale bytes from 56 to 181 (2^-71 .. 2^54) through the streaming kernels, every
+    expert's contribution still O(1) (workloads.make_mxfp4_experts)."""
     layer = LayerConfig(d_model=d, n_q_heads=8, n_kv_heads=2, head_dim=64, ffn_dim=F, n_experts=16, top_k=4,
                         rope_theta=500000.0)
-    inp, q4 = build(layer, [70, 33, 129, 5, 64], 3)
+    inp, q4 = build(layer, [70, 33, 129, 5, 64], 3, scale_spread=spread)
+    if spread:
+        sc = torch.cat([q4["w_exp_gate_up_s"].flatten(), q4["w_exp_down_s"].flatten()])
+        assert int(sc.min()) <= 60 and int(sc.max()) >= 180
     lay0 = B.Layer(layer, None)
     w = device_weights(lay0, inp, q4)
     lay = B.Layer(layer, w)
@@ -91,17 +95,14 @@ def test_routed_decode_steps_streaming_4bit_experts(d, F):
 
     ref = O.Layer(layer.as_dict(), oracle_weights(inp, q4))
     pre, yd, Ks, Vs, routes = ref.forward(to_numpy_f64(inp.x_prefill), cu, to_numpy_f64(inp.x_decode))
-    n_cmp = 0
+    log, n_close = ErrLog(), 0
     for s in range(S):
-        for b in range(N):
-            ri, rg, rl = routes[s][b]
-            ok, _ = H.routed_rows_match(idx[s, b:b + 1].cpu().numpy(), ri[None], rl[None], 4, 8e-3)
-            if ok.all() and np.array_equal(np.sort(idx[s, b].cpu().numpy()), np.sort(ri)):
-                e = vec_rel_err(to_numpy_f64(y_dec[s, b]), yd[s, b])
-                assert e < TOL, (s, b, e)
-                assert rel_err(to_numpy_f64(y_dec[s, b]), yd[s, b]) < ELEM_TOL
-                n_cmp += 1
-    assert n_cmp >= S * N - 3
+        logits = np.stack([routes[s][b][2] for b in range(N)])
+        h = np.stack([routes[s][b][3] for b in range(N)])
+        gi = idx[s].cpu().numpy()
+        n_close += H.check_routing(gi, logits, 4, 8e-3, gate[s].cpu().numpy())
+        log.cmp("y_dec%d" % s, to_numpy_f64(y_dec[s]), ref.ffn(h, forced_idx=gi)[0])     # every row
+    log.check("rows with a close call: %d of %d (all compared) |" % (n_close, S * N))
 
 
 def test_4bit_and_16bit_paths_agree_on_the_same_values():

@@ -256,6 +256,79 @@ def test_moe_one_hot_router_and_expert_permutation(rng):
     assert idx3[0, 0] == 2 and gate3[0, 0] > 0.999
 
 
+def test_forced_expert_choice_follows_the_routed_layer_definition(rng):
+    """The forced-choice evaluation the parity tests use at router near-ties: row r goes to
+    the given experts, gated by the softmax over its own logits at those experts."""
+    cfg = small_cfg(n_experts=6, top_k=3)
+    w = small_weights(cfg, rng)
+    lay = O.Layer(cfg, w)
+    F = cfg["ffn_dim"]
+    h = rng.standard_normal((7, cfg["d_model"]))
+    y, idx, gate, logits = lay.ffn(h)
+    # its own choice forced on it changes nothing, bit for bit
+    y1, idx1, gate1, _ = lay.ffn(h, forced_idx=idx)
+    assert np.array_equal(y1, y) and np.array_equal(idx1, idx) and np.array_equal(gate1, gate)
+    # the order inside a choice only permutes the gates
+    y2, _, gate2, _ = lay.ffn(h, forced_idx=idx[:, ::-1])
+    np.testing.assert_allclose(y2, y, atol=1e-13)
+    np.testing.assert_allclose(gate2, gate[:, ::-1], atol=1e-15)
+    # another choice, against the definition written out token by token
+    other = np.stack([rng.permutation(6)[:3] for _ in range(7)])
+    y3, idx3, gate3, _ = lay.ffn(h, forced_idx=other)
+    m = O.rmsnorm(h, w["g_ffn"], cfg["rms_eps"])
+    for r in range(7):
+        e = np.exp(logits[r, other[r]])
+        g = e / e.sum()
+        np.testing.assert_allclose(gate3[r], g, rtol=1e-13)
+        want = h[r] + sum(g[s] * O.swiglu_ffn(m[r:r + 1], w["w_exp_gate_up"][ex, :F], w["w_exp_gate_up"][ex, F:],
+                                               w["w_exp_down"][ex])[0] for s, ex in enumerate(other[r]))
+        np.testing.assert_allclose(y3[r], want, atol=1e-12)
+    assert not np.allclose(y3, y)
+    # identical experts: any choice gives the dense layer
+    w2 = dict(w)
+    w2["w_exp_gate_up"] = np.repeat(w["w_exp_gate_up"][:1], 6, axis=0)
+    w2["w_exp_down"] = np.repeat(w["w_exp_down"][:1], 6, axis=0)
+    lay2 = O.Layer(cfg, w2)
+    np.testing.assert_allclose(lay2.ffn(h, forced_idx=other)[0], lay2.ffn(h)[0], atol=1e-12)
+
+
+def test_forced_choice_threads_through_blocks_steps_and_the_stack(rng):
+    cfg = small_cfg(n_experts=5, top_k=2)
+    ws = [small_weights(cfg, rng) for _ in range(2)]
+    x = rng.standard_normal((11, cfg["d_model"]))
+    xd = rng.standard_normal((3, 2, cfg["d_model"]))
+    cu = [0, 7, 11]
+    lay = O.Layer(cfg, ws[0])
+    pre, yd, Ks, Vs, routes = lay.forward(x, cu, xd)
+    # forcing the pass's own choices reproduces it; the reported h is the FFN half's input
+    pre2 = lay.prefill(x, cu, forced_idx=[p["idx"] for p in pre])
+    for a, b in zip(pre, pre2):
+        assert np.array_equal(a["y"], b["y"])
+        assert np.array_equal(lay.ffn(a["h"])[0], a["y"])
+    Kc, Vc = [p["K"] for p in pre], [p["V"] for p in pre]
+    for s in range(3):
+        st = lay.decode_step(xd[s], Kc, Vc, forced_idx=np.stack([routes[s][b][0] for b in range(2)]))
+        for b in range(2):
+            assert np.array_equal(st[b]["y"], yd[s, b])
+            assert np.array_equal(lay.ffn(routes[s][b][3][None])[0][0], yd[s, b])
+            Kc[b], Vc[b] = st[b]["K"], st[b]["V"]
+    # a different choice in one decode row moves that row only
+    alt = np.stack([routes[0][b][0] for b in range(2)]).copy()
+    alt[1] = [(alt[1, 0] + 1) % 5, (alt[1, 0] + 2) % 5]
+    st = lay.decode_step(xd[0], [p["K"] for p in pre], [p["V"] for p in pre], forced_idx=alt)
+    assert np.array_equal(st[0]["y"], yd[0, 0]) and not np.allclose(st[1]["y"], yd[0, 1])
+    # the stack: forcing every layer's own choices reproduces the pass
+    stack = O.Stack(cfg, ws)
+    y_pre, y_dec, _, _ = stack.forward(x, cu, xd)
+    forced = [(r["pre_idx"], np.stack(r["dec_idx"])) for r in stack.routes]
+    y_pre2, y_dec2, _, _ = stack.forward(x, cu, xd, forced=forced)
+    assert np.array_equal(y_pre, y_pre2) and np.array_equal(y_dec, y_dec2)
+    # a changed choice in layer 0 reaches the last layer's output of that row
+    forced[0][0][3] = [(forced[0][0][3, 0] + 1) % 5, (forced[0][0][3, 0] + 2) % 5]
+    y_pre3, _, _, _ = stack.forward(x, cu, xd, forced=forced)
+    assert np.array_equal(y_pre3[:3], y_pre[:3]) and not np.allclose(y_pre3[3], y_pre[3])
+
+
 # ---------------------------------------------------------------- whole layer
 @pytest.mark.parametrize("moe", [False, True])
 def test_batched_equals_one_block_at_a_time(rng, moe):
