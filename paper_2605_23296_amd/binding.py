@@ -23,7 +23,7 @@ EXPORTS = [
     "compact_prefill", "compact_decode_step", "compact_layer_forward",
     "compact_profile_select", "compact_profile_read",
     "compact_rmsnorm", "compact_rope_kvwrite", "compact_gemm", "compact_attn_prefill",
-    "compact_attn_decode", "compact_moe_route", "compact_moe_ffn",
+    "compact_attn_decode", "compact_attn_decode_noalloc", "compact_moe_route", "compact_moe_ffn",
     "compact_prefix_workspace_bytes", "compact_prefix_decode_step", "compact_attn_decode_prefix",
     "compact_stack_workspace_bytes", "compact_stack_forward", "compact_prefill_extend", "compact_mxfp4_dequant",
     "compact_mixed_workspace_bytes", "compact_mixed_forward",
@@ -362,6 +362,9 @@ class Layer:
     def compact_attn_decode(self, q, kv, o):
         wsp, wsn = self._ws()
         self.check(self.L.compact_attn_decode(self.ctx, kv.N, _ptr(q), C.byref(kv.c), _ptr(o), wsp, wsn, _stream()))
+
+    def compact_attn_decode_noalloc(self, q, kv, o):
+        self.check(self.L.compact_attn_decode_noalloc(self.ctx, kv.N, _ptr(q), C.byref(kv.c), _ptr(o), _stream()))
 
     def compact_moe_route(self, m, w_router, idx, gate, logits=None):
         wsp, wsn = self._ws()

@@ -1553,6 +1553,123 @@ extern "C" int compact_attn_decode(compact_ctx* ctx, int32_t n_blocks, const voi
     return run_attn_decode(ctx, plan, n_blocks, 0, d_q, kv, (float*)d_workspace, d_o, s);
 }
 
+// ---------------------------------------------------------------------------
+// decode attention for callers that cannot allocate
+// ---------------------------------------------------------------------------
+// The split-KV partial records and the work list live in one file-scope device array
+// instead of the caller's workspace and the context's metadata buffer.  Every GPU the
+// library runs on holds its own copy of the array, at its own address, until the
+// process ends; host code reaches it only through the address hipGetSymbolAddress
+// returns for the current device (the array's name is a host-side stand-in, never a
+// device address).  The work list is written by a small kernel from values passed as
+// kernel arguments, so nothing is copied from host memory either.
+#define NOALLOC_MAX_BLOCKS 64
+#define NOALLOC_MAX_CHUNKS 2048
+#define NOALLOC_META_BYTES ((size_t)64 << 10)      // BlockMeta[64] (2 KB) + TileItem[2048] (16 KB)
+#define NOALLOC_PARTIAL_BYTES ((size_t)16 << 20)
+static __device__ __align__(256) unsigned char scratch[NOALLOC_META_BYTES + NOALLOC_PARTIAL_BYTES];
+
+#define NOALLOC_MAX_DEVICES 64
+static std::mutex g_scratch_mu;
+static unsigned char* g_scratch_ptr[NOALLOC_MAX_DEVICES] = {};
+
+// device address of the current device's copy of `scratch` (looked up once per device)
+static int scratch_of_current_device(compact_ctx* ctx, unsigned char** out) {
+    int dev = -1;
+    HIP_TRY(ctx, hipGetDevice(&dev));
+    if (dev < 0 || dev >= NOALLOC_MAX_DEVICES) return set_err(ctx, COMPACT_EHIP, "device ordinal out of range");
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        HIP_TRY(ctx, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return set_err(ctx, COMPACT_EHIP, "hipGetSymbolAddress returned a null address");
+        g_scratch_ptr[dev] = (unsigned char*)p;
+    }
+    *out = g_scratch_ptr[dev];
+    return COMPACT_OK;
+}
+
+struct NoallocPlanArgs {          // passed by value as a kernel argument (1.3 KB)
+    int32_t n_blocks;
+    int32_t len[NOALLOC_MAX_BLOCKS];
+    int32_t capacity[NOALLOC_MAX_BLOCKS];
+    int64_t slab[NOALLOC_MAX_BLOCKS];
+};
+
+// One wavefront: lane b writes block b's record and, after a prefix sum of the chunk
+// counts over the wavefront, that block's (block, first row) chunk items in block order
+// (the order the host-built lists of the other entry points have).
+__global__ __launch_bounds__(64) void noalloc_plan_kernel(NoallocPlanArgs a, BlockMeta* meta, TileItem* chunks) {
+    const int b = threadIdx.x;
+    int nch = 0;
+    if (b < a.n_blocks) {
+        BlockMeta m;
+        m.row0 = b;
+        m.len = a.len[b] - 1;        // the attention kernels attend rows 0 .. len inclusive
+        m.capacity = a.capacity[b];
+        m.pos_offset = 0;
+        m.slab = a.slab[b];
+        m.prior = 0;
+        m.pad_ = 0;
+        meta[b] = m;
+        nch = (a.len[b] + DECODE_CHUNK - 1) / DECODE_CHUNK;
+    }
+    int incl = nch;
+#pragma unroll
+    for (int ofs = 1; ofs < 64; ofs <<= 1) {
+        const int v = __shfl_up(incl, ofs, 64);
+        if (b >= ofs) incl += v;
+    }
+    const int first = incl - nch;
+    for (int i = 0; i < nch; ++i) chunks[first + i] = TileItem{b, i * DECODE_CHUNK};
+}
+
+extern "C" int compact_attn_decode_noalloc(compact_ctx* ctx, int32_t n_blocks, const void* d_q, const compact_kv* kv,
+                                           void* d_o, void* hip_stream) {
+    if (!ctx) return COMPACT_EINVAL;
+    if (ctx->cfg.dtype != COMPACT_BF16) return set_err(ctx, COMPACT_EUNSUPPORTED, "the allocation-free decode attention is built for bf16 storage");
+    if (n_blocks < 1) return set_err(ctx, COMPACT_EINVAL, "n_blocks must be >= 1");
+    if (!d_q || !d_o) return set_err(ctx, COMPACT_EINVAL, "null q or o");
+    TRY(check_kv(ctx, kv, n_blocks));
+    if (n_blocks > NOALLOC_MAX_BLOCKS)
+        return set_err(ctx, COMPACT_ECAPACITY, "more than 64 blocks: beyond the fixed scratch of the allocation-free entry point");
+    NoallocPlanArgs a;
+    memset(&a, 0, sizeof(a));
+    a.n_blocks = n_blocks;
+    int max_len = 0;
+    int64_t n_chunks = 0;
+    for (int b = 0; b < n_blocks; ++b) {
+        if (kv->h_len[b] < 1 || kv->h_len[b] > kv->h_capacity[b])
+            return set_err(ctx, COMPACT_ECAPACITY, "h_len must be in 1..capacity");
+        a.len[b] = kv->h_len[b];
+        a.capacity[b] = kv->h_capacity[b];
+        a.slab[b] = kv->h_slab_offset[b];
+        max_len = std::max(max_len, kv->h_len[b]);
+        n_chunks += chunks_for(kv->h_len[b]);
+    }
+    const int max_chunks = chunks_for(max_len);
+    if (n_chunks > NOALLOC_MAX_CHUNKS)
+        return set_err(ctx, COMPACT_ECAPACITY, "more than 2048 chunks of 256 cached rows in total: beyond the fixed scratch of the allocation-free entry point");
+    if (attn_decode_partial_floats(ctx->cfg, n_blocks, max_chunks) * 4 > NOALLOC_PARTIAL_BYTES)
+        return set_err(ctx, COMPACT_ECAPACITY, "split-KV records (n_blocks * n_q_heads * chunks of the longest cache * (head_dim + 2) floats) exceed the 16 MiB scratch of the allocation-free entry point");
+    hipStream_t s = (hipStream_t)hip_stream;
+    unsigned char* base = nullptr;
+    TRY(scratch_of_current_device(ctx, &base));
+    BlockMeta* meta = (BlockMeta*)base;
+    TileItem* chunks = (TileItem*)(base + align_up(sizeof(BlockMeta) * NOALLOC_MAX_BLOCKS, 256));
+    float* partials = (float*)(base + NOALLOC_META_BYTES);
+    // Nothing in the scratch has to start at zero: the plan kernel writes every record and item the
+    // attention kernels read, and the combine reads only partial records the same call has written.
+    noalloc_plan_kernel<<<1, 64, 0, s>>>(a, meta, chunks);
+    LAUNCH_CHECK(ctx);
+    const int keep = ctx->profile_class;   // the per-kernel timer creates events on demand: not through this entry point
+    ctx->profile_class = COMPACT_K_NONE;
+    const int rc = launch_attn_decode_bf16(ctx, meta, chunks, (int)n_chunks, n_blocks, 0, max_chunks, (const bf16*)d_q,
+                                           (const bf16*)kv->d_k, (const bf16*)kv->d_v, partials, (bf16*)d_o, s);
+    ctx->profile_class = keep;
+    return rc;
+}
+
 extern "C" int compact_mxfp4_dequant(compact_ctx* ctx, const void* d_codes, const void* d_scales, int64_t rows, int32_t K,
                                      void* d_out, void* hip_stream) {
     if (!ctx) return COMPACT_EINVAL;

@@ -154,6 +154,24 @@ def test_kernel_hooks_reject_bad_arguments_without_a_device():
     assert blay.L.compact_gemm(blay.ctx, p, p, None, p, 128, 64, 100, 0, None, 0, None) == 2
 
 
+def test_no_alloc_decode_attention_checks_its_limits_without_a_device():
+    lay = _fake_layer("dense_8x4096")
+    L = B.lib()
+    q, o = C.c_void_p(0x3000), C.c_void_p(0x4000)
+    kv, keep = _kv([16] * 65, [8] * 65)
+    assert L.compact_attn_decode_noalloc(lay.ctx, 65, q, C.byref(kv), o, None) == 3        # more than 64 blocks
+    assert b"64 blocks" in L.compact_last_error(lay.ctx)
+    kv, keep = _kv([4104] * 64, [4100] * 64)
+    assert L.compact_attn_decode_noalloc(lay.ctx, 64, q, C.byref(kv), o, None) == 3        # records beyond 16 MiB
+    assert b"16 MiB" in L.compact_last_error(lay.ctx)
+    kv, keep = _kv([16], [17])
+    assert L.compact_attn_decode_noalloc(lay.ctx, 1, q, C.byref(kv), o, None) == 3         # h_len beyond the slab
+    kv, keep = _kv([16], [8])
+    assert L.compact_attn_decode_noalloc(lay.ctx, 1, None, C.byref(kv), o, None) == 1
+    assert L.compact_attn_decode_noalloc(lay.ctx, 0, q, C.byref(kv), o, None) == 1
+    assert L.compact_attn_decode_noalloc(_fake_layer("tiny_fp32").ctx, 1, q, C.byref(kv), o, None) == 5   # fp32 storage
+
+
 def test_prefix_aware_calls_reject_bad_arguments_without_a_device():
     lay = _fake_layer("dense_8x4096")
     L, ctx, w = lay.L, lay.ctx, C.byref(lay.w)
