@@ -18,7 +18,18 @@
  *    library owns nothing but the context and a small device metadata buffer.
  *  - Host arrays are read (and h_len written) before the call returns.
  *  - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL =
- *    the default stream) and the call returns without synchronising.
+ *    the default stream) and the call returns without synchronising.  One
+ *    exception: the first call through a context that needs device metadata
+ *    (block table, tile lists) allocates a 1 MiB device buffer and a pinned
+ *    staging copy for it (hipMalloc + hipHostMalloc) after one
+ *    hipDeviceSynchronize; a later call does so again only if its lists
+ *    outgrow the buffer (then doubled).  Steady-state calls neither allocate
+ *    nor synchronise the device; a call that uploads metadata waits on the
+ *    host until the previous upload has left the staging buffer.
+ *  - A context serves ONE stream at a time: its metadata buffer and staging
+ *    copy are shared by all its calls, so calls through one context on
+ *    different streams must be ordered by the caller.  Use one context per
+ *    stream for concurrent work.
  *  - Activations and weights are row-major, dtype per cfg.dtype (fp32 or
  *    bf16).  Weights are [out, in], so both GEMM operands are contiguous
  *    along the contraction.

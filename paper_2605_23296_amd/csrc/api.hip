@@ -295,7 +295,9 @@ static int upload_plan(compact_ctx* ctx, Plan& p, hipStream_t s) {
         ctx->d_meta = nullptr;
         ctx->h_stage = nullptr;
         ctx->meta_bytes = 0;
-        const size_t cap = std::max(total * 2, (size_t)1 << 16);
+        // 1 MiB holds the lists of every named workload several times over, so that in practice only the
+        // first call through a context allocates (and synchronises)
+        const size_t cap = std::max(total * 2, (size_t)1 << 20);
         HIP_TRY(ctx, hipMalloc(&ctx->d_meta, cap));
         HIP_TRY(ctx, hipHostMalloc(&ctx->h_stage, cap, hipHostMallocDefault));
         ctx->meta_bytes = cap;

@@ -2,11 +2,19 @@
 // Every block attends only its own tokens; the packed batch is walked through
 // a list of (block, 128-row query tile) items sorted heaviest-first.
 //
-//  * workgroup = 4 wavefronts = one query tile x one query head; wave w owns
-//    32 query rows and keeps Q^T in registers as the MFMA column operand;
+//  * two kernels.  Head_dim 128 with an even GQA group: a workgroup of 8
+//    wavefronts takes one query tile x TWO query heads of one KV head; the
+//    wavefronts w and w + 4 share a SIMD and run the same loop one phase apart
+//    ("ping-pong": one in its matrix phase while the other does its softmax),
+//    separated by workgroup barriers.  Otherwise (head_dim 64, odd group): a
+//    workgroup of 4 wavefronts = one query tile x one query head.  In both, a
+//    wavefront owns 32 query rows and keeps Q^T in registers as the MFMA
+//    column operand;
 //  * K tiles [64 tok][hd] and V^T tiles [hd][64 tok] (the V slab is stored
-//    transposed, so no transposition happens here) are staged in LDS, double
-//    buffered, register-prefetched, with XOR-swizzled 16-byte chunks;
+//    transposed, so no transposition happens here) are staged by 16-byte
+//    global loads that land in LDS directly (no register hop, no LDS stores),
+//    in XOR-swizzled 16-byte chunks: a ring of four stages shared by the two
+//    heads in the ping-pong kernel, of two stages in the other;
 //  * S^T = K Q^T and O^T += V^T P^T with v_mfma_f32_32x32x16_bf16.  Working
 //    on the transposed problem puts one query row in one lane column, so the
 //    online-softmax max/sum are in-lane reductions plus one cross-half

@@ -4,10 +4,13 @@
 //
 // Shape of the kernel (gfx950):
 //  * one workgroup = BM x BN output tile, K walked in tiles of 32;
-//  * X and W k-tiles are staged in a ring of four LDS stages, filled by
-//    16-byte direct-to-LDS global loads (no register hop) issued three k-tiles
-//    ahead of their use: a load's round trip is about as long as the MFMAs of
-//    two k-tiles, so anything shallower leaves the matrix pipe waiting;
+//  * X and W k-tiles are staged in a ring of five LDS stages (5 x 32 KB, the
+//    whole LDS of a CU), filled by 16-byte direct-to-LDS global loads (no
+//    register hop).  A k-tile row is 64 bytes, half a cache line, so the
+//    loads go out for two k-tiles at a time, the two halves of a line in
+//    adjacent instructions, 2 to 2.5 k-tiles ahead of their use: a load's
+//    round trip is about as long as the MFMAs of two k-tiles, so anything
+//    shallower leaves the matrix pipe waiting;
 //  * a tile row is 32 bf16 = 4 chunks of 16 bytes, chunk index XOR-ed with
 //    (row / 4) % 4: the LDS has 64 banks of 4 bytes, four 64-byte rows fill
 //    them once, and 16 lanes reading 16 consecutive rows at one k-offset (an
