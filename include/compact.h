@@ -337,13 +337,13 @@ int compact_attn_decode(compact_ctx* ctx, int32_t n_blocks, const void* d_q, con
  * do so on their behalf: code under HIP graph capture, tight serving loops, harnesses that
  * forbid hipMalloc.  Same inputs, same kernels and bit-identical output, but there is no
  * workspace argument: the split-KV partial records and the (block, chunk) work list live in
- * a fixed 16 MiB + 64 KiB device array inside the library (one copy per GPU, held until the
+ * a fixed 32 MiB + 64 KiB device array inside the library (one copy per GPU, held until the
  * process ends), and the work list is written by a kernel from the call's arguments instead
  * of being copied from host memory.  The call makes no hipMalloc / hipFree / hipHostMalloc
  * and no host-to-device copy, and enqueues three kernels on hip_stream.  bf16 storage only.
  * Limits, checked before any HIP call (COMPACT_ECAPACITY beyond them): n_blocks <= 64; at
- * most 2048 chunks of 256 cached rows over all blocks; n_blocks * n_q_heads *
- * ceil(max h_len / 256) * (head_dim + 2) * 4 bytes of partial records <= 16 MiB.
+ * most 4096 chunks of 256 cached rows over all blocks; n_blocks * n_q_heads *
+ * ceil(max h_len / 256) * (head_dim + 2) * 4 bytes of partial records <= 32 MiB.
  * All calls on one GPU share that array, through whatever context or stream: calls that
  * overlap in time on one GPU race; serialise them (one stream, or events).  Nothing in
  * the array has to be cleared between calls (every record a call reads it has written).

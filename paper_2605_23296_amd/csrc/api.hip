@@ -244,6 +244,7 @@ static int decode_max_ksplit(const compact_layer_cfg& c, int N) {
 }
 
 static int chunks_for(int len) { return (len + DECODE_CHUNK - 1) / DECODE_CHUNK; }
+static int prefix_chunks_for(int len) { return (len + PREFIX_CHUNK - 1) / PREFIX_CHUNK; }
 
 extern "C" int compact_workspace_bytes(const compact_ctx* ctx, int64_t max_tokens, int32_t max_blocks,
                                        int32_t max_kv_len, size_t* bytes) {
@@ -1147,7 +1148,7 @@ extern "C" int compact_stack_forward(compact_ctx* ctx, int32_t n_layers, const c
 // ---------------------------------------------------------------------------
 static int64_t prefix_max_recs(const compact_layer_cfg& c, int n_workers, int max_prefix_len, int max_tail_len) {
     const int G = c.n_q_heads / c.n_kv_heads;
-    return ((int64_t)chunks_for(max_prefix_len) * n_workers + (int64_t)n_workers * chunks_for(max_tail_len + 1)) * G;
+    return ((int64_t)prefix_chunks_for(max_prefix_len) * n_workers + (int64_t)n_workers * prefix_chunks_for(max_tail_len + 1)) * G;
 }
 
 extern "C" int compact_prefix_workspace_bytes(const compact_ctx* ctx, int32_t n_workers, int32_t max_prefix_len,
@@ -1207,16 +1208,16 @@ static int build_prefix_plan(compact_ctx* ctx, int n_workers, const compact_kv* 
     std::vector<std::vector<int32_t>> lists(n_workers);
     int32_t rec = 0;
     int w0 = 0;
-    for (int r0 = 0; r0 < max_prefix; r0 += DECODE_CHUNK) {
+    for (int r0 = 0; r0 < max_prefix; r0 += PREFIX_CHUNK) {
         while (h_prefix_len[w0] <= r0) ++w0;   // first worker whose prefix reaches into the chunk
-        PrefixItem it{r0, std::min(DECODE_CHUNK, max_prefix - r0), w0, n_workers - w0, 0, rec};
+        PrefixItem it{r0, std::min(PREFIX_CHUNK, max_prefix - r0), w0, n_workers - w0, 0, rec};
         for (int b = w0; b < n_workers; ++b) lists[b].push_back((int32_t)pa.items.size());
         pa.items.push_back(it);
         rec += it.nw * G;
     }
     for (int b = 0; b < n_workers; ++b)
-        for (int r0 = 0; r0 < tails->h_len[b] + steps; r0 += DECODE_CHUNK) {
-            PrefixItem it{r0, DECODE_CHUNK, b, 1, 1, rec};
+        for (int r0 = 0; r0 < tails->h_len[b] + steps; r0 += PREFIX_CHUNK) {
+            PrefixItem it{r0, PREFIX_CHUNK, b, 1, 1, rec};
             lists[b].push_back((int32_t)pa.items.size());
             pa.items.push_back(it);
             rec += G;
@@ -1251,7 +1252,7 @@ extern "C" int compact_prefix_decode_step(compact_ctx* ctx, const compact_weight
     hipStream_t s = (hipStream_t)hip_stream;
     // a plan built for one step covers every further step that opens no new chunk in any tail
     // (the record slots, hence the workspace, stay the same) and still fits the slabs
-    int k = -1, room = DECODE_CHUNK;
+    int k = -1, room = PREFIX_CHUNK;
     std::vector<int64_t> geom;
     if (ctx->step_cache && ctx->step_cache->valid && h_prefix_len && n_workers >= 1 && n_workers <= 64 &&
         shared->d_k && shared->d_v && shared->h_len && shared->h_capacity && shared->h_slab_offset && tails->d_k &&
@@ -1274,7 +1275,7 @@ extern "C" int compact_prefix_decode_step(compact_ctx* ctx, const compact_weight
             geom.push_back(tails->h_capacity[b]);
             geom.push_back(tails->h_slab_offset[b]);
             const int len = tails->h_len[b];
-            room = std::min(room, std::min(tails->h_capacity[b] - len, chunks_for(len + 1) * DECODE_CHUNK - len));
+            room = std::min(room, std::min(tails->h_capacity[b] - len, prefix_chunks_for(len + 1) * PREFIX_CHUNK - len));
         }
         Carver cv(d_workspace);
         DecodeBufs b;
@@ -1566,9 +1567,9 @@ extern "C" int compact_attn_decode(compact_ctx* ctx, int32_t n_blocks, const voi
 // device address).  The work list is written by a small kernel from values passed as
 // kernel arguments, so nothing is copied from host memory either.
 #define NOALLOC_MAX_BLOCKS 64
-#define NOALLOC_MAX_CHUNKS 2048
-#define NOALLOC_META_BYTES ((size_t)64 << 10)      // BlockMeta[64] (2 KB) + TileItem[2048] (16 KB)
-#define NOALLOC_PARTIAL_BYTES ((size_t)16 << 20)
+#define NOALLOC_MAX_CHUNKS 4096
+#define NOALLOC_META_BYTES ((size_t)64 << 10)      // BlockMeta[64] (2 KB) + TileItem[4096] (32 KB)
+#define NOALLOC_PARTIAL_BYTES ((size_t)32 << 20)
 static __device__ __align__(256) unsigned char scratch[NOALLOC_META_BYTES + NOALLOC_PARTIAL_BYTES];
 
 #define NOALLOC_MAX_DEVICES 64
@@ -1651,9 +1652,9 @@ extern "C" int compact_attn_decode_noalloc(compact_ctx* ctx, int32_t n_blocks, c
     }
     const int max_chunks = chunks_for(max_len);
     if (n_chunks > NOALLOC_MAX_CHUNKS)
-        return set_err(ctx, COMPACT_ECAPACITY, "more than 2048 chunks of 256 cached rows in total: beyond the fixed scratch of the allocation-free entry point");
+        return set_err(ctx, COMPACT_ECAPACITY, "more than 4096 chunks of 256 cached rows in total: beyond the fixed scratch of the allocation-free entry point");
     if (attn_decode_partial_floats(ctx->cfg, n_blocks, max_chunks) * 4 > NOALLOC_PARTIAL_BYTES)
-        return set_err(ctx, COMPACT_ECAPACITY, "split-KV records (n_blocks * n_q_heads * chunks of the longest cache * (head_dim + 2) floats) exceed the 16 MiB scratch of the allocation-free entry point");
+        return set_err(ctx, COMPACT_ECAPACITY, "split-KV records (n_blocks * n_q_heads * chunks of the longest cache * (head_dim + 2) floats) exceed the 32 MiB scratch of the allocation-free entry point");
     hipStream_t s = (hipStream_t)hip_stream;
     unsigned char* base = nullptr;
     TRY(scratch_of_current_device(ctx, &base));

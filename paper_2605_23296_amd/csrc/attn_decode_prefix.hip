@@ -15,12 +15,12 @@
 #include "common.h"
 
 #define LOG2E 1.4426950408889634f
-#define PFX_WAVES (DECODE_CHUNK / 32)
+#define PFX_WAVES (PREFIX_CHUNK / 32)
 #define PFX_QCOLS 32   // query columns staged at a time (two MFMA column groups)
 
 __device__ __forceinline__ float pfx_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-#define PFX_PLD (DECODE_CHUNK + 8)   // bf16 per column of the shared probability tile (padded against bank conflicts)
+#define PFX_PLD (PREFIX_CHUNK + 8)   // bf16 per column of the shared probability tile (padded against bank conflicts)
 
 template <int HD>
 __global__ __launch_bounds__(PFX_WAVES * 64, 4) void attn_decode_prefix_kernel(const BlockMeta* __restrict__ tail_meta,
@@ -35,7 +35,7 @@ __global__ __launch_bounds__(PFX_WAVES * 64, 4) void attn_decode_prefix_kernel(c
     constexpr int KS = HD / 32;            // k-steps of the QK product
     constexpr int DT = HD / 16;            // 16-row tiles of O^T, one per wavefront (the first DT wavefronts)
     constexpr int PLD = HD + 2;            // record: HD values, max, sum
-    constexpr int VS = DECODE_CHUNK / 32;  // k-steps of the PV product
+    constexpr int VS = PREFIX_CHUNK / 32;  // k-steps of the PV product
     __shared__ __attribute__((aligned(16))) bf16 qs[PFX_QCOLS * HD];    // query rows of the staged columns
     __shared__ __attribute__((aligned(16))) bf16 ps[16 * PFX_PLD];      // P^T of the current column group: [column][item row]
     __shared__ float s_max[PFX_WAVES][16], s_sum[PFX_WAVES][16];        // per-window maximum and sum of every column
@@ -51,7 +51,7 @@ __global__ __launch_bounds__(PFX_WAVES * 64, 4) void attn_decode_prefix_kernel(c
     int cap, n_rows;   // rows of the item that exist at all
     if (it.tail) {
         const BlockMeta bm = tail_meta[it.w0];
-        n_rows = min(bm.len + step + 1 - it.row0, DECODE_CHUNK);
+        n_rows = min(bm.len + step + 1 - it.row0, PREFIX_CHUNK);
         if (n_rows <= 0) return;   // a tail chunk this step does not reach yet
         cap = bm.capacity;
         kslab = ktail + bm.slab + (size_t)kvh * cap * HD;
@@ -90,7 +90,7 @@ __global__ __launch_bounds__(PFX_WAVES * 64, 4) void attn_decode_prefix_kernel(c
             vf[j] = *reinterpret_cast<const bf16x8*>(vp + voff);
         }
         // rows past the item's end must not reach the MFMA (their probabilities are zero, their bits are anything)
-        if (n_rows < DECODE_CHUNK) {
+        if (n_rows < PREFIX_CHUNK) {
 #pragma unroll
             for (int j = 0; j < VS; ++j)
 #pragma unroll

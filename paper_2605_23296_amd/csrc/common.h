@@ -17,9 +17,12 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 #define WAVE 64
 
-// Chunk of cached tokens handled by one decode-attention workgroup.  Fixed, so
-// that the split of a block's cache depends on that block's length only.
+// Chunk of cached tokens that gives one split-KV record of the decode attention
+// (one work item of its kernel).  Fixed, so that the split of a block's cache
+// depends on that block's length only.
 #define DECODE_CHUNK 256
+// The same for the prefix-aware (cascade) decode attention.
+#define PREFIX_CHUNK 256
 // Query rows per prefill-attention tile and token rows per rotary/KV-write tile.
 #define PREFILL_QTILE 128
 #define ROPE_TILE 64

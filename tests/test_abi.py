@@ -161,9 +161,9 @@ def test_no_alloc_decode_attention_checks_its_limits_without_a_device():
     kv, keep = _kv([16] * 65, [8] * 65)
     assert L.compact_attn_decode_noalloc(lay.ctx, 65, q, C.byref(kv), o, None) == 3        # more than 64 blocks
     assert b"64 blocks" in L.compact_last_error(lay.ctx)
-    kv, keep = _kv([4104] * 64, [4100] * 64)
-    assert L.compact_attn_decode_noalloc(lay.ctx, 64, q, C.byref(kv), o, None) == 3        # records beyond 16 MiB
-    assert b"16 MiB" in L.compact_last_error(lay.ctx)
+    kv, keep = _kv([8208] * 64, [8200] * 64)
+    assert L.compact_attn_decode_noalloc(lay.ctx, 64, q, C.byref(kv), o, None) == 3        # records beyond 32 MiB
+    assert b"32 MiB" in L.compact_last_error(lay.ctx)
     kv, keep = _kv([16], [17])
     assert L.compact_attn_decode_noalloc(lay.ctx, 1, q, C.byref(kv), o, None) == 3         # h_len beyond the slab
     kv, keep = _kv([16], [8])

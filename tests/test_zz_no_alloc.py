@@ -80,11 +80,11 @@ def test_no_alloc_decode_attention_rejects_sizes_beyond_its_scratch():
     with pytest.raises(B.CompactError) as e:
         lay.compact_attn_decode_noalloc(q, kv, o)
     assert e.value.code == 3 and "64 blocks" in e.value.detail
-    # 32 heads x 130 floats x 9 chunks x 64 blocks fits; 64 blocks x 17 chunks x 32 x 130 x 4 = 18.1 MB does not
-    kv2 = B.KVCache(layer, [4104] * 64, DEV, torch.bfloat16)
+    # 64 blocks x 32 heads x 9 chunks x 130 floats fit; 64 blocks x 33 chunks x 32 x 130 x 4 = 35 MB do not
+    kv2 = B.KVCache(layer, [8208] * 64, DEV, torch.bfloat16)
     for b in range(64):
-        kv2.h_len[b] = 4100
+        kv2.h_len[b] = 8200
     q2 = rnd((64, layer.n_q_heads * layer.head_dim), 28)
     with pytest.raises(B.CompactError) as e:
         lay.compact_attn_decode_noalloc(q2, kv2, torch.empty_like(q2))
-    assert e.value.code == 3 and "16 MiB" in e.value.detail
+    assert e.value.code == 3 and "32 MiB" in e.value.detail
