@@ -37,8 +37,13 @@
  *    compact_last_error() gives a readable detail.  All argument validation
  *    happens before the first HIP call.
  *  - Results are deterministic run to run, and a block's results do not
- *    depend on which other blocks share the call (no work split is chosen
- *    from the batch).
+ *    depend on which other blocks share the call nor on its place among
+ *    them: no work split is chosen from the batch, with one exception.  The
+ *    decode projections come in one kernel family for at most 16 blocks and
+ *    one for 17 .. 64 (a third, the prefill kernels, beyond 64): the caches
+ *    and every output are bit-identical within a family; across the two, the
+ *    caches still are, the outputs agree to rounding (the down projection
+ *    adds over K in another order).
  */
 #ifndef COMPACT_H
 #define COMPACT_H

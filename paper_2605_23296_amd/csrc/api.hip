@@ -655,10 +655,18 @@ static int decode_impl(compact_ctx* ctx, const compact_weights* w, int n_blocks,
     const void* ffn_in = b.m;
     RowNorm rn{};
     bool pending_norm = false;
-    if (bf && resid_norm_stream_supported(N, c.d_model, Dq)) {
+    // (17 .. 64 rows: the same kernels with several groups of 16 rows per weight fragment, used where the kernel for
+    // at most 16 rows covers the shape too, so that both split K alike and a row's bits do not depend on the batch)
+    const bool o_few = bf && resid_norm_stream_supported(N, c.d_model, Dq);
+    const bool o_many = bf && !o_few && stream_mt_supported(N, c.d_model, Dq) && resid_norm_stream_supported(16, c.d_model, Dq);
+    if (o_few || o_many) {
         ProfileScope ps(ctx, COMPACT_K_GEMM_SKINNY, s);
-        TRY(launch_resid_norm_stream(ctx, (const bf16*)b.o, (const bf16*)w->w_o, (const bf16*)x, (const bf16*)w->g_ffn, b.h,
-                                     (bf16*)b.hg, b.ssq_parts, N, c.d_model, Dq, s));
+        if (o_few)
+            TRY(launch_resid_norm_stream(ctx, (const bf16*)b.o, (const bf16*)w->w_o, (const bf16*)x, (const bf16*)w->g_ffn, b.h,
+                                         (bf16*)b.hg, b.ssq_parts, N, c.d_model, Dq, s));
+        else
+            TRY(launch_resid_norm_stream_mt(ctx, (const bf16*)b.o, (const bf16*)w->w_o, (const bf16*)x, (const bf16*)w->g_ffn,
+                                            b.h, (bf16*)b.hg, b.ssq_parts, N, c.d_model, Dq, s));
         rn.ssq_parts = b.ssq_parts;
         rn.nparts = c.d_model / 16;
         rn.inv_d = 1.0f / (float)c.d_model;
@@ -674,6 +682,10 @@ static int decode_impl(compact_ctx* ctx, const compact_weights* w, int n_blocks,
             ProfileScope ps(ctx, COMPACT_K_GEMM_SKINNY, s);
             TRY(launch_gemm_skinny_swiglu(ctx, (const bf16*)ffn_in, (const bf16*)w->w_gate_up, (bf16*)b.act, N, c.ffn_dim,
                                           c.d_model, pending_norm ? &rn : nullptr, s));
+        } else if (bf && swiglu_mt_supported(N, c.ffn_dim, c.d_model) && skinny_swiglu_supported(16, c.ffn_dim, c.d_model)) {
+            ProfileScope ps(ctx, COMPACT_K_GEMM_SKINNY, s);
+            TRY(launch_swiglu_mt(ctx, (const bf16*)ffn_in, (const bf16*)w->w_gate_up, (bf16*)b.act, N, c.ffn_dim, c.d_model,
+                                 pending_norm ? &rn : nullptr, s));
         } else {
             if (pending_norm) {
                 TRY(launch_rownorm_apply(ctx, (const bf16*)b.hg, rn, (bf16*)b.m, N, c.d_model, s));
@@ -687,6 +699,8 @@ static int decode_impl(compact_ctx* ctx, const compact_weights* w, int n_blocks,
             TRY(launch_resid_out_stream(ctx, (const bf16*)b.act, (const bf16*)w->w_down, b.h, (bf16*)y, N, c.d_model,
                                         c.ffn_dim, s));
         } else {
+            // (more than 16 rows: a whole-K workgroup would have to pull all M x F activations through L2 for its 16 columns,
+            // four times the weight bytes at 64 rows; measured 49 us against 31 us for split-K + reduce on the 8B-shaped layer)
             TRY(gemm_partials(ctx, b.act, w->w_down, b.partials, N, c.d_model, c.ffn_dim, &ks, s));
             TRY(launch_residual_reduce(ctx, b.partials, ks, b.h, y, N, c.d_model, s));
         }

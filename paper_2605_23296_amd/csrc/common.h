@@ -219,6 +219,15 @@ int launch_resid_norm_stream(compact_ctx* ctx, const bf16* X, const bf16* W, con
 bool resid_out_stream_supported(int M, int N, int K);
 int launch_resid_out_stream(compact_ctx* ctx, const bf16* X, const bf16* W, const float* resid, bf16* y, int M, int N, int K,
                             hipStream_t s);
+// gemv_stream_mt.hip : the output projection (+ residual, RMSNorm statistics) and the fused gate/up projection for
+// 17 .. 64 rows, whole K (same split over K and summation order as the kernels for at most 16 rows, so a row's result
+// does not depend on how many rows share the step)
+bool stream_mt_supported(int M, int N, int K);
+int launch_resid_norm_stream_mt(compact_ctx* ctx, const bf16* X, const bf16* W, const bf16* resid, const bf16* g, float* h_out,
+                                bf16* hg_out, float* ssq_parts, int M, int N, int K, hipStream_t s);
+bool swiglu_mt_supported(int M, int F, int K);
+int launch_swiglu_mt(compact_ctx* ctx, const bf16* X, const bf16* W, bf16* act, int M, int F, int K, const RowNorm* norm,
+                     hipStream_t s);
 // m = bf16(hg / rms): finishes the RMSNorm whose sums of squares are in `norm`
 int launch_rownorm_apply(compact_ctx* ctx, const bf16* hg, const RowNorm& norm, bf16* m, int rows, int d, hipStream_t s);
 
