@@ -399,6 +399,8 @@ int launch_attn_decode_bf16(compact_ctx* ctx, const BlockMeta* d_meta, const Til
     HIP_TRY(ctx, hipGetDevice(&dev));
     HIP_TRY(ctx, hipDeviceGetAttribute(&n_cus, hipDeviceAttributeMultiprocessorCount, dev));
     const int64_t n_work = (int64_t)n_chunks * c.n_kv_heads;
+    // as many workgroups as stay resident (measured: fewer, evenly loaded ones -- 544 x 2 items instead of 768 x 1-2 --
+    // and more than stay resident are both slower)
     dim3 grid((unsigned)std::min<int64_t>(n_work, (int64_t)n_cus * DEC_MAX_GROUPS(c.head_dim)));
     dim3 cgrid(c.n_q_heads, n_blocks);
     const int64_t n_rec = (int64_t)n_blocks * c.n_q_heads * max_chunks;   // records the partial buffer is laid out for
