@@ -174,9 +174,10 @@ static size_t max_partial_cols(const compact_layer_cfg& c) {
 
 static int moe_mtile(const compact_layer_cfg& c) { return c.dtype == COMPACT_BF16 ? gemm_bf16_mtile() : gemm_f32_mtile(); }
 
-static void carve_moe_plan(Carver& cv, const compact_layer_cfg& c, int64_t rows, MoePlan& plan) {
+// mt = rows per tile of the plan's tile map: the row tile of the prefill-size expert GEMMs, or 16 for the decode
+// steps' per-expert streaming
+static void carve_moe_plan(Carver& cv, const compact_layer_cfg& c, int64_t rows, MoePlan& plan, int mt) {
     const int64_t rk = rows * c.top_k;
-    const int mt = moe_mtile(c);
     plan.max_mtiles = (int32_t)(rk / mt + c.n_experts + 1);
     plan.counts = (int32_t*)cv.take(sizeof(int32_t) * c.n_experts);
     plan.offsets = (int32_t*)cv.take(sizeof(int32_t) * (c.n_experts + 1));
@@ -204,7 +205,7 @@ static void carve_prefill(Carver& cv, const compact_layer_cfg& c, int64_t T, Pre
         b.logits = (float*)cv.take((size_t)T * c.n_experts * 4);
         b.idx = (int32_t*)cv.take((size_t)T * c.top_k * 4);
         b.gate = (float*)cv.take((size_t)T * c.top_k * 4);
-        carve_moe_plan(cv, c, T, b.plan);
+        carve_moe_plan(cv, c, T, b.plan, moe_mtile(c));
         b.expert_out = cv.take((size_t)T * c.top_k * c.d_model * es);
     }
 }
@@ -228,7 +229,7 @@ static void carve_decode(Carver& cv, const compact_layer_cfg& c, int N, int max_
         b.logits = (float*)cv.take((size_t)N * c.n_experts * 4);
         b.idx = (int32_t*)cv.take((size_t)N * c.top_k * 4);
         b.gate = (float*)cv.take((size_t)N * c.top_k * 4);
-        carve_moe_plan(cv, c, N, b.plan);
+        carve_moe_plan(cv, c, N, b.plan, 16);
         b.expert_out = cv.take((size_t)N * c.top_k * c.d_model * es);
     }
 }
@@ -709,16 +710,18 @@ static int decode_impl(compact_ctx* ctx, const compact_weights* w, int n_blocks,
         int32_t* idx = route && route->d_expert_idx ? route->d_expert_idx : b.idx;
         float* gate = route && route->d_gate ? route->d_gate : b.gate;
         TRY(launch_moe_route(ctx, b.m, w->w_router, N, idx, gate, b.logits, s, b.partials));
-        if (bf && N <= 16) {
+        if (bf && N * c.top_k <= 256) {
             // few rows per expert: stream every routed expert's weights once (split-K
             // partials in the expert-sorted row order), SwiGLU, down projection, and a
-            // combine that applies the gate weights to the fp32 sums
+            // combine that applies the gate weights to the fp32 sums.  The routing plan (one
+            // workgroup, at most 256 routed rows = 64 blocks at top-4) cuts every expert's rows
+            // into tiles of 16, one grid slice each: an expert with more than 16 rows (possible
+            // beyond 16 blocks) is streamed once per tile.
             const int rk = N * c.top_k;
-            TRY(launch_moe_plan(ctx, idx, gate, N, moe_mtile(c), b.plan, s));
+            TRY(launch_moe_plan(ctx, idx, gate, N, 16, b.plan, s));
             const bool q4 = w->w_exp_gate_up_q != nullptr;   // block-scaled 4-bit copy of the experts
-            // every routed expert has at most N <= 16 rows, i.e. exactly one tile of the plan's tile map:
-            // that map lists the routed experts (then -1), so only min(rk, E) grid slices are launched
-            const int n_listed = std::min(rk, c.n_experts);
+            // the tile map lists the tiles (then -1): at most one per routed row, and no more than experts + rows / 16
+            const int n_listed = std::min(rk, c.n_experts + rk / 16);
             const int ks1 = q4 ? mxfp4_ksplit(c.d_model) : skinny_ksplit(1, 2 * c.ffn_dim, c.d_model);
             {
                 ProfileScope ps(ctx, COMPACT_K_GEMM_SKINNY, s);
@@ -726,11 +729,12 @@ static int decode_impl(compact_ctx* ctx, const compact_weights* w, int n_blocks,
                     TRY(launch_gemm_skinny_grouped_mxfp4(ctx, (const bf16*)b.m, b.plan.sorted_token,
                                                          (const uint8_t*)w->w_exp_gate_up_q, (const uint8_t*)w->w_exp_gate_up_s,
                                                          b.plan.offsets, c.n_experts, rk, b.partials, 2 * c.ffn_dim, c.d_model,
-                                                         ks1, s, b.plan.tile_expert, n_listed));
+                                                         ks1, s, b.plan.tile_expert, n_listed, b.plan.tile_row0, b.plan.tile_rows));
                 else
                     TRY(launch_gemm_skinny_grouped(ctx, (const bf16*)b.m, b.plan.sorted_token, (const bf16*)w->w_exp_gate_up,
                                                    (int64_t)2 * c.ffn_dim * c.d_model, b.plan.offsets, c.n_experts, rk,
-                                                   b.partials, 2 * c.ffn_dim, c.d_model, ks1, s, b.plan.tile_expert, n_listed));
+                                                   b.partials, 2 * c.ffn_dim, c.d_model, ks1, s, b.plan.tile_expert, n_listed,
+                                                   b.plan.tile_row0, b.plan.tile_rows));
             }
             TRY(launch_swiglu_reduce(ctx, b.partials, ks1, b.act, rk, c.ffn_dim, s));
             const int ks2 = q4 ? mxfp4_ksplit(c.ffn_dim) : skinny_ksplit(1, c.d_model, c.ffn_dim);
@@ -739,11 +743,13 @@ static int decode_impl(compact_ctx* ctx, const compact_weights* w, int n_blocks,
                 if (q4)
                     TRY(launch_gemm_skinny_grouped_mxfp4(ctx, (const bf16*)b.act, nullptr, (const uint8_t*)w->w_exp_down_q,
                                                          (const uint8_t*)w->w_exp_down_s, b.plan.offsets, c.n_experts, rk,
-                                                         b.partials, c.d_model, c.ffn_dim, ks2, s, b.plan.tile_expert, n_listed));
+                                                         b.partials, c.d_model, c.ffn_dim, ks2, s, b.plan.tile_expert, n_listed,
+                                                         b.plan.tile_row0, b.plan.tile_rows));
                 else
                     TRY(launch_gemm_skinny_grouped(ctx, (const bf16*)b.act, nullptr, (const bf16*)w->w_exp_down,
                                                    (int64_t)c.d_model * c.ffn_dim, b.plan.offsets, c.n_experts, rk, b.partials,
-                                                   c.d_model, c.ffn_dim, ks2, s, b.plan.tile_expert, n_listed));
+                                                   c.d_model, c.ffn_dim, ks2, s, b.plan.tile_expert, n_listed, b.plan.tile_row0,
+                                                   b.plan.tile_rows));
             }
             TRY(launch_moe_combine_partials(ctx, b.partials, ks2, rk, b.h, b.plan.slot_of, b.plan.sorted_gate, N, y, s));
         } else {
@@ -1723,7 +1729,7 @@ extern "C" int compact_moe_ffn(compact_ctx* ctx, const compact_weights* w, const
     Carver cv(d_workspace);
     void* act = cv.take((size_t)rows * c.top_k * c.ffn_dim * es);
     MoePlan plan;
-    carve_moe_plan(cv, c, rows, plan);
+    carve_moe_plan(cv, c, rows, plan, moe_mtile(c));
     void* expert_out = cv.take((size_t)rows * c.top_k * c.d_model * es);
     if (!d_workspace || cv.off > ws_bytes) return set_err(ctx, COMPACT_EWORKSPACE, "workspace too small for the expert feed-forward");
     return moe_ffn_rows(ctx, w, d_m, d_h, false, d_expert_idx, d_gate, rows, act, plan, expert_out, d_y, (hipStream_t)hip_stream);

@@ -183,7 +183,8 @@ int launch_mxfp4_dequant(compact_ctx* ctx, const uint8_t* codes, const uint8_t* 
 int launch_gemm_skinny_grouped_mxfp4(compact_ctx* ctx, const bf16* X, const int32_t* a_gather, const uint8_t* Wq,
                                      const uint8_t* Ws, const int32_t* offsets, int n_experts, int total_rows,
                                      float* partials, int N, int K, int ks, hipStream_t s,
-                                     const int32_t* expert_list = nullptr, int n_listed = 0);
+                                     const int32_t* expert_list = nullptr, int n_listed = 0,
+                                     const int32_t* tile_row0 = nullptr, const int32_t* tile_rows = nullptr);
 
 // gemm_skinny.hip : partials[ks][M][N] (fp32) = A[M,K] B[N,K]^T split over K
 int skinny_ksplit(int M, int N, int K);
@@ -197,9 +198,11 @@ bool skinny_norm_in_supported(int M, int N, int K);
 // given); partials[ks][total_rows][N] keep the sorted order
 int launch_gemm_skinny_grouped(compact_ctx* ctx, const bf16* X, const int32_t* a_gather, const bf16* W, int64_t w_expert_stride,
                                const int32_t* offsets, int n_experts, int total_rows, float* partials, int N, int K, int ks,
-                               hipStream_t s, const int32_t* expert_list = nullptr, int n_listed = 0);
-// expert_list (nullable): the experts to run, one per grid slice, -1 = none (the tile map of the
-// routing plan when no expert has more rows than a tile); spares launching a slice per idle expert
+                               hipStream_t s, const int32_t* expert_list = nullptr, int n_listed = 0,
+                               const int32_t* tile_row0 = nullptr, const int32_t* tile_rows = nullptr);
+// expert_list (nullable): the experts to run, one per grid slice, -1 = none; spares launching a slice per idle
+// expert.  With tile_row0 / tile_rows (the routing plan's tile map, tiles of at most 16 rows) a grid slice is a
+// tile: an expert with more than 16 rows is streamed once per tile of 16
 // decode gate/up projection with the SwiGLU fused in (no partials): act[M, F] =
 // silu(r X Wg^T) * (r X Wu^T); X may hold un-normalised rows (x * g) whose 1/rms r
 // comes from `norm` (null: r = 1)

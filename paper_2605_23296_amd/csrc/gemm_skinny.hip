@@ -27,9 +27,14 @@ int skinny_ksplit(int M, int N, int K) {
 // of the expert-sorted order (at most MT*16 of them), read from X through
 // a_gather (null: X is already in sorted order), multiplied with that expert's
 // weight matrix, and the partials keep the sorted order: P[slice][sorted row][N].
-// Experts nobody was routed to leave at once.
+// Experts nobody was routed to leave at once.  With a tile map (expert_list =
+// the map's experts, tile_row0 / tile_rows its row ranges, tiles of at most MT*16
+// rows) blockIdx.z is a tile: an expert with more rows than a tile holds is
+// streamed once per tile.
 struct SkinnyGroup {
     const int32_t* expert_list;  // [gridDim.z] experts to run, -1 = none (null: expert = blockIdx.z)
+    const int32_t* tile_row0;    // [gridDim.z] first sorted row of the tile (null: the expert's first row)
+    const int32_t* tile_rows;    // [gridDim.z] rows of the tile (null: all of the expert's rows)
     const int32_t* offsets;   // [E + 1]
     const int32_t* a_gather;  // [total_rows] or null
     int64_t w_expert_stride;  // elements
@@ -58,8 +63,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const bf16* __r
     if (GROUPED) {
         const int e = grp.expert_list ? grp.expert_list[blockIdx.z] : (int)blockIdx.z;
         if (e < 0) return;
-        row_base = grp.offsets[e];
-        M = min(grp.offsets[e + 1] - row_base, MT * 16);
+        row_base = grp.tile_row0 ? grp.tile_row0[blockIdx.z] : grp.offsets[e];
+        M = min(grp.tile_rows ? grp.tile_rows[blockIdx.z] : grp.offsets[e + 1] - row_base, MT * 16);
         if (M <= 0) return;
         W += (size_t)e * grp.w_expert_stride;
         p_rows = grp.total_rows;
@@ -333,10 +338,11 @@ int launch_gemm_skinny(compact_ctx* ctx, const bf16* A, const bf16* B, float* pa
 // partials[ks][total_rows][N], rows in expert-sorted order.
 int launch_gemm_skinny_grouped(compact_ctx* ctx, const bf16* X, const int32_t* a_gather, const bf16* W, int64_t w_expert_stride,
                                const int32_t* offsets, int n_experts, int total_rows, float* partials, int N, int K, int ks,
-                               hipStream_t s, const int32_t* expert_list, int n_listed) {
+                               hipStream_t s, const int32_t* expert_list, int n_listed, const int32_t* tile_row0,
+                               const int32_t* tile_rows) {
     if (N % 16 != 0 || K % 64 != 0) return set_err(ctx, COMPACT_ESHAPE, "weight-streaming GEMM needs N % 16 == 0 and K % 64 == 0");
     if (ks != skinny_ksplit(1, N, K)) return set_err(ctx, COMPACT_EINVAL, "unexpected K split");
-    SkinnyGroup g{expert_list, offsets, a_gather, w_expert_stride, total_rows};
+    SkinnyGroup g{expert_list, tile_row0, tile_rows, offsets, a_gather, w_expert_stride, total_rows};
     dim3 grid(ks, (N + 63) / 64, expert_list ? n_listed : n_experts);
     const size_t smem = (size_t)16 * (SKINNY_KSLICE + 8) * sizeof(bf16);
     gemm_skinny_kernel<1, true, 4><<<grid, 256, smem, s>>>(X, W, partials, 0, N, K, g, SkinnyNormIn{});

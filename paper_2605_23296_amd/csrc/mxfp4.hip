@@ -78,6 +78,8 @@ int launch_mxfp4_dequant(compact_ctx* ctx, const uint8_t* codes, const uint8_t* 
 // ---------------------------------------------------------------------------
 struct MxGroup {
     const int32_t* expert_list;  // [gridDim.z] experts to run, -1 = none (null: expert = blockIdx.z)
+    const int32_t* tile_row0;    // [gridDim.z] first sorted row of the grid slice's tile (null: the expert's first row)
+    const int32_t* tile_rows;    // [gridDim.z] its rows, at most 16 (null: all of the expert's rows)
     const int32_t* offsets;    // [E + 1] rows of every expert in the expert-sorted order
     const int32_t* a_gather;   // [total_rows] source row of X, or null (X already sorted)
     int64_t q_expert_stride;   // bytes between consecutive experts' codes
@@ -95,8 +97,8 @@ __global__ __launch_bounds__(256) void gemm_skinny_mxfp4_kernel(const bf16* __re
     const int r = lane & 15, c = lane >> 4;
     const int e = grp.expert_list ? grp.expert_list[blockIdx.z] : (int)blockIdx.z;
     if (e < 0) return;
-    const int row_base = grp.offsets[e];
-    const int M = min(grp.offsets[e + 1] - row_base, 16);
+    const int row_base = grp.tile_row0 ? grp.tile_row0[blockIdx.z] : grp.offsets[e];
+    const int M = min(grp.tile_rows ? grp.tile_rows[blockIdx.z] : grp.offsets[e + 1] - row_base, 16);
     if (M <= 0) return;   // nobody was routed to this expert
     Wq += (size_t)e * grp.q_expert_stride;
     Ws += (size_t)e * grp.s_expert_stride;
@@ -165,10 +167,10 @@ __global__ __launch_bounds__(256) void gemm_skinny_mxfp4_kernel(const bf16* __re
 int launch_gemm_skinny_grouped_mxfp4(compact_ctx* ctx, const bf16* X, const int32_t* a_gather, const uint8_t* Wq,
                                      const uint8_t* Ws, const int32_t* offsets, int n_experts, int total_rows,
                                      float* partials, int N, int K, int ks, hipStream_t s, const int32_t* expert_list,
-                                     int n_listed) {
+                                     int n_listed, const int32_t* tile_row0, const int32_t* tile_rows) {
     if (N % 16 != 0 || K % MX_BLOCK != 0) return set_err(ctx, COMPACT_ESHAPE, "4-bit weight streaming needs N % 16 == 0 and K % 32 == 0");
     if (ks != mxfp4_ksplit(K)) return set_err(ctx, COMPACT_EINVAL, "unexpected K split");
-    MxGroup g{expert_list, offsets, a_gather, (int64_t)N * (K / 2), (int64_t)N * (K / MX_BLOCK), total_rows};
+    MxGroup g{expert_list, tile_row0, tile_rows, offsets, a_gather, (int64_t)N * (K / 2), (int64_t)N * (K / MX_BLOCK), total_rows};
     dim3 grid(ks, (N + 63) / 64, expert_list ? n_listed : n_experts);
     const size_t smem = (size_t)16 * (MX_KSLICE + 8) * sizeof(bf16);
     gemm_skinny_mxfp4_kernel<<<grid, 256, smem, s>>>(X, Wq, Ws, partials, N, K, g);

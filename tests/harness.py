@@ -109,6 +109,8 @@ def check_routing(idx_gpu, logits_ref, k, margin_rel, gate_gpu=None):
     logits_ref = np.asarray(logits_ref).reshape(idx_gpu.shape[0], -1)
     order = np.argsort(-logits_ref, axis=-1, kind="stable")
     srt = np.take_along_axis(logits_ref, order, axis=-1)
+    if srt.shape[1] == k:       # every expert is chosen: no runner-up
+        srt = np.concatenate([srt, np.full((srt.shape[0], 1), -np.inf)], axis=1)
     margin = margin_rel * np.abs(logits_ref).max()
     gaps = srt[:, :k] - srt[:, 1:k + 1]                    # gap j: between the j-th and (j+1)-th largest
     set_safe = gaps[:, k - 1] > margin

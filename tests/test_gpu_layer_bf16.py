@@ -180,6 +180,8 @@ def check_moe(inp, margin_rel, fp32=False):
         log.cmp("y_dec%d" % s, g["y_decode"][s], lay.ffn(h_ref, forced_idx=g["idx_decode"][s])[0])
     total = inp.cu_seqlens[-1] + S * N
     log.check("rows with a close call: %d of %d (all compared) |" % (n_unsafe, total))
+    # the most rows any expert received in one decode step
+    return max(int(np.bincount(np.asarray(g["idx_decode"][s]).reshape(-1)).max()) for s in range(S)) if S else 0
 
 
 SMALL_MOE = LayerConfig(d_model=256, n_q_heads=8, n_kv_heads=2, head_dim=64, ffn_dim=320, n_experts=16, top_k=4,
@@ -203,3 +205,25 @@ def test_moe_120b_shape_reduced():
     layer.n_experts = 16            # same expert shape, fewer experts: bounds the checker's time
     wl = Workload("moe_reduced", layer, [200, 65], 2, 2)
     check_moe(make_inputs(wl), margin_rel=2e-2)
+
+
+@pytest.mark.parametrize("n_blocks", [17, 40, 64])
+def test_small_moe_layer_17_to_64_blocks(n_blocks):
+    """Routed decode steps with more than 16 blocks: every routed expert's weights are streamed once for up to 64 rows
+    (experts here receive 0 .. 30 rows: one to two groups of 16, empty experts, and with 64 blocks 256 routed rows, the
+    most the one-workgroup routing plan takes).  Routing tables and every row against the checker."""
+    lens = [(5 * b) % 23 + 1 for b in range(n_blocks)]
+    wl = Workload("small_moe", copy.deepcopy(SMALL_MOE), lens, n_blocks, 2)
+    most = check_moe(make_inputs(wl), margin_rel=2e-2)
+    assert most > 16 or n_blocks < 40, most      # some expert needs more than one group of 16 rows
+
+
+def test_moe_120b_shape_24_blocks_every_expert_takes_every_row():
+    """The 120B-shaped experts (d 2880, F 2880), 24 blocks, eight experts and top-8: every expert receives all 24 rows
+    of a step, i.e. two groups of 16 rows (the second half full) per expert in the streaming kernels."""
+    layer = copy.deepcopy(WORKLOADS["moe_16x8192"].layer)
+    layer.n_experts = 8
+    layer.top_k = 8
+    wl = Workload("moe_reduced", layer, [9] * 24, 24, 2)
+    most = check_moe(make_inputs(wl), margin_rel=2e-2)
+    assert most == 24
