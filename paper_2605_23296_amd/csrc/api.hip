@@ -18,6 +18,18 @@ int set_err(compact_ctx* ctx, int code, const std::string& msg) {
     return code;
 }
 
+int device_cu_count(compact_ctx* ctx, int* n_cus) {
+    if (ctx->n_cus <= 0) {
+        int dev = 0, n = 0;
+        HIP_TRY(ctx, hipGetDevice(&dev));
+        HIP_TRY(ctx, hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev));
+        if (n <= 0) return set_err(ctx, COMPACT_EHIP, "device reports no compute units");
+        ctx->n_cus = n;
+    }
+    *n_cus = ctx->n_cus;
+    return COMPACT_OK;
+}
+
 // ---------------------------------------------------------------------------
 // profiling
 // ---------------------------------------------------------------------------

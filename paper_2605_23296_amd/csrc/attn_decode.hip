@@ -395,9 +395,8 @@ int launch_attn_decode_bf16(compact_ctx* ctx, const BlockMeta* d_meta, const Til
     if (n_chunks == 0) return COMPACT_OK;
     if (!d_qrow) q_stride = c.n_q_heads * c.head_dim;   // q [n_blocks, Hq * hd], row b for block b
     // persistent workgroups: as many as stay resident (DEC_MAX_GROUPS per CU), each with a contiguous share
-    int n_cus = 0, dev = 0;
-    HIP_TRY(ctx, hipGetDevice(&dev));
-    HIP_TRY(ctx, hipDeviceGetAttribute(&n_cus, hipDeviceAttributeMultiprocessorCount, dev));
+    int n_cus = 0;
+    if (int rc = device_cu_count(ctx, &n_cus)) return rc;
     const int64_t n_work = (int64_t)n_chunks * c.n_kv_heads;
     // as many workgroups as stay resident (measured: fewer, evenly loaded ones -- 544 x 2 items instead of 768 x 1-2 --
     // and more than stay resident are both slower)

@@ -80,6 +80,7 @@ struct compact_ctx {
     size_t prof_used = 0;
     int64_t prof_launches = 0;
     double prof_ms = 0.0;
+    int n_cus = 0;                       // compute units of the device, 0 = not looked up yet
 };
 
 // RAII-free helper used by launchers: brackets a launch with events when its
@@ -94,6 +95,8 @@ struct ProfileScope {
 };
 
 int set_err(compact_ctx* ctx, int code, const std::string& msg);
+// compute units of the current device (looked up once per context); COMPACT_OK or an error code
+int device_cu_count(compact_ctx* ctx, int* n_cus);
 #define HIP_TRY(ctx, expr)                                                             \
     do {                                                                               \
         hipError_t _e = (expr);                                                        \
