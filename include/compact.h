@@ -107,8 +107,8 @@ typedef struct compact_weights {
      * FP4 E2M1 elements, two per byte with the even-indexed element in the low nibble
      * (*_q: uint8 [E, rows, K/2]), and one E8M0 scale 2^(e-127) per 32 consecutive
      * elements along K (*_s: uint8 [E, rows, K/32]; e in 8..246, 255 = NaN is not
-     * supported).  All four or none.  When given, decode steps with at most 16 rows
-     * stream these instead of the 16-bit copy, which must then hold exactly their
+     * supported).  All four or none.  When given, decode steps with at most 256
+     * routed rows (blocks x top_k: 64 blocks at top-4) stream these instead of the 16-bit copy, which must then hold exactly their
      * expanded values (compact_mxfp4_dequant writes them); bf16 storage only.      */
     const void* w_exp_gate_up_q;
     const void* w_exp_gate_up_s;
