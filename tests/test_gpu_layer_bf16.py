@@ -149,6 +149,17 @@ def test_dense_decode_with_17_to_64_blocks(n_blocks):
         assert vec_rel_err(g["y_decode"][:, 0], full["y_decode"][:, b]) < 4e-3
 
 
+@pytest.mark.parametrize("n_blocks", [20, 47])
+def test_dense_decode_with_17_to_64_blocks_at_the_smallest_shapes(n_blocks):
+    """The 17..64-row kernels at the smallest contraction lengths they take (output projection K = 2048,
+    gate/up K = 2048, an FFN width of 17 workgroups of 64 columns), two and three groups of 16 rows:
+    every row against the checker."""
+    layer = LayerConfig(d_model=2048, n_q_heads=16, n_kv_heads=4, head_dim=128, ffn_dim=1088, rope_theta=500000.0, dtype="bf16")
+    lens = [(11 * b) % 37 + 1 for b in range(n_blocks)]
+    inp = make_inputs(Workload("edge_rows", layer, lens, n_blocks, 2), gain_jitter=True)
+    check_dense(inp, sampled=False)
+
+
 def test_run_to_run_determinism():
     inp = make_inputs(WORKLOADS["dense_8x4096"], block_lens=[257, 300], decode_steps=2)
     a = H.gpu_forward(inp)
