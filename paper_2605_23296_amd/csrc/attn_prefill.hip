@@ -273,17 +273,39 @@ __global__ __launch_bounds__(PP ? 512 : 256, 2) void attn_prefill_bf16_kernel(co
                     if (tok > qrow) sacc[tt][e] = -INFINITY;
                 }
         }
-        float mx = -INFINITY;
+        // The running maximum is only a scaling reference.  The common case takes the probabilities
+        // against the reference as it stands and looks at nothing but their sum: while every lane's
+        // sum of its 32 values stays below 2^12, fp32 sums and bf16 probabilities carry them without
+        // loss and the tile's maximum is never formed.  Otherwise (always on the first tile, whose
+        // reference is -inf: the sum comes out inf or NaN) the exact maximum is taken, the reference
+        // moves there, the accumulators are rescaled and the probabilities are formed again.
+        auto probs = [&]() {
+            const float neg_m = -m_run;
+            float ps = 0.f;
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt)
+            for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[tt][e]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;
-        // The running maximum is only a scaling reference: it is moved (and the
-        // accumulators rescaled) when some row's scores outgrow it by more than 2^8;
-        // until then exp2 stays within a factor 256 of 1, which fp32 sums and bf16
-        // probabilities carry without loss.  The first tile always takes this path.
-        if (__any(mx > m_run + 8.0f)) {
+                for (int g8 = 0; g8 < 2; ++g8) {
+                    float pv[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        pv[j] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[tt][g8 * 8 + j], scale_log2, neg_m));
+                        ps += pv[j];
+                    }
+                    pf[tt * 2 + g8] = pack_bf16x8(pv);
+                }
+            return ps;
+        };
+        float ps = probs();
+        // (query columns past the block's end see unmasked cache rows past it -- whatever the slab holds --
+        // and must not take part in the decision: a row's bits may depend on its own block only)
+        if (__any(!(ps < 4096.0f) && qrow < len)) {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[tt][e]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;
             const float m_new = fmaxf(m_run, mx);   // finite: tile 0 holds token 0 <= every query row
             const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
             l_run *= corr;
@@ -292,21 +314,8 @@ __global__ __launch_bounds__(PP ? 512 : 256, 2) void attn_prefill_bf16_kernel(co
             for (int d = 0; d < DT; ++d)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) oacc[d][e] *= corr;
+            ps = probs();
         }
-        const float neg_m = -m_run;
-        float ps = 0.f;
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-            for (int g8 = 0; g8 < 2; ++g8) {
-                float pv[8];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    pv[j] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[tt][g8 * 8 + j], scale_log2, neg_m));
-                    ps += pv[j];
-                }
-                pf[tt * 2 + g8] = pack_bf16x8(pv);
-            }
         l_run += ps;
     };
     // ---- O^T += V^T P^T ---------------------------------------------------
