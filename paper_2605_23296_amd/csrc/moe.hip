@@ -18,19 +18,39 @@ __global__ __launch_bounds__(256) void topk_route_kernel(float* __restrict__ log
     if (row >= rows) return;
     const int lane = threadIdx.x & (WAVE - 1);
     float v[4];
+    if (ks > 0) {
+        // all partials of the lane's experts are requested before the first is used (slices in groups of
+        // 8), then added in slice order: the kernel is a few memory round trips long, not ks * 4
+        float a[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int s0 = 0; s0 < ks; s0 += 8) {
+            float pv[4][8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int e = lane + i * 64;
-        v[i] = -INFINITY;
-        if (e < E) {
-            if (ks > 0) {
-                float a = 0.f;
-                for (int sl = 0; sl < ks; ++sl) a += partials[((size_t)sl * rows + row) * E + e];
-                logits[row * E + e] = a;
-                v[i] = a;
-            } else {
-                v[i] = logits[row * E + e];
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int e = lane + i * 64;
+                    pv[i][u] = (e < E && s0 + u < ks) ? partials[((size_t)(s0 + u) * rows + row) * E + e] : 0.f;
+                }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (s0 + u < ks) a[i] += pv[i][u];
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int e = lane + i * 64;
+            v[i] = -INFINITY;
+            if (e < E) {
+                logits[row * E + e] = a[i];
+                v[i] = a[i];
             }
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int e = lane + i * 64;
+            v[i] = e < E ? logits[row * E + e] : -INFINITY;
         }
     }
     float sel_v[8];
@@ -314,16 +334,30 @@ __global__ __launch_bounds__(256) void moe_combine_partials_kernel(const float* 
     const int64_t row = blockIdx.y;
     const int c = (blockIdx.x * 256 + threadIdx.x) * 4;
     if (c >= d) return;
+    // the loads go out in three waves (all slots, then all gate weights, then per expert all its slices, 8 at a
+    // time) instead of one after the other; the sums keep their order: slices in slice order, experts in j order
+    constexpr int KMAX = 8;   // top_k <= 8
+    int64_t slot[KMAX];
+    float gw[KMAX];
+#pragma unroll
+    for (int j = 0; j < KMAX; ++j) slot[j] = slot_of[row * k + min(j, k - 1)];
+#pragma unroll
+    for (int j = 0; j < KMAX; ++j) gw[j] = sorted_gate[slot[j]];
     float4 acc = *reinterpret_cast<const float4*>(hres + row * d + c);
-    for (int j = 0; j < k; ++j) {
-        const int64_t slot = slot_of[row * k + j];
-        const float gw = sorted_gate[slot];
+#pragma unroll
+    for (int j = 0; j < KMAX; ++j) {
+        if (j >= k) break;
         float4 e = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int s = 0; s < ks; ++s) {
-            const float4 v = *reinterpret_cast<const float4*>(P + ((int64_t)s * total_rows + slot) * d + c);
-            e.x += v.x; e.y += v.y; e.z += v.z; e.w += v.w;
+        for (int s0 = 0; s0 < ks; s0 += 8) {
+            float4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                v[u] = *reinterpret_cast<const float4*>(P + ((int64_t)min(s0 + u, ks - 1) * total_rows + slot[j]) * d + c);
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (s0 + u < ks) { e.x += v[u].x; e.y += v[u].y; e.z += v[u].z; e.w += v[u].w; }
         }
-        acc.x += gw * e.x; acc.y += gw * e.y; acc.z += gw * e.z; acc.w += gw * e.w;
+        acc.x += gw[j] * e.x; acc.y += gw[j] * e.y; acc.z += gw[j] * e.z; acc.w += gw[j] * e.w;
     }
     bf16x4 o;
     o[0] = (bf16)acc.x; o[1] = (bf16)acc.y; o[2] = (bf16)acc.z; o[3] = (bf16)acc.w;
