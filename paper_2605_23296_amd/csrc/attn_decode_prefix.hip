@@ -200,9 +200,10 @@ __global__ __launch_bounds__(PFX_WAVES * 64, 4) void attn_decode_prefix_kernel(c
 // Merges the records of one (worker, head): the items on the worker's list.  Tail
 // chunks the step has not reached yet carry weight zero and are never read (nobody
 // wrote them).  256 threads: HD / 2 threads span a record, 512 / HD records are read
-// side by side; all sums run in a fixed order.
+// side by side, 16 loads in flight per thread (4: 30.6 us at 24 workers, 16: 24.5 us); all sums run in a fixed order.
 #define PFX_MAX_ITEMS 1024
 #define PFX_CT 256
+#define PFX_FLIGHT 16
 template <int HD>
 __global__ __launch_bounds__(PFX_CT) void attn_decode_prefix_combine_kernel(const BlockMeta* __restrict__ tail_meta,
                                                                             const PrefixItem* __restrict__ items,
@@ -258,21 +259,21 @@ __global__ __launch_bounds__(PFX_CT) void attn_decode_prefix_combine_kernel(cons
 #pragma unroll
     for (int i = 1; i < PFX_CT / 64; ++i) l += red[i];
     const int sl = t / TPR, e = t % TPR;
-    // four records in flight per thread; a record that carries no weight (a tail chunk nobody wrote)
+    // PFX_FLIGHT records in flight per thread; a record that carries no weight (a tail chunk nobody wrote)
     // is read from a valid address and dropped
     float2 acc = float2{0.f, 0.f};
-    for (int i0 = sl; i0 < n; i0 += 4 * NS) {
-        float2 v[4];
-        float wi[4];
+    for (int i0 = sl; i0 < n; i0 += PFX_FLIGHT * NS) {
+        float2 v[PFX_FLIGHT];
+        float wi[PFX_FLIGHT];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < PFX_FLIGHT; ++u) {
             const int i = i0 + u * NS;
             wi[u] = i < n ? wgt[i] : 0.f;
             const int ro = i < n ? max(roff[i], 0) : 0;
             v[u] = *reinterpret_cast<const float2*>(base + (size_t)ro * PLD + 2 * e);
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < PFX_FLIGHT; ++u)
             if (wi[u] != 0.f) {
                 acc.x += wi[u] * v[u].x;
                 acc.y += wi[u] * v[u].y;

@@ -34,6 +34,10 @@ def fill_cache(kv, b, K, V):
     ("moe_16x8192", [64, 300, 301], [5, 1, 257]),                             # head_dim 64, group of 8
     ("dense_8x4096", [0, 0, 40], [3, 1, 2]),                                  # workers without any prefix
     ("dense_8x4096", [90 * (b + 1) for b in range(24)], [1 + b % 3 for b in range(24)]),   # 24 workers: six column groups
+    # items of 1024 rows walked in pieces of 256: prefixes on and around both boundaries, tails that reach into a second item
+    ("dense_8x4096", [255, 256, 1023, 1024, 1025, 2047, 2048, 2049, 2304, 3000], [1, 2, 1030, 1, 3, 1024, 1, 2, 1025, 5]),
+    ("moe_16x8192", [1023, 1025, 2300] + [2560] * 10, [1, 260, 3] + [2] * 10),            # head_dim 64: 104 columns, seven groups
+    ("dense_8x4096", [1500] * 30, [1 + b % 2 for b in range(30)]),                          # 120 columns: two batches of column groups
 ])
 def test_prefix_decode_attention_kernel(wl, prefix, tail):
     layer = WORKLOADS[wl].layer
