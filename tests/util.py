@@ -38,7 +38,9 @@ def rms_err(got, ref):
 
 # bf16 storage mode, whole-layer outputs against the fp64 checker (the derivation is in
 # tests/test_gpu_layer_bf16.py): per output vector, per element (floored at the tensor's
-# rms), and pooled rms per kind of output.
+# rms), and pooled rms per kind of output.  The pooled bound sits between what storage rounding alone
+# gives (3.4e-3, tests/test_bf16_floor.py) plus the kernels' own roundings (measured 4.2e-3 .. 5.2e-3) and
+# what a dropped term or a bias would produce (1e-2 and up).
 BF16_VEC_TOL = 2e-2
 BF16_ELEM_TOL = 3e-2
 BF16_RMS_TOL = 6e-3
