@@ -50,8 +50,10 @@ struct SkinnyNormIn {
     float* ssq_parts = nullptr;
 };
 
-template <int MT, bool GROUPED, int WAVES>
-__global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const bf16* __restrict__ X, const bf16* __restrict__ W,
+// RING < SKINNY_STEPS: only the first RING loads of the slice go out at once, the rest one per k-step as the
+// registers come free (half the registers per wavefront, twice the wavefronts per CU for the same bytes in flight).
+template <int MT, bool GROUPED, int WAVES, int RING = SKINNY_STEPS>
+__global__ __launch_bounds__(WAVES * 64, RING < SKINNY_STEPS ? 2 : 1) void gemm_skinny_kernel(const bf16* __restrict__ X, const bf16* __restrict__ W,
                                                           float* __restrict__ P, int M, int N, int K, const SkinnyGroup grp,
                                                           const SkinnyNormIn nin) {
     constexpr int LDX = SKINNY_KSLICE + 8;
@@ -81,11 +83,11 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const bf16* __r
     const bool active = n0 < N;
 
     // the weight stream goes first: everything below overlaps with it
-    bf16x8 a[SKINNY_STEPS];
+    bf16x8 a[RING];
+    const bf16* wp = W + (size_t)(min(n0, N - 16) + r) * K + k0 + c * 8;
     if (active) {
-        const bf16* wp = W + (size_t)(n0 + r) * K + k0 + c * 8;
 #pragma unroll
-        for (int s = 0; s < SKINNY_STEPS; ++s)
+        for (int s = 0; s < RING; ++s)
             if (s < nsteps) a[s] = *reinterpret_cast<const bf16x8*>(wp + s * 32);
     }
 
@@ -139,8 +141,10 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const bf16* __r
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 const bf16x8 b = *reinterpret_cast<const bf16x8*>(xs + (mt * 16 + r) * LDX + s * 32 + c * 8);
-                acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[s], b, acc[mt], 0, 0, 0);
+                acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[s % RING], b, acc[mt], 0, 0, 0);
             }
+            if (RING < SKINNY_STEPS && s + RING < SKINNY_STEPS && s + RING < nsteps)
+                a[s % RING] = *reinterpret_cast<const bf16x8*>(wp + (s + RING) * 32);
         }
     }
     // acc[mt][e]: activation row m = mt*16 + r, weight row n = n0 + 4c + e
@@ -298,18 +302,18 @@ int launch_gemm_skinny_swiglu(compact_ctx* ctx, const bf16* X, const bf16* W, bf
     }
 }
 
-template <int MT, int WAVES>
+template <int MT, int WAVES, int RING = SKINNY_STEPS>
 static int launch_skinny_cfg(compact_ctx* ctx, const bf16* A, const bf16* B, float* partials, int M, int N, int K, int ks,
                              const SkinnyNormIn& nin, hipStream_t s) {
     const size_t smem = (size_t)MT * 16 * (SKINNY_KSLICE + 8) * sizeof(bf16);
     static bool attr = false;
     if (!attr && smem > 48 * 1024) {
-        HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel<MT, false, WAVES>),
+        HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel<MT, false, WAVES, RING>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
         attr = true;
     }
     dim3 grid(ks, (N + 16 * WAVES - 1) / (16 * WAVES));
-    gemm_skinny_kernel<MT, false, WAVES><<<grid, WAVES * 64, smem, s>>>(A, B, partials, M, N, K, SkinnyGroup{}, nin);
+    gemm_skinny_kernel<MT, false, WAVES, RING><<<grid, WAVES * 64, smem, s>>>(A, B, partials, M, N, K, SkinnyGroup{}, nin);
     LAUNCH_CHECK(ctx);
     return COMPACT_OK;
 }
@@ -332,11 +336,19 @@ int launch_gemm_skinny(compact_ctx* ctx, const bf16* A, const bf16* B, float* pa
         nin.g = norm_g;
         nin.ssq_parts = norm_ssq_parts;
     }
+    // 49 .. 64 rows: two workgroups of 8 wavefronts fit a CU (the staged slice is 66 KB); a grid beyond what the
+    // chip holds at once (the down projection of the 8B-shaped layer: 28 slices x 32 column groups) goes to
+    // workgroups of 16 wavefronts with 6 of the 16 loads up front instead: again two per CU, all resident in one
+    // round, half the activation staging (39.9 -> 34.9 us; at 32 rows the same change cost 2 us and is not made)
+    int n_cus = 0;
+    if (int rc = device_cu_count(ctx, &n_cus)) return rc;
+    const bool fat = (int64_t)ks * ((N + 127) / 128) > 2 * (int64_t)n_cus;
     switch ((M + 15) / 16) {
         case 1: return launch_skinny_cfg<1, 4>(ctx, A, B, partials, M, N, K, ks, nin, s);
         case 2: return launch_skinny_cfg<2, 8>(ctx, A, B, partials, M, N, K, ks, nin, s);
         case 3: return launch_skinny_cfg<3, 8>(ctx, A, B, partials, M, N, K, ks, nin, s);
-        default: return launch_skinny_cfg<4, 8>(ctx, A, B, partials, M, N, K, ks, nin, s);
+        default: return fat ? launch_skinny_cfg<4, 16, 6>(ctx, A, B, partials, M, N, K, ks, nin, s)
+                            : launch_skinny_cfg<4, 8>(ctx, A, B, partials, M, N, K, ks, nin, s);
     }
 }
 
