@@ -40,9 +40,10 @@
  *    depend on which other blocks share the call nor on its place among
  *    them: no work split is chosen from the batch, with one exception.  The
  *    decode projections come in one kernel family for at most 16 blocks and
- *    one for 17 .. 64 (a third, the prefill kernels, beyond 64): the caches
- *    and every output are bit-identical within a family; across the two, the
- *    caches still are, the outputs agree to rounding (the down projection
+ *    one for more (beyond 64 blocks the rows of a step go through the second
+ *    family in groups of 33 .. 64, each group streaming the weights again): the
+ *    caches and every output are bit-identical within a family; across the two,
+ *    the caches still are, the outputs agree to rounding (the down projection
  *    adds over K in another order).
  */
 #ifndef COMPACT_H

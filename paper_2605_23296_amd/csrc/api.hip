@@ -624,14 +624,37 @@ static void step_cache_commit(compact_ctx* ctx, StepCache& sc, std::vector<int64
     sc.valid = true;
 }
 
-// one decode step for all blocks; plan.meta.len = cached tokens before step 0.
-static int decode_impl(compact_ctx* ctx, const compact_weights* w, int n_blocks, int step, const void* x,
-                       compact_kv* kv, void* y, const compact_route_out* route, const DecodeBufs& b,
-                       const Plan& plan, hipStream_t s, const PrefixArgs* pfx = nullptr) {
+// Parts of one decode step: the projections before the attention (rows r0 .. r0 + n_rows - 1 of the step), the
+// attention (always all n_total blocks), the projections and the feed-forward half after it (rows again).
+enum { DECODE_FRONT = 1, DECODE_ATTN = 2, DECODE_BACK = 4, DECODE_ALL = 7 };
+// most rows the decode-step projection kernels take at once (bf16 storage)
+constexpr int DECODE_MAX_ROWS = 64;
+
+// plan.meta.len = cached tokens before step 0.  Only the query and attention-output rows travel between the parts; every
+// other buffer of `b_all` is scratch that a later group of rows may overwrite (the launches are ordered on the stream).
+static int decode_part(compact_ctx* ctx, const compact_weights* w, int n_total, int r0, int n_rows, int part, int step,
+                       const void* x_all, compact_kv* kv, void* y_all, const compact_route_out* route_all,
+                       const DecodeBufs& b_all, const Plan& plan, hipStream_t s, const PrefixArgs* pfx) {
     const compact_layer_cfg& c = ctx->cfg;
-    const int N = n_blocks;
+    const int N = n_rows;
     const int Dq = c.n_q_heads * c.head_dim, Dtot = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
+    const size_t es = c.dtype == COMPACT_BF16 ? 2 : 4;
+    const void* x = (const char*)x_all + (size_t)r0 * c.d_model * es;
+    void* y = (char*)y_all + (size_t)r0 * c.d_model * es;
+    DecodeBufs b = b_all;
+    b.q = (char*)b_all.q + (size_t)r0 * Dq * es;
+    b.o = (char*)b_all.o + (size_t)r0 * Dq * es;
+    const BlockMeta* meta = plan.d_meta + r0;
+    compact_route_out route_rows{};
+    const compact_route_out* route = nullptr;
+    if (route_all) {
+        route_rows = *route_all;
+        if (route_rows.d_expert_idx) route_rows.d_expert_idx += (size_t)r0 * c.top_k;
+        if (route_rows.d_gate) route_rows.d_gate += (size_t)r0 * c.top_k;
+        route = &route_rows;
+    }
     int ks = 1;
+    if (part & DECODE_FRONT) {
     // RMSNorm + QKV projection.  bf16 storage: the projection stages bf16(x * g) itself and leaves the row sums of squares, the
     // epilogue multiplies by 1 / rms before the rotation.
     if (c.dtype == COMPACT_BF16 && skinny_norm_in_supported(N, Dtot, c.d_model)) {
@@ -646,21 +669,23 @@ static int decode_impl(compact_ctx* ctx, const compact_weights* w, int n_blocks,
         rq.nparts = ks;
         rq.inv_d = 1.0f / (float)c.d_model;
         rq.eps = c.rms_eps;
-        TRY(launch_decode_qkv_epilogue(ctx, plan.d_meta, N, step, b.partials, ks, b.q, kv->d_k, kv->d_v, s, &rq));
+        TRY(launch_decode_qkv_epilogue(ctx, meta, N, step, b.partials, ks, b.q, kv->d_k, kv->d_v, s, &rq));
     } else {
         TRY(launch_rmsnorm(ctx, x, false, w->g_attn, b.n, N, s));
         TRY(gemm_partials(ctx, b.n, w->w_qkv, b.partials, N, Dtot, c.d_model, &ks, s));
-        TRY(launch_decode_qkv_epilogue(ctx, plan.d_meta, N, step, b.partials, ks, b.q, kv->d_k, kv->d_v, s));
+        TRY(launch_decode_qkv_epilogue(ctx, meta, N, step, b.partials, ks, b.q, kv->d_k, kv->d_v, s));
     }
-    if (pfx) {
+    }
+    if ((part & DECODE_ATTN) && pfx) {
         TRY(launch_attn_decode_prefix_bf16(ctx, plan.d_meta, pfx->shared, (const PrefixItem*)(plan.d_extra + pfx->off_items),
                                            (int)pfx->items.size(), (const int32_t*)(plan.d_extra + pfx->off_wl_off),
-                                           (const int32_t*)(plan.d_extra + pfx->off_wl), pfx->max_list, N, step,
-                                           (const bf16*)b.q, (const bf16*)pfx->d_k, (const bf16*)pfx->d_v, (const bf16*)kv->d_k,
-                                           (const bf16*)kv->d_v, pfx->records, pfx->total_recs, (bf16*)b.o, s));
-    } else {
-        TRY(run_attn_decode(ctx, plan, N, step, b.q, kv, b.attn_partials, b.o, s));
+                                           (const int32_t*)(plan.d_extra + pfx->off_wl), pfx->max_list, n_total, step,
+                                           (const bf16*)b_all.q, (const bf16*)pfx->d_k, (const bf16*)pfx->d_v, (const bf16*)kv->d_k,
+                                           (const bf16*)kv->d_v, pfx->records, pfx->total_recs, (bf16*)b_all.o, s));
+    } else if (part & DECODE_ATTN) {
+        TRY(run_attn_decode(ctx, plan, n_total, step, b_all.q, kv, b_all.attn_partials, b_all.o, s));
     }
+    if (!(part & DECODE_BACK)) return COMPACT_OK;
     // O projection + residual, and the RMSNorm that feeds the FFN.  bf16 storage with
     // few rows: one whole-K kernel leaves h, the un-normalised FFN input h * g and the
     // row sums of squares; whoever consumes the input applies 1/rms.
@@ -768,6 +793,26 @@ static int decode_impl(compact_ctx* ctx, const compact_weights* w, int n_blocks,
             TRY(moe_ffn_rows(ctx, w, b.m, b.h, true, idx, gate, N, b.act, b.plan, b.expert_out, y, s));
         }
     }
+    return COMPACT_OK;
+}
+
+// one decode step for all blocks.  bf16 storage with more than DECODE_MAX_ROWS blocks: the projections run group of
+// rows after group of rows (each group streams the weights once more), the attention once for all blocks; a block's
+// bits are those of the kernels for 17 .. 64 rows whatever its group.
+static int decode_impl(compact_ctx* ctx, const compact_weights* w, int n_blocks, int step, const void* x,
+                       compact_kv* kv, void* y, const compact_route_out* route, const DecodeBufs& b,
+                       const Plan& plan, hipStream_t s, const PrefixArgs* pfx = nullptr) {
+    if (ctx->cfg.dtype != COMPACT_BF16 || n_blocks <= DECODE_MAX_ROWS)
+        return decode_part(ctx, w, n_blocks, 0, n_blocks, DECODE_ALL, step, x, kv, y, route, b, plan, s, pfx);
+    // as few groups as possible, of (nearly) equal size: at least 33 rows each, so that every row goes through the
+    // kernel family for 17 .. 64 rows
+    const int n_groups = (n_blocks + DECODE_MAX_ROWS - 1) / DECODE_MAX_ROWS;
+    const int per = (n_blocks + n_groups - 1) / n_groups;
+    for (int r0 = 0; r0 < n_blocks; r0 += per)
+        TRY(decode_part(ctx, w, n_blocks, r0, std::min(per, n_blocks - r0), DECODE_FRONT, step, x, kv, y, route, b, plan, s, pfx));
+    TRY(decode_part(ctx, w, n_blocks, 0, n_blocks, DECODE_ATTN, step, x, kv, y, route, b, plan, s, pfx));
+    for (int r0 = 0; r0 < n_blocks; r0 += per)
+        TRY(decode_part(ctx, w, n_blocks, r0, std::min(per, n_blocks - r0), DECODE_BACK, step, x, kv, y, route, b, plan, s, pfx));
     return COMPACT_OK;
 }
 

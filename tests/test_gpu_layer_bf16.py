@@ -229,6 +229,25 @@ def test_small_moe_layer_17_to_64_blocks(n_blocks):
     assert most > 16 or n_blocks < 40, most      # some expert needs more than one group of 16 rows
 
 
+def test_more_than_64_blocks_in_a_decode_step_dense_and_routed():
+    """Beyond 64 decode rows the projections of a step run group of rows after group of rows (70 blocks: two groups
+    of 35), the attention once for all blocks: every row of every step against the checker, dense and routed."""
+    lens = [(7 * b) % 31 + 1 for b in range(70)]
+    inp = make_inputs(WORKLOADS["dense_8x4096"], block_lens=lens, decode_steps=2, gain_jitter=True)
+    full = check_dense(inp, sampled=False)
+    # the rows of a step go through the kernels for 17 .. 64 rows in two groups of 35: a block's bits are those it
+    # has in any batch of 17 .. 64 blocks, whichever group it falls into and wherever it stands
+    probe = [0, 34, 35, 69]
+    order = [40, 41] + probe + list(range(1, 15))
+    g = H.gpu_forward(sub_batch(inp, order))
+    for b in probe:
+        i = order.index(b)
+        assert np.array_equal(g["y_decode"][:, i], full["y_decode"][:, b]), b
+        assert np.array_equal(g["K"][i], full["K"][b]) and np.array_equal(g["V"][i], full["V"][b])
+    wl = Workload("small_moe", copy.deepcopy(SMALL_MOE), lens, 70, 2)
+    check_moe(make_inputs(wl), margin_rel=2e-2)
+
+
 def test_moe_120b_shape_24_blocks_every_expert_takes_every_row():
     """The 120B-shaped experts (d 2880, F 2880), 24 blocks, eight experts and top-8: every expert receives all 24 rows
     of a step, i.e. two groups of 16 rows (the second half full) per expert in the streaming kernels."""
