@@ -160,6 +160,46 @@ def test_dense_decode_with_17_to_64_blocks_at_the_smallest_shapes(n_blocks):
     check_dense(inp, sampled=False)
 
 
+def test_decode_steps_from_empty_caches():
+    """Blocks whose caches hold nothing yet (h_len = 0) beside a block that holds rows: the first decode step of an
+    empty block attends its own row only, and S steps from nothing are the causal prefill of the S step inputs."""
+    from paper_2605_23296_amd import binding as B
+    from paper_2605_23296_amd.workloads import to_numpy_f64
+    layer = LayerConfig(d_model=512, n_q_heads=4, n_kv_heads=2, head_dim=128, ffn_dim=1024, rope_theta=500000.0, dtype="bf16")
+    inp = make_inputs(Workload("from_nothing", layer, [1, 1, 7], 3, 6), gain_jitter=True)
+    N, S, d = 3, 6, layer.d_model
+    lay = H.gpu_layer(inp)
+    dt = torch.bfloat16
+    kv = B.KVCache(layer, [S + 2, S + 2, 7 + S], "cuda", dt)
+    lay.ensure_workspace(16, N, 7 + S, "cuda")
+    # block 2 is prefilled alone (seven rows); blocks 0 and 1 stay empty
+    one = B.KVCache(layer, [7 + S], "cuda", dt)
+    x2 = inp.x_prefill[2:9].to("cuda").contiguous()
+    y2 = torch.empty(7, d, dtype=dt, device="cuda")
+    lay.compact_prefill([0, 7], x2, one, y2)
+    kv.h_len[0] = kv.h_len[1] = 0
+    kv.h_len[2] = 7
+    kv.block_k(2).copy_(one.block_k(0))
+    kv.block_v(2).copy_(one.block_v(0))
+    y_dec = torch.empty(S, N, d, dtype=dt, device="cuda")
+    for s in range(S):
+        lay.compact_decode_step(inp.x_decode[s].to("cuda").contiguous(), kv, y_dec[s])
+    torch.cuda.synchronize()
+    assert list(kv.lens()) == [S, S, 7 + S]
+    ref = H.oracle_layer(inp)
+    xd = to_numpy_f64(inp.x_decode)
+    log = ErrLog()
+    for b in (0, 1):
+        r = ref.prefill_block(xd[:, b])          # S steps from nothing = the prefill of the S inputs
+        log.cmp("y_dec%d" % b, to_numpy_f64(y_dec[:, b]), r["y"])
+        log.cmp("K%d" % b, to_numpy_f64(kv.block_k(b)), r["K"])
+        log.cmp("V%d" % b, to_numpy_f64(kv.block_v(b)), r["V"])
+    r = ref.prefill_block(np.concatenate([to_numpy_f64(inp.x_prefill[2:9]), xd[:, 2]], axis=0))
+    log.cmp("y_dec2", to_numpy_f64(y_dec[:, 2]), r["y"][7:])
+    log.cmp("K2", to_numpy_f64(kv.block_k(2)), r["K"])
+    log.check("decode from empty caches")
+
+
 def test_run_to_run_determinism():
     inp = make_inputs(WORKLOADS["dense_8x4096"], block_lens=[257, 300], decode_steps=2)
     a = H.gpu_forward(inp)
