@@ -86,3 +86,31 @@ def test_batched_equals_one_block_at_a_time_bitwise():
         assert np.array_equal(g["y_prefill"], full["y_prefill"][inp.cu_seqlens[b]:inp.cu_seqlens[b + 1]])
         assert np.array_equal(g["y_decode"][:, 0], full["y_decode"][:, b])
         assert np.array_equal(g["K"][0], full["K"][b]) and np.array_equal(g["V"][0], full["V"][b])
+
+
+def test_forty_thousand_tiny_blocks_grow_the_metadata_buffer():
+    """40 000 blocks of one to three tokens: the block table alone (32 bytes a block) outgrows the context's first
+    metadata buffer, which is replaced on the way; a small batch before and after must give the same bits, and
+    sampled blocks of the big batch match the checker (prefill rows, caches and one decode step)."""
+    wl = WORKLOADS["tiny_fp32"]
+    small = make_inputs(wl, block_lens=[5, 1, 9], decode_steps=1)
+    n = 40000
+    lens = [1 + (b * 7) % 3 for b in range(n)]
+    big = make_inputs(wl, block_lens=lens, decode_steps=1)
+    lay = H.gpu_layer(big)                      # same weights for all three calls (same seed, same layer)
+    before = H.gpu_forward(small, lay=lay)
+    g = H.gpu_forward(big, lay=lay)
+    after = H.gpu_forward(small, lay=lay)
+    for k in ("y_prefill", "y_decode", "y_last"):
+        assert np.array_equal(before[k], after[k]), k
+    ref = H.oracle_layer(big)
+    cu = big.cu_seqlens
+    xp, xd = to_numpy_f64(big.x_prefill), to_numpy_f64(big.x_decode)
+    worst = 0.0
+    for b in [0, 1, 2, 4095, 4096, 20000, 32767, 32768, n - 2, n - 1]:
+        r = ref.prefill_block(xp[cu[b]:cu[b + 1]])
+        worst = max(worst, rel_err(g["y_prefill"][cu[b]:cu[b + 1]], r["y"]))
+        d = ref.decode_block(xd[0, b], r["K"], r["V"])
+        worst = max(worst, rel_err(g["y_decode"][0, b], d["y"]), rel_err(g["K"][b], d["K"]), rel_err(g["V"][b], d["V"]))
+        assert g["lens"][b] == lens[b] + 1
+    assert worst < TOL, worst
