@@ -37,7 +37,8 @@ def fill_cache(kv, b, K, V):
     # items of 1024 rows walked in pieces of 256: prefixes on and around both boundaries, tails that reach into a second item
     ("dense_8x4096", [255, 256, 1023, 1024, 1025, 2047, 2048, 2049, 2304, 3000], [1, 2, 1030, 1, 3, 1024, 1, 2, 1025, 5]),
     ("moe_16x8192", [1023, 1025, 2300] + [2560] * 10, [1, 260, 3] + [2] * 10),            # head_dim 64: 104 columns, seven groups
-    ("dense_8x4096", [1500] * 30, [1 + b % 2 for b in range(30)]),                          # 120 columns: two batches of column groups
+    ("dense_8x4096", [1500] * 30, [1 + b % 2 for b in range(30)]),                          # 120 columns: eight column groups
+    ("dense_8x4096", [40 * (b // 2) for b in range(64)], [1 + b % 4 for b in range(64)]),   # 64 workers (the most a call takes): 256 columns
 ])
 def test_prefix_decode_attention_kernel(wl, prefix, tail):
     layer = WORKLOADS[wl].layer
