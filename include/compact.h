@@ -78,7 +78,7 @@ enum { COMPACT_FP32 = 0, COMPACT_BF16 = 1 };
  * Query head h reads KV head h / (n_q_heads / n_kv_heads).
  * Constraints: head_dim in {64, 128}; n_q_heads % n_kv_heads == 0 with a
  * group of at most 16; d_model, ffn_dim multiples of 64; d_model <= 8192; top_k <= 8;
- * n_experts <= 256.                                                        */
+ * n_experts <= 256, a multiple of 8 in bf16 storage.                      */
 typedef struct compact_layer_cfg {
     int32_t d_model;
     int32_t n_q_heads;

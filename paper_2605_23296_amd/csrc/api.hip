@@ -104,6 +104,10 @@ static int validate_cfg(const compact_layer_cfg* c, std::string& why) {
         why = "top_k must be in 1..min(8, n_experts)";
         return COMPACT_ESHAPE;
     }
+    if (c->n_experts % 8 != 0 && c->dtype == COMPACT_BF16) {
+        why = "bf16 storage needs n_experts to be a multiple of 8 (the router logits come out of the MFMA GEMM in 8-column pieces)";
+        return COMPACT_ESHAPE;
+    }
     if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) {
         why = "rms_eps must be >= 0 and rope_theta > 0";
         return COMPACT_EINVAL;

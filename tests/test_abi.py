@@ -37,6 +37,7 @@ def test_create_validates_cfg():
         (dict(head_dim=48), 2), (dict(n_kv_heads=3), 2), (dict(d_model=100), 2),
         (dict(n_experts=4, top_k=0), 2), (dict(n_experts=4, top_k=5), 2), (dict(d_model=0), 1),
         (dict(dtype="fp32", rope_theta=-1.0), 1),
+        (dict(dtype="bf16", n_experts=12, top_k=2), 2),     # bf16 storage: experts in multiples of 8
     ]
     for kw, code in bad:
         d = good.as_dict()

@@ -200,6 +200,34 @@ def test_decode_steps_from_empty_caches():
     log.check("decode from empty caches")
 
 
+@pytest.mark.parametrize("kw", [
+    dict(n_q_heads=6, n_kv_heads=2, head_dim=64),                 # odd GQA group (3), head_dim 64
+    dict(n_q_heads=3, n_kv_heads=1, head_dim=128),                # odd group at head_dim 128: the four-wavefront prefill kernel
+    dict(n_q_heads=16, n_kv_heads=1, head_dim=64),                # the widest group a layer may have (16 = all MFMA columns)
+    dict(n_q_heads=4, n_kv_heads=4, head_dim=128),                # no grouping at all
+    dict(n_experts=6, top_k=2),                                   # expert count off every tile size
+    dict(n_experts=12, top_k=3),
+    dict(n_experts=8, top_k=1),
+    dict(n_experts=256, top_k=8, ffn_dim=64),                     # the most experts and the widest choice a layer may have
+], ids=lambda kw: "-".join("%s%s" % (k[:4], v) for k, v in kw.items()))
+def test_unusual_layer_shapes(kw):
+    """Layer shapes the configuration check accepts but no named workload has: every one must run (or be refused at
+    creation, never later) and match the checker on ragged blocks, prefill and decode."""
+    base = dict(d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=64, ffn_dim=256, rope_theta=500000.0, dtype="bf16")
+    base.update(kw)
+    layer = LayerConfig(**base)
+    if layer.n_experts % 8 != 0:
+        from paper_2605_23296_amd import binding as B
+        with pytest.raises(B.CompactError, match="multiple of 8"):
+            B.Layer(layer, None)
+        return
+    inp = make_inputs(Workload("odd_shape", layer, [70, 3, 129], 3, 3), gain_jitter=True)
+    if layer.n_experts > 0:
+        check_moe(inp, margin_rel=2e-2)
+    else:
+        check_dense(inp, sampled=False)
+
+
 def test_run_to_run_determinism():
     inp = make_inputs(WORKLOADS["dense_8x4096"], block_lens=[257, 300], decode_steps=2)
     a = H.gpu_forward(inp)
