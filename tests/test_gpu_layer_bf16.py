@@ -39,7 +39,7 @@ def sample_rows(L, rng, n=12):
     return rows
 
 
-def check_dense(inp, steps=None, pos_offset=None, sampled=True):
+def check_dense(inp, steps=None, pos_offset=None, sampled=True, noise=1.0):
     rng = np.random.default_rng(5)
     S = inp.x_decode.shape[0]
     g = H.gpu_forward(inp, pos_offset=pos_offset)
@@ -49,7 +49,8 @@ def check_dense(inp, steps=None, pos_offset=None, sampled=True):
     from paper_2605_23296_amd.workloads import to_numpy_f64
     pre, yd, Ks, Vs, _ = lay.forward_sampled(to_numpy_f64(inp.x_prefill), inp.cu_seqlens, to_numpy_f64(inp.x_decode),
                                              rows, steps, pos_offset)
-    log = ErrLog()
+    from tests.util import BF16_VEC_TOL, BF16_ELEM_TOL, BF16_RMS_TOL
+    log = ErrLog(BF16_VEC_TOL, BF16_ELEM_TOL * noise, BF16_RMS_TOL * noise)
     cmp = log.cmp
     for b, L in enumerate(inp.block_lens):
         cmp("y_pre%d" % b, g["y_prefill"][inp.cu_seqlens[b]:inp.cu_seqlens[b + 1]][rows[b]], pre[b]["y"])
@@ -209,23 +210,34 @@ def test_decode_steps_from_empty_caches():
     dict(n_experts=12, top_k=3),
     dict(n_experts=8, top_k=1),
     dict(n_experts=256, top_k=8, ffn_dim=64),                     # the most experts and the widest choice a layer may have
+    dict(d_model=64, n_q_heads=1, n_kv_heads=1, head_dim=64, ffn_dim=64),      # the smallest layer the check accepts
+    dict(d_model=8192, n_q_heads=64, n_kv_heads=8, head_dim=128, ffn_dim=128),  # the widest model dimension, 3 decode rows
+    dict(d_model=8192, n_q_heads=64, n_kv_heads=8, head_dim=128, ffn_dim=128, blocks=12),   # ... and 12
+    dict(d_model=2112, n_q_heads=6, n_kv_heads=2, head_dim=128, ffn_dim=1344),  # widths that are multiples of 64 and of nothing larger
+    dict(d_model=2112, n_q_heads=6, n_kv_heads=2, head_dim=128, ffn_dim=1344, blocks=20),
 ], ids=lambda kw: "-".join("%s%s" % (k[:4], v) for k, v in kw.items()))
 def test_unusual_layer_shapes(kw):
     """Layer shapes the configuration check accepts but no named workload has: every one must run (or be refused at
     creation, never later) and match the checker on ragged blocks, prefill and decode."""
     base = dict(d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=64, ffn_dim=256, rope_theta=500000.0, dtype="bf16")
     base.update(kw)
+    n_blocks = base.pop("blocks", 3)
     layer = LayerConfig(**base)
     if layer.n_experts % 8 != 0:
         from paper_2605_23296_amd import binding as B
         with pytest.raises(B.CompactError, match="multiple of 8"):
             B.Layer(layer, None)
         return
-    inp = make_inputs(Workload("odd_shape", layer, [70, 3, 129], 3, 3), gain_jitter=True)
+    lens = [70, 3, 129] + [(5 * b) % 17 + 1 for b in range(n_blocks - 3)]
+    inp = make_inputs(Workload("odd_shape", layer, lens, n_blocks, 3), gain_jitter=True)
     if layer.n_experts > 0:
         check_moe(inp, margin_rel=2e-2)
     else:
-        check_dense(inp, sampled=False)
+        # N(0, 0.02) weights amplify a branch by 0.02^2 * d per projection pair: at d_model 8192 the attention branch
+        # (3.3 x) carries nine tenths of the output, and its storage roundings (normalised rows, q/k/v, probabilities,
+        # attention output: about 0.3 % each) put the noise floor at 0.65 % of rms(y) instead of the 0.4 % of the
+        # named shapes, where the feed-forward branch dominates: element and rms bounds 1.5 x
+        check_dense(inp, sampled=False, noise=1.5 if layer.d_model == 8192 else 1.0)
 
 
 def test_run_to_run_determinism():
