@@ -240,6 +240,25 @@ def test_unusual_layer_shapes(kw):
         check_dense(inp, sampled=False, noise=1.5 if layer.d_model == 8192 else 1.0)
 
 
+def test_a_side_stream_gives_the_bits_of_the_default_stream():
+    """Every call enqueues on the stream it is given: a whole pass on a stream of the caller's own (ordered after the
+    inputs by an event, as a caller would) gives the bits of the pass on the default stream, dense and routed."""
+    for wl in (Workload("dense_side", LayerConfig(d_model=512, n_q_heads=4, n_kv_heads=2, head_dim=128, ffn_dim=1024,
+                                                    rope_theta=500000.0, dtype="bf16"), [300, 77, 513], 3, 3),
+               Workload("moe_side", copy.deepcopy(SMALL_MOE), [130, 40, 9], 3, 3)):
+        inp = make_inputs(wl, gain_jitter=True)
+        ref = H.gpu_forward(inp)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            got = H.gpu_forward(inp)
+        side.synchronize()
+        for k in ("y_prefill", "y_last", "y_decode"):
+            assert np.array_equal(ref[k], got[k]), (wl.name, k)
+        for b in range(3):
+            assert np.array_equal(ref["K"][b], got["K"][b]) and np.array_equal(ref["V"][b], got["V"][b])
+
+
 def test_run_to_run_determinism():
     inp = make_inputs(WORKLOADS["dense_8x4096"], block_lens=[257, 300], decode_steps=2)
     a = H.gpu_forward(inp)
