@@ -73,6 +73,17 @@ def test_bf16_mixed_schedules_ragged_blocks():
         check(inp, budget, False, ref)
 
 
+def test_bf16_mixed_schedule_with_more_than_64_blocks():
+    """70 short blocks: the steps after the last prefill chunk are decode steps of 70 rows (two groups of 35 through
+    the projection kernels), and a budget of 100 rows mixes up to 70 decode rows with chunk rows before that."""
+    layer = LayerConfig(d_model=512, n_q_heads=4, n_kv_heads=2, head_dim=128, ffn_dim=1024, rope_theta=500000.0)
+    lens = [(7 * b) % 31 + 1 for b in range(70)]
+    inp = make_inputs(Workload("many_blocks", layer, lens, 70, 3), gain_jitter=True)
+    ref = oracle_pass(inp)
+    for budget in (100, 4096):
+        check(inp, budget, False, ref)
+
+
 def test_bf16_mixed_routed_layer_every_row():
     """The mixed call does not report its routing tables, so the checker lists, per row, every
     expert set that is a valid top-k choice when logits closer than the rounding margin may
