@@ -65,7 +65,7 @@ def device_weights(lay0, inp, q4):
 
 
 @pytest.mark.parametrize("d,F,spread,lens", [(256, 320, 0, None), (1216, 1088, 0, None), (1216, 1088, 30, None),
-                                             (256, 320, 0, [7] * 48)])
+                                             (256, 320, 0, [7] * 48), (256, 320, 0, [5] * 70)])
 def test_routed_decode_steps_streaming_4bit_experts(d, F, spread, lens):
     """d = 256: one k-slice of two MFMA groups; d = 1216 / F = 1088: a full 1024-wide slice plus a
     slice of 6 (2) blocks, i.e. a partial group of four.  Empty experts, experts with several rows.
