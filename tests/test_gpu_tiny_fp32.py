@@ -114,3 +114,25 @@ def test_forty_thousand_tiny_blocks_grow_the_metadata_buffer():
         worst = max(worst, rel_err(g["y_decode"][0, b], d["y"]), rel_err(g["K"][b], d["K"]), rel_err(g["V"][b], d["V"]))
         assert g["lens"][b] == lens[b] + 1
     assert worst < TOL, worst
+
+
+@pytest.mark.parametrize("kw", [
+    dict(n_q_heads=6, n_kv_heads=2, head_dim=64), dict(n_q_heads=3, n_kv_heads=1, head_dim=128),
+    dict(n_q_heads=16, n_kv_heads=1, head_dim=64), dict(n_q_heads=4, n_kv_heads=4, head_dim=128),
+    dict(n_experts=6, top_k=2), dict(n_experts=12, top_k=3), dict(n_experts=8, top_k=1),
+    dict(n_experts=256, top_k=8, ffn_dim=64), dict(d_model=64, n_q_heads=1, n_kv_heads=1, head_dim=64, ffn_dim=64),
+    dict(d_model=2112, n_q_heads=6, n_kv_heads=2, head_dim=128, ffn_dim=1344),
+], ids=lambda kw: "-".join("%s%s" % (k[:4], v) for k, v in kw.items()))
+def test_unusual_layer_shapes_fp32(kw):
+    """Layer shapes no named workload has, in fp32 storage at 1e-5 (routed layers: the routing is then decided in
+    fp32 against fp64, and a row whose logits nearly tie is checked with the choice the GPU made)."""
+    from paper_2605_23296_amd.workloads import LayerConfig, Workload
+    base = dict(d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=64, ffn_dim=256, rope_theta=500000.0, dtype="fp32")
+    base.update(kw)
+    layer = LayerConfig(**base)
+    inp = make_inputs(Workload("odd_shape", layer, [70, 3, 129], 3, 3), gain_jitter=True)
+    if layer.n_experts == 0:
+        check_forward(inp)
+        return
+    from tests.test_gpu_layer_bf16 import check_moe
+    check_moe(inp, margin_rel=1e-4, fp32=True)
