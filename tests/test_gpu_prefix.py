@@ -41,7 +41,21 @@ def fill_cache(kv, b, K, V):
     ("dense_8x4096", [40 * (b // 2) for b in range(64)], [1 + b % 4 for b in range(64)]),   # 64 workers (the most a call takes): 256 columns
 ])
 def test_prefix_decode_attention_kernel(wl, prefix, tail):
-    layer = WORKLOADS[wl].layer
+    prefix_kernel_case(WORKLOADS[wl].layer, prefix, tail)
+
+
+@pytest.mark.parametrize("heads", [(4, 4, 128), (3, 1, 128), (16, 1, 64), (6, 2, 64), (1, 1, 64)],
+                         ids=lambda h: "%dq%dkv_x%d" % h)
+def test_prefix_decode_attention_kernel_head_groupings(heads):
+    """No grouping, odd groups, the widest group (16 query heads per KV head) and a single head, with workers
+    whose prefixes end on and off the chunk edges."""
+    from paper_2605_23296_amd.workloads import LayerConfig
+    hq, hkv, hd = heads
+    layer = LayerConfig(d_model=256, n_q_heads=hq, n_kv_heads=hkv, head_dim=hd, ffn_dim=256, rope_theta=500000.0, dtype="bf16")
+    prefix_kernel_case(layer, [0, 255, 256, 257, 600, 600, 1024], [1, 2, 300, 1, 5, 1, 257])
+
+
+def prefix_kernel_case(layer, prefix, tail):
     N, Hq, Hkv, hd = len(prefix), layer.n_q_heads, layer.n_kv_heads, layer.head_dim
     lay = B.Layer(layer, None)
     T = max(prefix)
