@@ -97,7 +97,7 @@ def test_gemm_fp32(M, N, K, epi, res):
 
 
 # ---------------------------------------------------------------- rotary + KV write, prefill attention
-def attention_case(layer, lens, seed, pos_offset=None):
+def attention_case(layer, lens, seed, pos_offset=None, edit=None):
     """qkv rows -> (GPU: rope_kvwrite + attn_prefill) vs (checker: rope + gqa_attention)."""
     dt = tdtype(layer)
     lay = B.Layer(layer, None)
@@ -106,6 +106,8 @@ def attention_case(layer, lens, seed, pos_offset=None):
         cu.append(cu[-1] + L)
     Dq, Dkv, hd = layer.Dq, layer.Dkv, layer.head_dim
     qkv = rnd((cu[-1], Dq + 2 * Dkv), dt, seed)
+    if edit is not None:
+        qkv = edit(qkv, cu)
     qkv_in = to_numpy_f64(qkv)
     kv = B.KVCache(layer, [L + 3 for L in lens], "cuda", dt, pos_offset)
     # poison the slabs: rows past a block's length must never reach a result
@@ -144,6 +146,39 @@ def test_prefill_attention_bf16_hd128_ragged():
     attention_case(DENSE, [1, 63, 64, 65, 127, 128, 129, 300, 641], seed=11, pos_offset=[0, 3, 0, 100, 0, 7, 0, 4000, 9])
 
 
+@pytest.mark.parametrize("pattern", ["growing", "sink"])
+@pytest.mark.parametrize("layer_name", ["dense", "moe"])
+def test_prefill_attention_when_the_scaling_reference_has_to_move(layer_name, pattern):
+    """Scores that keep growing along a block (every new tile of 64 keys outgrows the running reference by 2^8, so
+    the reference moves and the accumulators are rescaled tile after tile) and an attention sink (token 0 outweighs
+    everything after it by 2^60: the reference is set once and never moves).  The structure sits in the rotary pair
+    with the lowest frequency, which positions up to a few thousand leave practically unrotated."""
+    layer = copy.deepcopy(DENSE if layer_name == "dense" else MOE)
+    if layer_name == "moe":
+        layer.n_q_heads, layer.n_kv_heads = 16, 2
+    hd, Hq, Hkv = layer.head_dim, layer.n_q_heads, layer.n_kv_heads
+    Dq, Dkv = Hq * hd, Hkv * hd
+    per_key = 8.0 / 64.0 / (16.0 * 1.4426950408889634 / np.sqrt(hd))   # k value that adds 2^8 per 64 keys at q = 16
+
+    def edit(qkv, cu):
+        q = qkv[:, :Dq].view(-1, Hq, hd)
+        k = qkv[:, Dq:Dq + Dkv].view(-1, Hkv, hd)
+        q[:, :, hd // 2 - 1] = 16.0
+        q[:, :, hd - 1] = 0.0
+        k[:, :, hd - 1] = 0.0
+        for b in range(len(cu) - 1):
+            j = torch.arange(cu[b + 1] - cu[b], device=qkv.device, dtype=torch.float32)
+            if pattern == "growing":
+                val = j * per_key
+            else:
+                val = torch.zeros_like(j)
+                val[0] = 60.0 * 64.0 / 8.0 * per_key
+            k[cu[b]:cu[b + 1], :, hd // 2 - 1] = val.to(qkv.dtype)[:, None]
+        return qkv
+
+    attention_case(layer, [1, 64, 65, 300, 777], seed=17, edit=edit)
+
+
 def test_prefill_attention_bf16_hd64_group_of_8():
     small = copy.deepcopy(MOE)
     small.n_q_heads, small.n_kv_heads = 16, 2
@@ -175,7 +210,7 @@ def test_prefill_attention_fp32():
 
 
 # ---------------------------------------------------------------- decode attention
-def decode_case(layer, lens, seed):
+def decode_case(layer, lens, seed, grow=None):
     dt = tdtype(layer)
     lay = B.Layer(layer, None)
     N, Hq, Hkv, hd = len(lens), layer.n_q_heads, layer.n_kv_heads, layer.head_dim
@@ -186,6 +221,8 @@ def decode_case(layer, lens, seed):
     for b, L in enumerate(lens):
         k = rnd((L, Hkv, hd), dt, seed + 10 * b)
         v = rnd((L, Hkv, hd), dt, seed + 10 * b + 1)
+        if grow is not None:   # scores that grow (or fall) along the cache: k[j][0] = grow * j against q[0] = 16
+            k[:, :, 0] = (torch.arange(L, device=k.device, dtype=torch.float32) * grow).to(dt)[:, None]
         cap = kv.caps[b]
         kslab = kv.k[kv.offs[b]:kv.offs[b] + cap * Hkv * hd].view(Hkv, cap, hd)
         vslab = kv.v[kv.offs[b]:kv.offs[b] + cap * Hkv * hd].view(Hkv, hd, cap)
@@ -195,6 +232,8 @@ def decode_case(layer, lens, seed):
         Ks.append(to_numpy_f64(k))
         Vs.append(to_numpy_f64(v))
     q = rnd((N, Hq * hd), dt, seed + 5)
+    if grow is not None:
+        q.view(N, Hq, hd)[:, :, 0] = 16.0
     o = torch.empty_like(q)
     lay.ws = torch.empty(lay.workspace_bytes(0, N, max(lens)), dtype=torch.uint8, device="cuda")
     lay.compact_attn_decode(q, kv, o)
@@ -250,6 +289,15 @@ def test_decode_attention_many_ragged_blocks_repeats_bit_for_bit(layer_name):
         ref = O.gqa_attention(qn[b:b + 1], to_numpy_f64(kv.block_k(b)), to_numpy_f64(kv.block_v(b)),
                               visible=np.array([lens[b]])).reshape(-1)
         assert rms_err(to_numpy_f64(outs[0][b]), ref) < 6e-3 and rel_err(to_numpy_f64(outs[0][b]), ref) < 3e-2
+
+
+@pytest.mark.parametrize("sign", [1.0, -1.0])
+def test_decode_attention_scores_that_grow_or_fall_along_the_cache(sign):
+    """2^8 more (or less) per 64 cached rows: the running maximum moves at every step of the walk through an item,
+    and the chunks' records differ by hundreds of binary orders when they are merged."""
+    for layer in (DENSE, MOE):
+        per_key = 8.0 / 64.0 / (16.0 * 1.4426950408889634 / np.sqrt(layer.head_dim))
+        decode_case(layer, [1, 100, 129, 256, 257, 700, 2049], seed=41, grow=sign * per_key)
 
 
 def test_decode_attention_fp32():
