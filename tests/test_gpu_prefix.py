@@ -55,7 +55,16 @@ def test_prefix_decode_attention_kernel_head_groupings(heads):
     prefix_kernel_case(layer, [0, 255, 256, 257, 600, 600, 1024], [1, 2, 300, 1, 5, 1, 257])
 
 
-def prefix_kernel_case(layer, prefix, tail):
+@pytest.mark.parametrize("sign", [1.0, -1.0])
+def test_prefix_decode_attention_scores_that_grow_or_fall_along_the_history(sign):
+    """2^8 more (or less) per 64 shared rows: the records of a worker's chunks differ by hundreds of binary orders
+    when they are merged, and the private tails (plain random keys) drown or dominate."""
+    layer = WORKLOADS["dense_8x4096"].layer
+    per_key = 8.0 / 64.0 / (16.0 * 1.4426950408889634 / np.sqrt(layer.head_dim))
+    prefix_kernel_case(layer, [0, 100, 256, 257, 700, 1500, 1500], [3, 1, 2, 300, 1, 5, 1], grow=sign * per_key)
+
+
+def prefix_kernel_case(layer, prefix, tail, grow=None):
     N, Hq, Hkv, hd = len(prefix), layer.n_q_heads, layer.n_kv_heads, layer.head_dim
     lay = B.Layer(layer, None)
     T = max(prefix)
@@ -65,12 +74,16 @@ def prefix_kernel_case(layer, prefix, tail):
         c.k.fill_(float("nan"))
         c.v.fill_(float("nan"))
     Kp, Vp = rnd((T, Hkv, hd), 1), rnd((T, Hkv, hd), 2)
+    if grow is not None:   # scores that grow along the history: k[j][0] = grow * j against q[0] = 16
+        Kp[:, :, 0] = (torch.arange(T, device=Kp.device, dtype=torch.float32) * grow).to(Kp.dtype)[:, None]
     fill_cache(shared, 0, Kp, Vp)
     Kt = [rnd((t, Hkv, hd), 10 + b) for b, t in enumerate(tail)]
     Vt = [rnd((t, Hkv, hd), 30 + b) for b, t in enumerate(tail)]
     for b in range(N):
         fill_cache(tails, b, Kt[b], Vt[b])
     q = rnd((N, Hq * hd), 3)
+    if grow is not None:
+        q.view(N, Hq, hd)[:, :, 0] = 16.0
     o = torch.full((N, Hq * hd), float("nan"), dtype=torch.bfloat16, device=DEV)
     lay.ws = torch.empty(lay.prefix_workspace_bytes(N, max(T, 1), max(tail)), dtype=torch.uint8, device=DEV)
     lay.compact_attn_decode_prefix(q, shared, prefix, tails, o)
