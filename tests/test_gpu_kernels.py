@@ -61,6 +61,13 @@ GEMM_SHAPES = [
     (64, 4096, 14336, 0, True),     # weight-streaming path, 64 rows, long K
     (33, 2880, 2880, 0, False),     # weight-streaming path, K with a short last slice
     (65, 512, 128, 0, False),       # just above the weight-streaming limit
+    # several tiles per CU, tails in both directions
+    (4196, 4360, 256, 0, True),     # 17 x 18 tiles of 8 k-tiles, row tail of 100, column tail of 8, residual
+    (4196, 4360, 1088, 0, False),   # 34 k-tiles
+    (4352, 4096, 320, 0, False),    # 10 k-tiles
+    (4352, 4096, 192, 0, False),    # 6 k-tiles
+    (4196, 2184, 512, 1, False),    # SwiGLU epilogue: 17 x 18 tiles of 128 output columns, column tail of 8
+    (8192, 8192, 4096, 0, True),    # 1024 tiles: four per workgroup
 ]
 
 
